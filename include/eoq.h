@@ -1,0 +1,234 @@
+/*
+ * libeoq -- the full-int8 training step of a Fixup residual CNN without BatchNorm
+ * (EOQ framework, arXiv 2105.13890) for AMD MI355X (gfx950).
+ *
+ * C ABI.  No exceptions cross this boundary; every call returns an eoq_status code.
+ *
+ * Conventions shared by all calls
+ *   - Every tensor / slot pointer is a DEVICE pointer owned by the caller, unless a
+ *     parameter is explicitly marked "host".  The library never allocates or frees
+ *     tensor memory and never synchronises: work is enqueued on the context's HIP
+ *     stream.  The descriptor structs themselves are host memory, read during the call.
+ *   - Codes.  Bit width k = 8 everywhere (Section 5.1).  A quantised value is an integer
+ *     code times a power of two.  Forward tensors use fixed grids: int8 activations,
+ *     int8 weights and the int32 scalar codes (bias, multiplier) have value code * 2^-7;
+ *     a convolution accumulator has value acc * 2^-14.  Backward tensors (errors,
+ *     gradients) carry one exponent per tensor, value = code * 2^E, with E held in a
+ *     device-resident int32 "exponent slot" so that no call needs a host round trip.
+ *   - R(.) of Eq.5 rounds to nearest, ties to even.
+ *   - Layouts: activations / errors NHWC int8; weights KRSC int8; accumulators int32 in
+ *     the layout of the tensor they become.  P, Q are the output height / width,
+ *     P = (H + 2*pad - R) / stride + 1.
+ *   - Statistics slots.  "absmax" slots are int32 holding max|v| (combined with atomic
+ *     max), "sum" slots are int64 (combined with atomic add).  The caller zeroes them
+ *     (eoq_fill_zero) before the first producer of a step.
+ *   - Shapes the MFMA kernels accept: K % 16 == 0 (output channels).  Input channels
+ *     C % 16 == 0 run the implicit-GEMM path directly; any other C goes through an
+ *     explicit, zero-padded im2col held in the workspace.
+ *   - Errors that can only be seen on the device (an accumulator leaving int32, an
+ *     exponent gap too large to align) set bits in a device status word, read with
+ *     eoq_status().
+ */
+#ifndef EOQ_H
+#define EOQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum eoq_status_code {
+    EOQ_OK = 0,
+    EOQ_ERR_ARG = 1,       /* null pointer / bad enum / bad size */
+    EOQ_ERR_SHAPE = 2,     /* shape outside what the kernels accept */
+    EOQ_ERR_WORKSPACE = 3, /* workspace missing or too small */
+    EOQ_ERR_RANGE = 4,     /* device status word reported a range violation */
+    EOQ_ERR_HIP = 5        /* a HIP runtime call failed */
+};
+
+enum eoq_flag_bits {
+    EOQ_FLAG_ACC_OVERFLOW = 1, /* a weight-gradient element does not fit int32 */
+    EOQ_FLAG_EXP_GAP = 2,      /* two exponents too far apart to align exactly */
+    EOQ_FLAG_NONFINITE = 4,    /* eoq_quantize met a NaN or an infinity */
+    EOQ_FLAG_SHIFT_RANGE = 8   /* an update would need a left shift beyond 24 bits */
+};
+
+typedef struct eoq_ctx eoq_ctx;
+
+/* Create a context bound to `hip_stream` (a hipStream_t; NULL = the default stream) on the
+ * current device.  Allocates a few KB of device memory for the status word and scratch slots. */
+int eoq_create(eoq_ctx **ctx, void *hip_stream);
+int eoq_destroy(eoq_ctx *ctx);
+const char *eoq_strerror(int code);
+/* Synchronise the stream, copy the device status word to *flags (host) and clear it.
+ * Returns EOQ_ERR_RANGE when any bit was set. */
+int eoq_status(eoq_ctx *ctx, uint32_t *flags);
+
+/* Convolution geometry.  Input N x H x W x C, filters K x R x S x C. */
+typedef struct eoq_conv_desc {
+    int32_t N, H, W, C;
+    int32_t K, R, S;
+    int32_t stride, pad;
+} eoq_conv_desc;
+
+enum eoq_op { EOQ_OP_CONV_FWD = 0, EOQ_OP_CONV_BWD_DATA = 1, EOQ_OP_CONV_BWD_WEIGHT = 2 };
+/* Bytes of workspace the convolution call `op` needs for `desc` (0 is possible). */
+size_t eoq_workspace_bytes(const eoq_conv_desc *desc, int op);
+
+/* Set `bytes` (multiple of 4) of device memory to zero with a kernel (safe under graph capture). */
+int eoq_fill_zero(eoq_ctx *ctx, void *ptr, size_t bytes);
+
+/* ---- quantisers on real input: Section 3.2.2, Eq.5 (Q), Eq.6 (CQ), Eq.7 (SQ) ---------------
+ * y = x * 2^pre_shift (exact), then
+ *   EOQ_Q : q is int32[n], code = R(128 y)
+ *   EOQ_CQ: q is int8[n],  code = clamp(R(128 y), -127, 127)
+ *   EOQ_SQ: q is int8[n],  scale = 2^R(log2 max|y|), code = clamp(R(128 y / scale)); *exp_slot = R(..) - 7,
+ *           so that value = code * 2^(*exp_slot).  An all-zero tensor gives codes 0 and exponent 0.
+ *           R(log2 max) is taken from the float's exponent and mantissa, never through a log.
+ * exp_slot is ignored (may be NULL) for Q and CQ.  Non-finite input sets EOQ_FLAG_NONFINITE. */
+enum eoq_qmode { EOQ_Q = 0, EOQ_CQ = 1, EOQ_SQ = 2 };
+int eoq_quantize(eoq_ctx *ctx, const float *x, size_t n, int mode, int pre_shift, void *q, int32_t *exp_slot);
+
+/* ---- forward epilogue of one Fixup layer: Eq.2 lines x2..x5, Eq.9, Eq.10 ---------------------
+ *   t = R(acc / 128)                               Q_a1: grid 2^-14 -> 2^-7, not clamped
+ *   z = gamma * t + 128 * b_post + 128 * skip      grid 2^-14; gamma NULL = 128 (one), b_post NULL = 0
+ *   relu = 1:  y = clamp(R(max(z,0) / 128), 0, 127)   Q_a2;  mask bit = [z > 0]
+ *              u_next = clamp(y + b_next_pre, -127, 127)   the next layer's x1 (Eq.2 line 2)
+ *   relu = 0:  only t_wide is produced (1x1 shortcut convolution)
+ * skip: the residual input of the block, NPQK layout, int8 codes (skip_is_wide = 0) or int32 codes on
+ * the 2^-7 grid (skip_is_wide = 1).  Outputs that are NULL are not written.  relu_mask_bits holds one
+ * bit per output element: bit (i % 32) of word (i / 32), i = linear NPQK index.  Scalars are read from
+ * device memory at kernel time. */
+typedef struct eoq_epilogue {
+    const int32_t *gamma;
+    const int32_t *b_post;
+    const void *skip;
+    int32_t skip_is_wide;
+    int32_t relu;
+    const int32_t *b_next_pre;
+    int8_t *y;
+    int8_t *u_next;
+    uint32_t *relu_mask_bits;
+    int32_t *t_wide;
+} eoq_epilogue;
+
+/* ---- Eq.2 line x1: u = clamp(a + b_pre, -127, 127) on int8 codes (b_pre: device scalar code) -- */
+int eoq_pre_bias(eoq_ctx *ctx, const int8_t *a, size_t n, const int32_t *b_pre, int8_t *u);
+
+/* ---- forward convolution: Eq.2, conv(x1) -----------------------------------------------------
+ * acc[n,p,q,k] = sum_{r,s,c} u[n, p*stride+r-pad, q*stride+s-pad, c] * w[k,r,s,c]  (zero padding).
+ * When `ep` is non-NULL the epilogue above is fused and `acc` may be NULL; when `acc` is non-NULL
+ * the raw int32 accumulators are stored as well.  ws: see eoq_workspace_bytes (only needed when
+ * C % 16 != 0). */
+int eoq_conv_fwd(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *u, const int8_t *w, int32_t *acc,
+                 const eoq_epilogue *ep, void *ws, size_t ws_bytes);
+
+/* ---- backward-data convolution: Eq.3 line e4 before Q_e ---------------------------------------
+ * d_acc[n,h,x,c] = sum_{k,r,s} e[n,p,q,k] * w[k,r,s,c] over the (p,q) with h = p*stride+r-pad,
+ * x = q*stride+s-pad.  max|d_acc| is atomically max-combined into *absmax_slot (non-NULL). */
+int eoq_conv_bwd_data(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, const int8_t *w,
+                      int32_t *d_acc, int32_t *absmax_slot, void *ws, size_t ws_bytes);
+
+/* ---- weight-gradient convolution: Eq.4 line g_w before Q_g ------------------------------------
+ * g_acc[k,r,s,c] = sum_{n,p,q} e[n,p,q,k] * u[n, p*stride+r-pad, q*stride+s-pad, c], the exact integer
+ * sum (partial sums of at most 131072 terms are int32, their combination is int64).  An element
+ * outside int32 sets EOQ_FLAG_ACC_OVERFLOW.  max|g_acc| is max-combined into *absmax_slot. */
+int eoq_conv_bwd_weight(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, const int8_t *u,
+                        int32_t *g_acc, int32_t *absmax_slot, void *ws, size_t ws_bytes);
+
+/* ---- ReLU backward and the statistics of Eq.3 lines e1..e3 / Eq.4 lines g_b2, g_gamma ----------
+ * e1 = e0 * [mask]; *sum_e1 += sum e1 (bias gradient); *sum_e1t += sum e1 * t (multiplier gradient,
+ * t_wide and sum_e1t may be NULL); *absmax_e1 = max(*absmax_e1, max|e1|) (for Q_e of e1*gamma).
+ * mask_bits NULL means no ReLU (all ones).  e1 may alias e0. */
+int eoq_relu_bwd(eoq_ctx *ctx, const int8_t *e0, const uint32_t *mask_bits, const int32_t *t_wide, size_t n,
+                 int8_t *e1, int64_t *sum_e1, int64_t *sum_e1t, int32_t *absmax_e1);
+
+/* ---- abs-max of the exact sum of two errors with different exponents (first phase of the merge
+ * of branch and shortcut errors at a block input): v = a*2^(Ea-Em) + b*2^(Eb-Em), Em = min(Ea,Eb).
+ * A gap above 24 sets EOQ_FLAG_EXP_GAP. */
+int eoq_merge_absmax(eoq_ctx *ctx, const int8_t *a, const int32_t *exp_a, const int8_t *b, const int32_t *exp_b,
+                     size_t n, int32_t *absmax_slot);
+
+/* ---- requantisation passes ----------------------------------------------------------------------
+ * EOQ_RQ_FWD      : the forward epilogue above on a stored accumulator (acc, K, ep).
+ * EOQ_RQ_SQ_ACC   : Q_e / Q_g of an int32 tensor (Eq.11, Eq.12): v = acc, E = *exp_in + exp_in_off.
+ * EOQ_RQ_SQ_GAMMA : Q_e(e2 * gamma) of Eq.3: v = src_a * (*gamma), E = *exp_in + exp_in_off - 7;
+ *                   *absmax is max|src_a| (the kernel multiplies it by |gamma|).
+ * EOQ_RQ_SQ_MERGE : Q_e of branch + shortcut error: v as in eoq_merge_absmax, E = min(*exp_in, *exp_b).
+ * For the SQ modes, with M = *absmax: r = R(log2 M) (integer test, no tie possible),
+ * out = clamp(R(v * 2^(7-r)), -127, 127), *exp_out = E + r - 7; M = 0 gives zeros and *exp_out = E.
+ * Optional extras: *sum_out += sum of the output codes (bias gradient of Eq.4);
+ * *max_code_out = max|out| (lets eoq_update_int8 skip its own abs-max pass). */
+enum eoq_rq_mode { EOQ_RQ_FWD = 0, EOQ_RQ_SQ_ACC = 1, EOQ_RQ_SQ_GAMMA = 2, EOQ_RQ_SQ_MERGE = 3 };
+typedef struct eoq_requant_args {
+    int32_t mode;
+    int32_t K;                 /* FWD: channels (innermost extent) */
+    size_t n;                  /* elements */
+    const int32_t *acc;        /* FWD, SQ_ACC */
+    const eoq_epilogue *ep;    /* FWD (host struct) */
+    const int8_t *src_a;       /* SQ_GAMMA: e1;  SQ_MERGE: branch error, exponent *exp_in */
+    const int8_t *src_b;       /* SQ_MERGE: shortcut error, exponent *exp_b */
+    const int32_t *exp_b;
+    const int32_t *gamma;      /* SQ_GAMMA */
+    const int32_t *absmax;
+    const int32_t *exp_in;
+    int32_t exp_in_off;
+    int8_t *out;
+    int32_t *exp_out;
+    int64_t *sum_out;          /* may be NULL */
+    int32_t *max_code_out;     /* may be NULL */
+} eoq_requant_args;
+int eoq_requant_epilogue(eoq_ctx *ctx, const eoq_requant_args *args);
+
+/* ---- 8-bit update: Eq.13 and Q_w (Eq.8) ----------------------------------------------------------
+ * lr = m * 2^-j with integers (m, j) read from lr_slot[0], lr_slot[1] on the device, 1 <= m <= 32768.
+ * u = SQ(m * g * 2^(Eg - j)) -> (u_code, Eu);  d = R(u_code * 2^(Eu + 7));  w <- clamp(w - d, -127, 127).
+ * g_max_code: device slot with max|g| (from EOQ_RQ_SQ_ACC's max_code_out), or NULL to have the call
+ * find it with one extra pass. */
+int eoq_update_int8(eoq_ctx *ctx, int8_t *w, size_t n, const int8_t *g, const int32_t *g_exp_slot,
+                    const int32_t *g_max_code, const int32_t *lr_slot);
+
+/* ---- scalar parameters (bias, multiplier: Eq.10, Eq.4 lines g_b1, g_b2, g_gamma, Eq.13) -----------
+ * The gradient of a scalar is the sum over all elements, then Q_g of that one-element tensor, then
+ * the update above without the clamp.  Each descriptor names up to two terms S * 2^(E + off):
+ * sums[sum_idx[t]] and exps[exp_idx[t]] + exp_off[t]  (two terms when two convolutions read the same
+ * biased input).  descs is a DEVICE array.  g_code_out / g_exp_out (may be NULL) receive Q_g's result. */
+typedef struct eoq_scalar_grad {
+    int32_t param;      /* index into scalars[] */
+    int32_t n_terms;    /* 1 or 2 */
+    int32_t sum_idx[2];
+    int32_t exp_idx[2];
+    int32_t exp_off[2];
+} eoq_scalar_grad;
+int eoq_update_scalars(eoq_ctx *ctx, int32_t *scalars, const eoq_scalar_grad *descs, int32_t count,
+                       const int64_t *sums, const int32_t *exps, const int32_t *lr_slot,
+                       int32_t *g_code_out, int32_t *g_exp_out);
+
+/* ---- pooling, head (outside the quantised arithmetic of Eq.2-13 but on the step's path) ----------
+ * Max pool R x S / stride / pad on int8 codes; padding never wins.  u_next as in the epilogue.
+ * Backward routes each error to the first maximum in (r,s) scan order and adds overlapping windows
+ * (int32 result, |d| max-combined into *absmax_slot); a requant pass (EOQ_RQ_SQ_ACC) follows. */
+int eoq_maxpool_fwd(eoq_ctx *ctx, const int8_t *a, int32_t N, int32_t H, int32_t W, int32_t C, int32_t R,
+                    int32_t S, int32_t stride, int32_t pad, int8_t *y, const int32_t *b_next_pre, int8_t *u_next);
+int eoq_maxpool_bwd(eoq_ctx *ctx, const int8_t *a, const int8_t *e, int32_t N, int32_t H, int32_t W, int32_t C,
+                    int32_t R, int32_t S, int32_t stride, int32_t pad, int32_t *d, int32_t *absmax_slot);
+/* Global average pool, integer part: sum[n][c] = sum_{h,w} y[n,h,w,c]. */
+int eoq_gap_sum(eoq_ctx *ctx, const int8_t *y, int32_t N, int32_t HW, int32_t C, int32_t *sum);
+/* e[n,h,w,c] = codes[n][c] for all HW positions (error of the average pool, already quantised). */
+int eoq_broadcast_hw(eoq_ctx *ctx, const int8_t *codes, int32_t N, int32_t HW, int32_t C, int8_t *e);
+/* Float head (the last layer stays unquantised, Section 5.1), fp64 in a fixed operation order:
+ * feat = sum/(128*HW); logits = b + W feat (sequential fma, ascending feature); softmax with max
+ * subtraction; loss = mean cross-entropy; d = (float)((W^T dlogits) / HW) per real activation;
+ * then W -= lr*dW, b -= lr*db with lr = m * 2^-j from lr_slot.  ws: at least
+ * eoq_head_workspace_bytes(N, F, J) bytes. */
+size_t eoq_head_workspace_bytes(int32_t N, int32_t F, int32_t J);
+int eoq_head_fwd_bwd(eoq_ctx *ctx, int32_t N, int32_t F, int32_t J, int32_t HW, const int32_t *gap_sum,
+                     double *Wfc, double *bfc, const int32_t *labels, const int32_t *lr_slot, double *loss,
+                     float *d, double *logits, void *ws, size_t ws_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EOQ_H */

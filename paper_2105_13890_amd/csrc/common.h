@@ -1,0 +1,113 @@
+// Shared host/device helpers of libeoq (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/eoq.h"
+
+struct eoq_ctx {
+    hipStream_t stream;
+    int device;
+    uint32_t *d_status;   // device status word (eoq_flag_bits)
+    int32_t *d_scratch;   // EOQ_SCRATCH_SLOTS int32 slots for call-internal statistics
+};
+
+constexpr int EOQ_SCRATCH_SLOTS = 64;
+constexpr int CODE_MAX = 127;
+
+#define EOQ_HIP(expr)                                  \
+    do {                                               \
+        hipError_t e_ = (expr);                        \
+        if (e_ != hipSuccess) return EOQ_ERR_HIP;      \
+    } while (0)
+
+#define EOQ_LAUNCH_CHECK()                             \
+    do {                                               \
+        if (hipGetLastError() != hipSuccess) return EOQ_ERR_HIP; \
+    } while (0)
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+// ---- rounding: v * 2^-s to nearest, ties to even (s >= 1); exact left shift for s <= 0 ----
+__device__ __forceinline__ int64_t rne_shift64(int64_t v, int s)
+{
+    if (s <= 0) return v << (-s);
+    if (s > 62) s = 62;
+    return (v + ((int64_t(1) << (s - 1)) - 1) + ((v >> s) & 1)) >> s;
+}
+
+__device__ __forceinline__ int32_t rne_shift7(int32_t v)   // |v| < 2^30
+{
+    return (v + 63 + ((v >> 7) & 1)) >> 7;
+}
+
+__device__ __forceinline__ int clamp_i(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+// ---- R(log2 M) for an integer M >= 1 (Eq.7's scale exponent): floor(log2 M), plus one iff
+// M^2 > 2^(2p+1); equality is impossible for an integer, so the rounding never ties ----
+__device__ __forceinline__ int sq_exponent_u32(uint32_t M)
+{
+    int p = 31 - __clz((int)M);
+    uint64_t sq = (uint64_t)M * (uint64_t)M;
+    return p + (sq > (uint64_t(1) << (2 * p + 1)) ? 1 : 0);
+}
+
+__device__ __forceinline__ int sq_exponent_u64(uint64_t M)   // M < 2^62
+{
+    int p = 63 - __clzll((long long)M);
+    // compare M^2 with 2^(2p+1) without overflowing: M = 2^p * f, f in [1,2): f^2 > 2
+    // use 128-bit product via two halves
+    unsigned __int128 sq = (unsigned __int128)M * (unsigned __int128)M;
+    unsigned __int128 lim = (unsigned __int128)1 << (2 * p + 1);
+    return p + (sq > lim ? 1 : 0);
+}
+
+// SQ of one value given the tensor's scale exponent r: clamp(R(v * 2^(7-r)), -127, 127)
+__device__ __forceinline__ int sq_code(int64_t v, int r)
+{
+    int64_t c = rne_shift64(v, r - 7);
+    return (int)(c < -CODE_MAX ? -CODE_MAX : (c > CODE_MAX ? CODE_MAX : c));
+}
+
+// ---- wave / block reductions (wave = 64 lanes) ----
+__device__ __forceinline__ int wave_max_i32(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        int t = __shfl_xor(v, o, 64);
+        v = t > v ? t : v;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        uint32_t t = (uint32_t)__shfl_xor((int)v, o, 64);
+        v = t > v ? t : v;
+    }
+    return v;
+}
+
+__device__ __forceinline__ int64_t wave_sum_i64(int64_t v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        int lo = __shfl_xor((int)(v & 0xffffffff), o, 64);
+        int hi = __shfl_xor((int)(v >> 32), o, 64);
+        v += (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+    }
+    return v;
+}
+
+__device__ __forceinline__ void atomic_add_i64(int64_t *p, int64_t v)
+{
+    atomicAdd((unsigned long long *)p, (unsigned long long)v);
+}
+
+static inline int conv_out_dim(int in, int pad, int k, int st) { return (in + 2 * pad - k) / st + 1; }
+static inline size_t round_up(size_t v, size_t m) { return (v + m - 1) / m * m; }

@@ -1,0 +1,540 @@
+// HBM-bound passes of the training step: the real-input quantisers (Eq.5-7), the pre-bias
+// (Eq.2 line x1), ReLU backward with the scalar-gradient statistics (Eq.3 e1, Eq.4 g_b2 / g_gamma),
+// the scale-quantiser passes of the backward chain (Eq.11, Eq.12), the merge of branch and
+// shortcut errors, and the 8-bit update (Eq.13).
+//
+// Every kernel streams 16 elements per lane per iteration (one 16-byte int8 vector, four for
+// int32 / fp32 sources) with a grid-stride loop; tails shorter than 16 are done one by one.
+// All pointers must be 16-byte aligned.
+#include "common.h"
+
+namespace {
+
+constexpr int EW_THREADS = 256;
+constexpr unsigned EW_MAX_BLOCKS = 256 * 8;
+
+inline unsigned ew_blocks(size_t n_vec)
+{
+    size_t b = (n_vec + EW_THREADS - 1) / EW_THREADS;
+    if (b < 1) b = 1;
+    if (b > EW_MAX_BLOCKS) b = EW_MAX_BLOCKS;
+    return (unsigned)b;
+}
+
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+__device__ __forceinline__ int byte_at(const v4i &v, int i)   // sign-extended byte i (0..15)
+{
+    return (int)(int8_t)((uint32_t)v[i >> 2] >> (8 * (i & 3)));
+}
+
+__device__ __forceinline__ void set_byte(v4i &v, int i, int code)
+{
+    uint32_t sh = 8 * (i & 3);
+    v[i >> 2] = (int)(((uint32_t)v[i >> 2] & ~(0xffu << sh)) | (((uint32_t)code & 0xffu) << sh));
+}
+
+// ------------------------------------------------------------------------------------------
+// eoq_quantize
+// ------------------------------------------------------------------------------------------
+__global__ void absmax_f32_kernel(const float *x, size_t n, uint32_t *slot_bits, uint32_t *status)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    uint32_t m = 0;
+    for (; i < n; i += stride) {
+        uint32_t b = __float_as_uint(x[i]) & 0x7fffffffu;
+        m = b > m ? b : m;
+    }
+    m = wave_max_u32(m);
+    if ((threadIdx.x & 63) == 0) {
+        if (m >= 0x7f800000u) atomicOr(status, (uint32_t)EOQ_FLAG_NONFINITE);
+        if (m) atomicMax(slot_bits, m);
+    }
+}
+
+// R(log2 |x|max * 2^pre) from the float's bits (Eq.7, scale): value = mant * 2^(e - 23) with an
+// integer mantissa, so R(log2) = e - 23 + R(log2 mant), and R(log2 mant) is the integer test.
+__device__ __forceinline__ int scale_exponent_f32bits(uint32_t bits)
+{
+    int e = (int)(bits >> 23);
+    uint32_t mant = bits & 0x7fffffu;
+    if (e) mant |= 0x800000u; else e = 1;           // denormal: no hidden bit, exponent of the smallest normal
+    return e - 127 - 23 + sq_exponent_u32(mant);
+}
+
+template <int MODE>
+__global__ void quantize_f32_kernel(const float *x, size_t n, int pre_shift, void *q, int32_t *exp_slot,
+                                    const uint32_t *slot_bits, uint32_t *status)
+{
+    int sh = pre_shift + 7;
+    bool zero = false;
+    if (MODE == EOQ_SQ) {
+        uint32_t mb = *slot_bits;
+        if (mb == 0 || mb >= 0x7f800000u) {
+            zero = true;
+            if (blockIdx.x == 0 && threadIdx.x == 0) *exp_slot = 0;
+        } else {
+            int R = scale_exponent_f32bits(mb) + pre_shift;
+            sh = pre_shift + 7 - R;
+            if (blockIdx.x == 0 && threadIdx.x == 0) *exp_slot = R - 7;
+        }
+    }
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (; i < n; i += stride) {
+        float xf = x[i];
+        if (MODE != EOQ_SQ && (__float_as_uint(xf) & 0x7fffffffu) >= 0x7f800000u) { bad = true; xf = 0.f; }
+        double v = zero ? 0.0 : rint(ldexp((double)xf, sh));
+        if (MODE == EOQ_Q) {
+            v = v < -2147483648.0 ? -2147483648.0 : (v > 2147483647.0 ? 2147483647.0 : v);
+            ((int32_t *)q)[i] = (int32_t)v;
+        } else {
+            v = v < -127.0 ? -127.0 : (v > 127.0 ? 127.0 : v);
+            ((int8_t *)q)[i] = (int8_t)(int)v;
+        }
+    }
+    if (bad) atomicOr(status, (uint32_t)EOQ_FLAG_NONFINITE);
+}
+
+// ------------------------------------------------------------------------------------------
+// pre-bias
+// ------------------------------------------------------------------------------------------
+__global__ void pre_bias_kernel(const int8_t *a, size_t n, const int32_t *b_pre, int8_t *u)
+{
+    const int b = *b_pre;
+    const size_t nv = n / 16;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < nv; i += stride) {
+        v4i v = ((const v4i *)a)[i], o = {0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < 16; ++k) set_byte(o, k, clamp_i(byte_at(v, k) + b, -CODE_MAX, CODE_MAX));
+        ((v4i *)u)[i] = o;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 15)) {
+        size_t t = nv * 16 + threadIdx.x;
+        u[t] = (int8_t)clamp_i((int)a[t] + b, -CODE_MAX, CODE_MAX);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// ReLU backward + statistics
+// ------------------------------------------------------------------------------------------
+__global__ void relu_bwd_kernel(const int8_t *e0, const uint16_t *mask16, const int32_t *t, size_t n, int8_t *e1,
+                                int64_t *sum_e1, int64_t *sum_e1t, int32_t *absmax)
+{
+    const size_t nv = n / 16;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    int64_t s1 = 0, st = 0;
+    int mx = 0;
+    for (; i < nv; i += stride) {
+        v4i v = ((const v4i *)e0)[i], o = {0, 0, 0, 0};
+        uint32_t m = mask16 ? (uint32_t)mask16[i] : 0xffffu;
+        v4i tv[4];
+        if (t) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) tv[k] = ((const v4i *)t)[i * 4 + k];
+        }
+        int ls = 0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            int e = ((m >> k) & 1u) ? byte_at(v, k) : 0;
+            set_byte(o, k, e);
+            ls += e;
+            int ae = e < 0 ? -e : e;
+            mx = ae > mx ? ae : mx;
+            if (t) st += (int64_t)e * (int64_t)tv[k >> 2][k & 3];
+        }
+        s1 += ls;
+        if (e1) ((v4i *)e1)[i] = o;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 15)) {
+        size_t j = nv * 16 + threadIdx.x;
+        bool on = mask16 ? ((((const uint8_t *)mask16)[j >> 3] >> (j & 7)) & 1) : true;
+        int e = on ? (int)e0[j] : 0;
+        if (e1) e1[j] = (int8_t)e;
+        s1 += e;
+        int ae = e < 0 ? -e : e;
+        mx = ae > mx ? ae : mx;
+        if (t) st += (int64_t)e * (int64_t)t[j];
+    }
+    s1 = wave_sum_i64(s1);
+    mx = wave_max_i32(mx);
+    if (t) st = wave_sum_i64(st);
+    if ((threadIdx.x & 63) == 0) {
+        if (sum_e1 && s1) atomic_add_i64(sum_e1, s1);
+        if (t && sum_e1t && st) atomic_add_i64(sum_e1t, st);
+        if (absmax && mx) atomicMax(absmax, mx);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// merge: abs-max of a*2^(Ea-Em) + b*2^(Eb-Em)
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void merge_shifts(int Ea, int Eb, int &sa, int &sb, int &Em, uint32_t *status)
+{
+    Em = Ea < Eb ? Ea : Eb;
+    sa = Ea - Em;
+    sb = Eb - Em;
+    if (sa > 24 || sb > 24) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, (uint32_t)EOQ_FLAG_EXP_GAP);
+        sa = sa > 24 ? 24 : sa;
+        sb = sb > 24 ? 24 : sb;
+    }
+}
+
+__global__ void merge_absmax_kernel(const int8_t *a, const int32_t *exp_a, const int8_t *b, const int32_t *exp_b,
+                                    size_t n, int32_t *absmax, uint32_t *status)
+{
+    int sa, sb, Em;
+    merge_shifts(*exp_a, *exp_b, sa, sb, Em, status);
+    const size_t nv = n / 16;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    int mx = 0;
+    for (; i < nv; i += stride) {
+        v4i va = ((const v4i *)a)[i], vb = ((const v4i *)b)[i];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            int v = (byte_at(va, k) << sa) + (byte_at(vb, k) << sb);
+            v = v < 0 ? -v : v;
+            mx = v > mx ? v : mx;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 15)) {
+        size_t j = nv * 16 + threadIdx.x;
+        int v = ((int)a[j] << sa) + ((int)b[j] << sb);
+        v = v < 0 ? -v : v;
+        mx = v > mx ? v : mx;
+    }
+    mx = wave_max_i32(mx);
+    if ((threadIdx.x & 63) == 0 && mx) atomicMax(absmax, mx);
+}
+
+// ------------------------------------------------------------------------------------------
+// scale-quantiser passes (second phase: the abs-max is known)
+// ------------------------------------------------------------------------------------------
+struct SqArgs {
+    const int32_t *acc;
+    const int8_t *src_a, *src_b;
+    const int32_t *exp_b, *gamma, *absmax, *exp_in;
+    int32_t exp_in_off;
+    size_t n;
+    int8_t *out;
+    int32_t *exp_out;
+    int64_t *sum_out;
+    int32_t *max_code_out;
+    uint32_t *status;
+};
+
+template <int MODE>
+__global__ void sq_pass_kernel(SqArgs p)
+{
+    int sa = 0, sb = 0, g = 0;
+    int E = *p.exp_in + p.exp_in_off;
+    uint64_t M = (uint64_t)(uint32_t)*p.absmax;
+    if (MODE == EOQ_RQ_SQ_GAMMA) {
+        g = *p.gamma;
+        M *= (uint64_t)(g < 0 ? -g : g);
+        E -= 7;
+    }
+    if (MODE == EOQ_RQ_SQ_MERGE) {
+        int Em;
+        merge_shifts(*p.exp_in + p.exp_in_off, *p.exp_b, sa, sb, Em, p.status);
+        E = Em;
+    }
+    const int r = M ? sq_exponent_u64(M) : 7;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *p.exp_out = M ? E + r - 7 : E;
+        if (p.max_code_out) *p.max_code_out = M ? sq_code((int64_t)M, r) : 0;
+    }
+    const size_t nv = p.n / 16;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    int64_t s = 0;
+    for (; i < nv; i += stride) {
+        v4i o = {0, 0, 0, 0};
+        int ls = 0;
+        if (MODE == EOQ_RQ_SQ_ACC) {
+            v4i a[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) a[k] = ((const v4i *)p.acc)[i * 4 + k];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                int c = sq_code((int64_t)a[k >> 2][k & 3], r);
+                set_byte(o, k, c);
+                ls += c;
+            }
+        } else if (MODE == EOQ_RQ_SQ_GAMMA) {
+            v4i a = ((const v4i *)p.src_a)[i];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                int c = sq_code((int64_t)byte_at(a, k) * (int64_t)g, r);
+                set_byte(o, k, c);
+                ls += c;
+            }
+        } else {
+            v4i a = ((const v4i *)p.src_a)[i], b = ((const v4i *)p.src_b)[i];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                int c = sq_code((int64_t)((byte_at(a, k) << sa) + (byte_at(b, k) << sb)), r);
+                set_byte(o, k, c);
+                ls += c;
+            }
+        }
+        s += ls;
+        ((v4i *)p.out)[i] = o;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (p.n & 15)) {
+        size_t j = nv * 16 + threadIdx.x;
+        int64_t v;
+        if (MODE == EOQ_RQ_SQ_ACC) v = p.acc[j];
+        else if (MODE == EOQ_RQ_SQ_GAMMA) v = (int64_t)p.src_a[j] * (int64_t)g;
+        else v = ((int)p.src_a[j] << sa) + ((int)p.src_b[j] << sb);
+        int c = sq_code(v, r);
+        p.out[j] = (int8_t)c;
+        s += c;
+    }
+    if (p.sum_out) {
+        s = wave_sum_i64(s);
+        if ((threadIdx.x & 63) == 0 && s) atomic_add_i64(p.sum_out, s);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// update
+// ------------------------------------------------------------------------------------------
+__global__ void absmax_i8_kernel(const int8_t *g, size_t n, int32_t *slot)
+{
+    const size_t nv = n / 16;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    int mx = 0;
+    for (; i < nv; i += stride) {
+        v4i v = ((const v4i *)g)[i];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            int a = byte_at(v, k);
+            a = a < 0 ? -a : a;
+            mx = a > mx ? a : mx;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 15)) {
+        int a = g[nv * 16 + threadIdx.x];
+        a = a < 0 ? -a : a;
+        mx = a > mx ? a : mx;
+    }
+    mx = wave_max_i32(mx);
+    if ((threadIdx.x & 63) == 0 && mx) atomicMax(slot, mx);
+}
+
+// delta on the 2^-7 grid for one gradient code (Eq.13): u = SQ(m*g*2^(Eg-j)), d = R(u * 2^(Eu+7))
+struct UpdateRule {
+    int m, r, sh;   // sh = -(Eu + 7): right shift if positive
+    __device__ __forceinline__ int delta(int g) const
+    {
+        return (int)rne_shift64((int64_t)sq_code((int64_t)m * g, r), sh);
+    }
+};
+
+__device__ __forceinline__ bool make_update_rule(int max_code, int Eg, const int32_t *lr_slot, UpdateRule &u,
+                                                 uint32_t *status)
+{
+    if (max_code == 0) return false;
+    u.m = lr_slot[0];
+    const int j = lr_slot[1];
+    u.r = sq_exponent_u64((uint64_t)u.m * (uint64_t)max_code);
+    const int Eu = Eg - j + u.r - 7;
+    u.sh = -(Eu + 7);
+    if (u.sh < -24) {
+        atomicOr(status, (uint32_t)EOQ_FLAG_SHIFT_RANGE);
+        u.sh = -24;
+    }
+    return true;
+}
+
+__global__ void update_int8_kernel(int8_t *w, size_t n, const int8_t *g, const int32_t *g_exp, const int32_t *g_max,
+                                   const int32_t *lr_slot, uint32_t *status)
+{
+    UpdateRule u;
+    if (!make_update_rule(*g_max, *g_exp, lr_slot, u, status)) return;
+    const size_t nv = n / 16;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < nv; i += stride) {
+        v4i wv = ((const v4i *)w)[i], gv = ((const v4i *)g)[i], o = {0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            set_byte(o, k, clamp_i(byte_at(wv, k) - u.delta(byte_at(gv, k)), -CODE_MAX, CODE_MAX));
+        ((v4i *)w)[i] = o;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 15)) {
+        size_t t = nv * 16 + threadIdx.x;
+        w[t] = (int8_t)clamp_i((int)w[t] - u.delta(g[t]), -CODE_MAX, CODE_MAX);
+    }
+}
+
+__global__ void update_scalars_kernel(int32_t *scalars, const eoq_scalar_grad *descs, int count, const int64_t *sums,
+                                      const int32_t *exps, const int32_t *lr_slot, int32_t *g_code_out,
+                                      int32_t *g_exp_out, uint32_t *status)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    const eoq_scalar_grad d = descs[i];
+    // exact sum of the terms on the finest grid
+    int E0 = exps[d.exp_idx[0]] + d.exp_off[0];
+    int64_t S = sums[d.sum_idx[0]];
+    if (d.n_terms > 1) {
+        int E1 = exps[d.exp_idx[1]] + d.exp_off[1];
+        int64_t S1 = sums[d.sum_idx[1]];
+        int Em = E0 < E1 ? E0 : E1;
+        int s0 = E0 - Em, s1 = E1 - Em;
+        if (s0 > 24 || s1 > 24) {
+            atomicOr(status, (uint32_t)EOQ_FLAG_EXP_GAP);
+            s0 = s0 > 24 ? 24 : s0;
+            s1 = s1 > 24 ? 24 : s1;
+        }
+        S = (S << s0) + (S1 << s1);
+        E0 = Em;
+    }
+    // Q_g of the one-element tensor (Eq.12)
+    int gc = 0, Eg = E0;
+    if (S) {
+        uint64_t M = (uint64_t)(S < 0 ? -S : S);
+        int r = sq_exponent_u64(M);
+        gc = sq_code(S, r);
+        Eg = E0 + r - 7;
+    }
+    if (g_code_out) g_code_out[i] = gc;
+    if (g_exp_out) g_exp_out[i] = Eg;
+    // Q_u and the unclamped update (Eq.13, Eq.10)
+    UpdateRule u;
+    int a = gc < 0 ? -gc : gc;
+    if (make_update_rule(a, Eg, lr_slot, u, status)) scalars[d.param] -= u.delta(gc);
+}
+
+} // namespace
+
+// ============================================================================================
+// C ABI
+// ============================================================================================
+extern "C" int eoq_quantize(eoq_ctx *c, const float *x, size_t n, int mode, int pre_shift, void *q, int32_t *exp_slot)
+{
+    if (!c || (n && (!x || !q)) || mode < EOQ_Q || mode > EOQ_SQ) return EOQ_ERR_ARG;
+    if (mode == EOQ_SQ && !exp_slot) return EOQ_ERR_ARG;
+    if (pre_shift < -64 || pre_shift > 64) return EOQ_ERR_ARG;
+    uint32_t *slot = (uint32_t *)c->d_scratch;
+    const unsigned blocks = ew_blocks(n ? n : 1);
+    if (mode == EOQ_SQ) {
+        if (int rc = eoq_fill_zero(c, slot, 4)) return rc;
+        hipLaunchKernelGGL(absmax_f32_kernel, dim3(blocks), dim3(EW_THREADS), 0, c->stream, x, n, slot, c->d_status);
+        hipLaunchKernelGGL(quantize_f32_kernel<EOQ_SQ>, dim3(blocks), dim3(EW_THREADS), 0, c->stream, x, n, pre_shift, q,
+                           exp_slot, slot, c->d_status);
+    } else if (mode == EOQ_CQ) {
+        hipLaunchKernelGGL(quantize_f32_kernel<EOQ_CQ>, dim3(blocks), dim3(EW_THREADS), 0, c->stream, x, n, pre_shift, q,
+                           exp_slot, slot, c->d_status);
+    } else {
+        hipLaunchKernelGGL(quantize_f32_kernel<EOQ_Q>, dim3(blocks), dim3(EW_THREADS), 0, c->stream, x, n, pre_shift, q,
+                           exp_slot, slot, c->d_status);
+    }
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}
+
+extern "C" int eoq_pre_bias(eoq_ctx *c, const int8_t *a, size_t n, const int32_t *b_pre, int8_t *u)
+{
+    if (!c || !b_pre || (n && (!a || !u)) || !aligned16(a) || !aligned16(u)) return EOQ_ERR_ARG;
+    if (!n) return EOQ_OK;
+    hipLaunchKernelGGL(pre_bias_kernel, dim3(ew_blocks(n / 16)), dim3(EW_THREADS), 0, c->stream, a, n, b_pre, u);
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}
+
+extern "C" int eoq_relu_bwd(eoq_ctx *c, const int8_t *e0, const uint32_t *mask_bits, const int32_t *t_wide, size_t n,
+                            int8_t *e1, int64_t *sum_e1, int64_t *sum_e1t, int32_t *absmax_e1)
+{
+    if (!c || (n && !e0) || !aligned16(e0) || !aligned16(e1) || !aligned16(t_wide) || ((uintptr_t)mask_bits & 3))
+        return EOQ_ERR_ARG;
+    if (!n) return EOQ_OK;
+    hipLaunchKernelGGL(relu_bwd_kernel, dim3(ew_blocks(n / 16)), dim3(EW_THREADS), 0, c->stream, e0,
+                       (const uint16_t *)mask_bits, t_wide, n, e1, sum_e1, sum_e1t, absmax_e1);
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}
+
+extern "C" int eoq_merge_absmax(eoq_ctx *c, const int8_t *a, const int32_t *exp_a, const int8_t *b,
+                                const int32_t *exp_b, size_t n, int32_t *absmax_slot)
+{
+    if (!c || !exp_a || !exp_b || !absmax_slot || (n && (!a || !b)) || !aligned16(a) || !aligned16(b))
+        return EOQ_ERR_ARG;
+    if (!n) return EOQ_OK;
+    hipLaunchKernelGGL(merge_absmax_kernel, dim3(ew_blocks(n / 16)), dim3(EW_THREADS), 0, c->stream, a, exp_a, b,
+                       exp_b, n, absmax_slot, c->d_status);
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}
+
+int eoq_requant_fwd_standalone(eoq_ctx *c, const eoq_requant_args *a);   // conv_igemm.hip
+
+extern "C" int eoq_requant_epilogue(eoq_ctx *c, const eoq_requant_args *a)
+{
+    if (!c || !a) return EOQ_ERR_ARG;
+    if (a->mode == EOQ_RQ_FWD) return eoq_requant_fwd_standalone(c, a);
+    if (a->mode < EOQ_RQ_SQ_ACC || a->mode > EOQ_RQ_SQ_MERGE) return EOQ_ERR_ARG;
+    if (!a->absmax || !a->exp_in || !a->exp_out || (a->n && !a->out) || !aligned16(a->out)) return EOQ_ERR_ARG;
+    SqArgs p;
+    p.acc = a->acc; p.src_a = a->src_a; p.src_b = a->src_b; p.exp_b = a->exp_b; p.gamma = a->gamma;
+    p.absmax = a->absmax; p.exp_in = a->exp_in; p.exp_in_off = a->exp_in_off; p.n = a->n; p.out = a->out;
+    p.exp_out = a->exp_out; p.sum_out = a->sum_out; p.max_code_out = a->max_code_out; p.status = c->d_status;
+    const dim3 grid(ew_blocks(a->n / 16)), block(EW_THREADS);
+    switch (a->mode) {
+    case EOQ_RQ_SQ_ACC:
+        if ((a->n && !a->acc) || !aligned16(a->acc)) return EOQ_ERR_ARG;
+        hipLaunchKernelGGL(sq_pass_kernel<EOQ_RQ_SQ_ACC>, grid, block, 0, c->stream, p);
+        break;
+    case EOQ_RQ_SQ_GAMMA:
+        if ((a->n && !a->src_a) || !a->gamma || !aligned16(a->src_a)) return EOQ_ERR_ARG;
+        hipLaunchKernelGGL(sq_pass_kernel<EOQ_RQ_SQ_GAMMA>, grid, block, 0, c->stream, p);
+        break;
+    default:
+        if ((a->n && (!a->src_a || !a->src_b)) || !a->exp_b || !aligned16(a->src_a) || !aligned16(a->src_b))
+            return EOQ_ERR_ARG;
+        hipLaunchKernelGGL(sq_pass_kernel<EOQ_RQ_SQ_MERGE>, grid, block, 0, c->stream, p);
+        break;
+    }
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}
+
+extern "C" int eoq_update_int8(eoq_ctx *c, int8_t *w, size_t n, const int8_t *g, const int32_t *g_exp_slot,
+                               const int32_t *g_max_code, const int32_t *lr_slot)
+{
+    if (!c || !g_exp_slot || !lr_slot || (n && (!w || !g)) || !aligned16(w) || !aligned16(g)) return EOQ_ERR_ARG;
+    if (!n) return EOQ_OK;
+    const dim3 grid(ew_blocks(n / 16)), block(EW_THREADS);
+    if (!g_max_code) {
+        int32_t *slot = c->d_scratch + 1;
+        if (int rc = eoq_fill_zero(c, slot, 4)) return rc;
+        hipLaunchKernelGGL(absmax_i8_kernel, grid, block, 0, c->stream, g, n, slot);
+        g_max_code = slot;
+    }
+    hipLaunchKernelGGL(update_int8_kernel, grid, block, 0, c->stream, w, n, g, g_exp_slot, g_max_code, lr_slot,
+                       c->d_status);
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}
+
+extern "C" int eoq_update_scalars(eoq_ctx *c, int32_t *scalars, const eoq_scalar_grad *descs, int32_t count,
+                                  const int64_t *sums, const int32_t *exps, const int32_t *lr_slot,
+                                  int32_t *g_code_out, int32_t *g_exp_out)
+{
+    if (!c || count < 0 || (count && (!scalars || !descs || !sums || !exps)) || !lr_slot) return EOQ_ERR_ARG;
+    if (!count) return EOQ_OK;
+    hipLaunchKernelGGL(update_scalars_kernel, dim3((count + 63) / 64), dim3(64), 0, c->stream, scalars, descs, count,
+                       sums, exps, lr_slot, g_code_out, g_exp_out, c->d_status);
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}

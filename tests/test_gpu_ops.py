@@ -1,0 +1,281 @@
+"""GPU parity, one C-ABI call at a time: every int8 / int32 output of libeoq must equal the CPU
+oracle bit for bit on the same seeded inputs.  Shapes span several tiles and ragged tails."""
+import numpy as np
+import pytest
+
+import seeded_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_2105_13890_amd import eoq
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    c = eoq.Context()
+    yield c
+    assert c.status() == 0
+    c.close()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def zeros(shape, dtype):
+    return torch.zeros(shape, dtype=dtype, device="cuda")
+
+
+def desc_of(d):
+    from paper_2105_13890_amd import eoq
+    return eoq.ConvDesc(d.N, d.H, d.W, d.C, d.K, d.R, d.S, d.stride, d.pad)
+
+
+def ws_for(d, op):
+    from paper_2105_13890_amd import eoq
+    n = eoq.Context.workspace_bytes(desc_of(d), op)
+    return zeros((max(n, 16),), torch.uint8)
+
+
+from oracle import ops as oo            # noqa: E402
+from oracle import quant as oq          # noqa: E402
+from oracle.ops import ConvShape        # noqa: E402
+
+CONV_SHAPES = [
+    ConvShape(8, 32, 32, 16, 16, 3, 3, 1, 1),      # the lone-block workload's convolution
+    ConvShape(2, 14, 14, 64, 128, 3, 3, 1, 1),
+    ConvShape(3, 17, 13, 32, 48, 3, 3, 2, 1),      # ragged M, stride 2, K not a multiple of 32
+    ConvShape(2, 28, 28, 128, 256, 1, 1, 1, 0),
+    ConvShape(2, 28, 28, 64, 256, 1, 1, 2, 0),     # strided shortcut convolution
+    ConvShape(1, 9, 9, 512, 64, 1, 1, 1, 0),
+    ConvShape(2, 8, 8, 256, 512, 3, 3, 1, 1),      # long reduction (2304)
+    ConvShape(5, 12, 12, 16, 32, 5, 5, 1, 2),
+    ConvShape(2, 33, 33, 3, 64, 7, 7, 2, 3),       # stem: C = 3 goes through the explicit im2col
+    ConvShape(4, 16, 16, 3, 16, 3, 3, 1, 1),
+]
+IDS = [f"{d.N}x{d.H}x{d.W}x{d.C}-k{d.K}r{d.R}s{d.stride}" for d in CONV_SHAPES]
+
+
+@pytest.mark.parametrize("d", CONV_SHAPES, ids=IDS)
+def test_conv_fwd_raw_accumulators(ctx, d):
+    from paper_2105_13890_amd import eoq
+    u = si.uniform_int8(0, "u", (d.N, d.H, d.W, d.C))
+    w = si.uniform_int8(0, "w", (d.K, d.R, d.S, d.C))
+    acc = zeros((d.N, d.P, d.Q, d.K), torch.int32)
+    ctx.conv_fwd(desc_of(d), dev(u), dev(w), acc=acc, ws=ws_for(d, eoq.OP_CONV_FWD))
+    assert np.array_equal(host(acc), oo.conv_fwd(d, u, w))
+
+
+@pytest.mark.parametrize("d", CONV_SHAPES[:8], ids=IDS[:8])
+def test_conv_fwd_fused_epilogue(ctx, d):
+    from paper_2105_13890_amd import eoq
+    u = si.uniform_int8(1, "u", (d.N, d.H, d.W, d.C))
+    w = si.uniform_int8(1, "w", (d.K, d.R, d.S, d.C), -30, 30)
+    oshape = (d.N, d.P, d.Q, d.K)
+    for case, (gam, bpost, bnext, skip_kind) in enumerate([(None, 3, -2, None), (117, -5, 4, "i8"), (140, 2, 0, "wide")]):
+        skip = None
+        if skip_kind == "i8":
+            skip = si.uniform_int8(2, "skip", oshape, 0, 127)
+        elif skip_kind == "wide":
+            skip = (si.uniform_int8(2, "skipw", oshape).astype(np.int32) * 9)
+        y, un, tw = zeros(oshape, torch.int8), zeros(oshape, torch.int8), zeros(oshape, torch.int32)
+        n = int(np.prod(oshape))
+        mask = zeros(((n + 31) // 32,), torch.int32)
+        sc = dev(np.array([gam if gam is not None else 0, bpost, bnext], dtype=np.int32))
+        skip_d = dev(skip) if skip is not None else None     # keep alive: the epilogue struct holds raw pointers
+        ep = ctx.epilogue(gamma=sc[0:1] if gam is not None else None, b_post=sc[1:2], skip=skip_d,
+                          relu=1, b_next_pre=sc[2:3], y=y, u_next=un, mask=mask, t_wide=tw)
+        ctx.conv_fwd(desc_of(d), dev(u), dev(w), ep=ep, ws=ws_for(d, eoq.OP_CONV_FWD))
+        t = oo.q_a1(oo.conv_fwd(d, u, w))
+        z = oo.post_conv(t, gam if gam is not None else 128, bpost, skip)
+        yo, mo = oo.relu_q_a2(z)
+        assert np.array_equal(host(tw), t), case
+        assert np.array_equal(host(y), yo), case
+        assert np.array_equal(host(un), oo.pre_bias(yo, bnext)), case
+        bits = np.unpackbits(host(mask).view(np.uint8), bitorder="little")[:n]
+        assert np.array_equal(bits.astype(bool), mo.reshape(-1)), case
+    # shortcut convolution: only the wide Q_a1 output
+    tw = zeros(oshape, torch.int32)
+    ep = ctx.epilogue(relu=0, t_wide=tw)
+    ctx.conv_fwd(desc_of(d), dev(u), dev(w), ep=ep, ws=ws_for(d, eoq.OP_CONV_FWD))
+    assert np.array_equal(host(tw), oo.q_a1(oo.conv_fwd(d, u, w)))
+
+
+@pytest.mark.parametrize("d", CONV_SHAPES[:8], ids=IDS[:8])
+def test_conv_bwd_data(ctx, d):
+    from paper_2105_13890_amd import eoq
+    e = si.uniform_int8(3, "e", (d.N, d.P, d.Q, d.K))
+    w = si.uniform_int8(3, "w", (d.K, d.R, d.S, d.C))
+    dx = zeros((d.N, d.H, d.W, d.C), torch.int32)
+    slot = zeros((4,), torch.int32)
+    ctx.conv_bwd_data(desc_of(d), dev(e), dev(w), dx, slot[0:1], ws_for(d, eoq.OP_CONV_BWD_DATA))
+    want = oo.conv_bwd_data(d, e, w)
+    assert np.array_equal(host(dx), want)
+    assert int(host(slot)[0]) == int(np.abs(want).max())
+
+
+@pytest.mark.parametrize("d", CONV_SHAPES, ids=IDS)
+def test_conv_bwd_weight(ctx, d):
+    from paper_2105_13890_amd import eoq
+    e = si.uniform_int8(4, "e", (d.N, d.P, d.Q, d.K))
+    u = si.uniform_int8(4, "u", (d.N, d.H, d.W, d.C))
+    g = zeros((d.K, d.R, d.S, d.C), torch.int32)
+    slot = zeros((4,), torch.int32)
+    ctx.conv_bwd_weight(desc_of(d), dev(e), dev(u), g, slot[0:1], ws_for(d, eoq.OP_CONV_BWD_WEIGHT))
+    want = oo.conv_bwd_weight(d, e, u)
+    assert np.array_equal(host(g), want)
+    assert int(host(slot)[0]) == int(np.abs(want).max())
+
+
+@pytest.mark.parametrize("n", [1, 15, 16, 4099, 70001])
+def test_quantize_modes(ctx, n):
+    from paper_2105_13890_amd import eoq
+    x = (si.standard_normal(5, "x", (n,)) * 1.7).astype(np.float32)
+    x[0] = 0.5 / 128  # a tie
+    q32 = zeros((n,), torch.int32)
+    ctx.quantize(dev(x), eoq.Q, 0, q32)
+    assert np.array_equal(host(q32), oq.q_code(x))
+    q8 = zeros((n,), torch.int8)
+    ctx.quantize(dev(x), eoq.CQ, -2, q8)
+    assert np.array_equal(host(q8), oq.cq_code(x.astype(np.float64) * 0.25))
+    slot = zeros((1,), torch.int32)
+    for scale in (1.0, 3e-5, 2.0 ** -140, 7e9):
+        xs = (x.astype(np.float64) * scale).astype(np.float32)
+        ctx.quantize(dev(xs), eoq.SQ, 0, q8, slot)
+        c, E = oq.sq_real(xs)
+        assert int(host(slot)[0]) == E and np.array_equal(host(q8), c), scale
+    ctx.quantize(dev(np.zeros(n, dtype=np.float32)), eoq.SQ, 0, q8, slot)
+    assert int(host(slot)[0]) == 0 and not host(q8).any()
+
+
+@pytest.mark.parametrize("n", [16, 48, 16 * 1000 + 16, 16 * 40001])
+def test_relu_bwd_and_sq_passes(ctx, n):
+    from paper_2105_13890_amd import eoq
+    e0 = si.uniform_int8(6, "e0", (n,))
+    maskb = (si.words(6, "mask", n) & np.uint64(1)).astype(bool)
+    t = (si.uniform_int8(6, "t", (n,)).astype(np.int32) * 37)
+    mask = dev(np.packbits(maskb, bitorder="little").view(np.int32) if n % 32 == 0 else
+               np.frombuffer(np.packbits(maskb, bitorder="little").tobytes() + b"\0\0", dtype=np.int32))
+    e1 = zeros((n,), torch.int8)
+    sums = zeros((4,), torch.int64)
+    slots = zeros((8,), torch.int32)
+    ctx.relu_bwd(dev(e0), mask, dev(t), e1, sums[0:1], sums[1:2], slots[0:1])
+    e1o = (e0.astype(np.int64) * maskb).astype(np.int8)
+    assert np.array_equal(host(e1), e1o)
+    assert int(host(sums)[0]) == int(e1o.astype(np.int64).sum())
+    assert int(host(sums)[1]) == int((e1o.astype(np.int64) * t).sum())
+    assert int(host(slots)[0]) == int(np.abs(e1o.astype(np.int64)).max())
+    # Q_e(e1 * gamma)
+    E0 = -11
+    gam = dev(np.array([117], dtype=np.int32))
+    slots[1] = E0
+    out = zeros((n,), torch.int8)
+    ctx.requant_epilogue(eoq.RQ_SQ_GAMMA, n, src_a=e1, gamma=gam, absmax=slots[0:1], exp_in=slots[1:2],
+                         out=out, exp_out=slots[2:3])
+    e3, E3 = oo.sq_error_gamma(e1o, E0, 117)
+    assert np.array_equal(host(out), e3) and int(host(slots)[2]) == E3
+    # Q_e of an int32 accumulator, with the bias-gradient sum and the max code
+    acc = (si.uniform_int8(6, "acc", (n,)).astype(np.int32) * 9173) + si.uniform_int8(6, "acc2", (n,))
+    slots[3] = int(np.abs(acc).max())
+    ctx.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=dev(acc), absmax=slots[3:4], exp_in=slots[1:2], exp_in_off=-7,
+                         out=out, exp_out=slots[4:5], sum_out=sums[2:3], max_code_out=slots[5:6])
+    e4, E4 = oo.sq_acc(acc, E0 - 7)
+    assert np.array_equal(host(out), e4) and int(host(slots)[4]) == E4
+    assert int(host(sums)[2]) == int(e4.astype(np.int64).sum())
+    assert int(host(slots)[5]) == int(np.abs(e4.astype(np.int64)).max())
+    # merge of two errors on different grids
+    ea, eb = si.uniform_int8(6, "ea", (n,)), si.uniform_int8(6, "eb", (n,))
+    for Ea, Eb in ((-12, -12), (-15, -12), (-9, -14)):
+        ex = dev(np.array([Ea, Eb], dtype=np.int32))
+        slots[6] = 0
+        ctx.merge_absmax(dev(ea), ex[0:1], dev(eb), ex[1:2], slots[6:7])
+        ctx.requant_epilogue(eoq.RQ_SQ_MERGE, n, src_a=dev(ea), src_b=dev(eb), exp_in=ex[0:1], exp_b=ex[1:2],
+                             absmax=slots[6:7], out=out, exp_out=slots[7:8])
+        em, Em = oo.merge_errors(ea, Ea, eb, Eb)
+        assert np.array_equal(host(out), em) and int(host(slots)[7]) == Em
+    # all-zero tensors keep their exponent
+    slots[3] = 0
+    ctx.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=zeros((n,), torch.int32), absmax=slots[3:4], exp_in=slots[1:2],
+                         exp_in_off=-7, out=out, exp_out=slots[4:5])
+    assert not host(out).any() and int(host(slots)[4]) == E0 - 7
+
+
+def test_update_int8_and_scalars(ctx):
+    from paper_2105_13890_amd import eoq
+    n = 16 * 777 + 5
+    for trial, (Eg, m, j) in enumerate([(-12, 1, -3), (-9, 1, 0), (-7, 3, 2), (-14, 25, -6), (-20, 1, 4)]):
+        W = si.uniform_int8(trial, "W", (n,))
+        g, _ = oq.sq_int(si.uniform_int8(trial, "g", (n,)).astype(np.int64) * 3, 0)
+        g = g.astype(np.int8)
+        Wd = dev(W)
+        sl = dev(np.array([Eg, m, j], dtype=np.int32))
+        ctx.update_int8(Wd, dev(g), sl[0:1], None, sl[1:3])
+        assert np.array_equal(host(Wd), oo.update_weights(W, g, Eg, m, j)), trial
+    # scalars: one- and two-term gradients
+    scal = np.array([128, 0, -3, 7, 128, 5], dtype=np.int32)
+    sums = np.array([300, -100, 0, 3, 5, -123456789, 40], dtype=np.int64)
+    exps = np.array([-20, -10, -12, -25], dtype=np.int32)
+    entries = [(0, [(0, 0, 0)]), (1, [(1, 0, 0)]), (2, [(2, 0, 0)]), (3, [(3, 1, 0), (4, 2, 0)]),
+               (4, [(5, 3, -7)]), (5, [(6, 2, 0), (3, 1, -1)])]
+    tab = eoq.scalar_grad_table(entries, "cuda")
+    for (m, j) in ((1, -10), (3, -14), (1, 0)):
+        sd = dev(scal.copy())
+        gc, ge = zeros((len(entries),), torch.int32), zeros((len(entries),), torch.int32)
+        lr = dev(np.array([m, j], dtype=np.int32))
+        ctx.update_scalars(sd, tab, len(entries), dev(sums), dev(exps), lr, gc, ge)
+        for i, (param, terms) in enumerate(entries):
+            tl = [(int(sums[s]), int(exps[e]) + off) for s, e, off in terms]
+            gco, geo = oo.scalar_gradient(tl)
+            assert (int(host(gc)[i]), int(host(ge)[i])) == (gco, geo), (i, m, j)
+            assert int(host(sd)[param]) == oo.update_scalar(int(scal[param]), gco, geo, m, j), (i, m, j)
+
+
+def test_pool_gap_broadcast(ctx):
+    N, H, W, Cc = 3, 13, 15, 32
+    a = si.uniform_int8(7, "a", (N, H, W, Cc), -6, 6)
+    yo, arg = oo.maxpool_fwd(a)
+    P, Q = yo.shape[1:3]
+    y, un = zeros(yo.shape, torch.int8), zeros(yo.shape, torch.int8)
+    b = dev(np.array([-4], dtype=np.int32))
+    ctx.maxpool_fwd(dev(a), N, H, W, Cc, 3, 3, 2, 1, y, b, un)
+    assert np.array_equal(host(y), yo) and np.array_equal(host(un), oo.pre_bias(yo, -4))
+    e = si.uniform_int8(7, "e", yo.shape)
+    d = zeros(a.shape, torch.int32)
+    slot = zeros((1,), torch.int32)
+    ctx.maxpool_bwd(dev(a), dev(e), N, H, W, Cc, 3, 3, 2, 1, d, slot)
+    want = oo.maxpool_bwd(e, arg, a.shape)
+    assert np.array_equal(host(d), want) and int(host(slot)[0]) == int(np.abs(want).max())
+    s = zeros((N, Cc), torch.int32)
+    ctx.gap_sum(dev(a), N, H * W, Cc, s)
+    assert np.array_equal(host(s), a.astype(np.int64).sum(axis=(1, 2)))
+    codes = si.uniform_int8(7, "codes", (N, Cc))
+    eb = zeros((N, H, W, Cc), torch.int8)
+    ctx.broadcast_hw(dev(codes), N, H * W, Cc, eb)
+    assert np.array_equal(host(eb), np.broadcast_to(codes[:, None, None, :], eb.shape))
+
+
+@pytest.mark.parametrize("N,F,J,HW", [(5, 64, 10, 64), (19, 200, 37, 49)])
+def test_head_bit_exact(ctx, N, F, J, HW):
+    gap = (si.words(8, "gap", N * F) % np.uint64(127 * HW)).astype(np.int32).reshape(N, F)
+    Wfc = si.standard_normal(8, "Wfc", (J, F)) * 0.2
+    bfc = si.standard_normal(8, "bfc", (J,)) * 0.1
+    lab = si.labels(8, "lab", N, J)
+    m, j = 3, 5
+    loss_o, d_o, dW_o, db_o, logits_o = oo.head(gap, Wfc, bfc, lab, HW)
+    Wd, bd = dev(Wfc), dev(bfc)
+    loss, d, logits = zeros((1,), torch.float64), zeros((N, F), torch.float32), zeros((N, J), torch.float64)
+    ws = zeros((ctx.head_workspace_bytes(N, F, J) // 8 + 1,), torch.float64)
+    lr = dev(np.array([m, j], dtype=np.int32))
+    ctx.head_fwd_bwd(N, F, J, HW, dev(gap), Wd, bd, dev(lab), lr, loss, d, logits, ws)
+    assert np.array_equal(host(logits), logits_o)
+    assert np.array_equal(host(d), d_o)                      # bit-exact: it feeds the integer chain
+    assert float(host(loss)[0]) == pytest.approx(loss_o, rel=1e-12)
+    lrf = m * 2.0 ** -j
+    assert np.array_equal(host(Wd), Wfc - lrf * dW_o)
+    assert np.array_equal(host(bd), bfc - lrf * db_o)
