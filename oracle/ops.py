@@ -191,7 +191,7 @@ def merge_errors(ea, Ea: int, eb, Eb: int, max_gap: int = 24):
     return codes.astype(np.int8), Eo
 
 
-def scalar_gradient(terms, max_gap: int = 40):
+def scalar_gradient(terms, max_gap: int = 24):
     """Gradient of a scalar parameter (Eq.4): the sum over all elements, then
     Q_g of the one-element tensor.  `terms` = [(S, E), ...] integer sums with
     their exponents (two terms when two convolutions share the biased input)."""
@@ -223,4 +223,6 @@ def update_weights(W, g_codes, Eg, lr_m, lr_j) -> np.ndarray:
 def update_scalar(code: int, g_code: int, Eg: int, lr_m: int, lr_j: int) -> int:
     """Bias / multiplier codes use the unclamped basic quantiser (Eq.10)."""
     d = update_delta(np.array([g_code]), Eg, lr_m, lr_j)
-    return int(code) - int(d[0])
+    new = int(code) - int(d[0])
+    assert -2 ** 31 < new < 2 ** 31, "scalar code left the int32 range it is stored in"
+    return new

@@ -1,0 +1,530 @@
+"""Sequencing of libeoq calls into whole full-int8 training steps of a Fixup residual network.
+
+This module only decides WHICH C-ABI call runs on WHICH buffer; all arithmetic happens in the
+library's kernels.  Layer arithmetic: Eq.2 (forward), Eq.3 (errors), Eq.4 (parameter gradients),
+Eq.8-13 (quantisation strategies, update); block topology: the Fixup residual block of Section 3.1
+(one multiplier per block, a bias before every convolution and every ReLU, a strided 1x1
+convolution on the biased block input when the shape changes).  Everything a step needs stays
+on the device: exponents, abs-max statistics, scalar-gradient sums and the learning rate live in
+device slots, so a step enqueues kernels without a single host synchronisation and can be
+captured into a HIP graph.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+
+import numpy as np
+import torch
+
+import seeded_inputs as si
+
+from . import eoq
+
+
+@dataclass
+class Unit:
+    """One Fixup layer (Eq.2) and the buffers it owns."""
+    name: str
+    desc: eoq.ConvDesc
+    b_pre: str | None
+    gamma: str | None
+    b_post: str | None
+    relu: bool = True
+    w: torch.Tensor = None            # int8 KRSC
+    u: torch.Tensor = None            # int8 biased input x1 (what the convolution reads)
+    mask: torch.Tensor = None         # ReLU bits
+    t: torch.Tensor = None            # wide Q_a1 output (multiplier layers, shortcut convolutions)
+    y: torch.Tensor = None            # int8 output, kept only where a later block adds it back
+
+    @property
+    def out_shape(self):
+        d = self.desc
+        return (d.N, d.P, d.Q, d.K)
+
+    @property
+    def in_shape(self):
+        d = self.desc
+        return (d.N, d.H, d.W, d.C)
+
+
+@dataclass
+class Block:
+    name: str
+    units: list
+    ds: Unit | None
+
+
+class _Slots:
+    """Named int32 / int64 device slots (exponents, abs-max values, sums)."""
+
+    def __init__(self):
+        self.names32: dict[str, int] = {}
+        self.names64: dict[str, int] = {}
+
+    def i32(self, name):
+        return self.names32.setdefault(name, len(self.names32))
+
+    def i64(self, name):
+        return self.names64.setdefault(name, len(self.names64))
+
+
+class FixupNet:
+    def __init__(self, cfg: dict, batch: int, seed: int = 0, trace: bool = False):
+        assert torch.cuda.is_available(), "libeoq needs the GPU; there is no CPU path"
+        self.cfg, self.N, self.seed, self.tracing = dict(cfg), batch, seed, trace
+        self.dev = torch.device("cuda")
+        self.ctx = eoq.Context()
+        self.trace: dict[str, object] = {}
+        bt = cfg["block"]
+        m = 2 if bt == "basic" else 3
+        L = int(sum(cfg["depths"]))
+        alpha = float(L) ** (-1.0 / (2 * m - 2))          # Eq.1
+        N = batch
+        hw, ch = cfg["in_hw"], cfg["in_ch"]
+        self.scal_names: list[str] = []
+        self.units: list[Unit] = []
+
+        def D(h, c, k, r, st, pad):
+            return eoq.ConvDesc(N, h, h, c, k, r, r, st, pad)
+
+        self.stem = None
+        self.pool = False
+        if cfg["stem"] == "cifar":
+            w0 = cfg["widths"][0]
+            self.stem = Unit("stem", D(hw, ch, w0, 3, 1, 1), None, None, "stem.b")
+            ch = w0
+        elif cfg["stem"] == "imagenet":
+            w0 = cfg["widths"][0]
+            self.stem = Unit("stem", D(hw, ch, w0, 7, 2, 3), None, None, "stem.b")
+            self.pool = True
+            self.pool_in_hw = self.stem.desc.P
+            hw = (self.pool_in_hw + 2 - 3) // 2 + 1
+            ch = w0
+        self.blocks: list[Block] = []
+        for s_i, (depth, width) in enumerate(zip(cfg["depths"], cfg["widths"])):
+            for b_i in range(depth):
+                stride = 2 if (b_i == 0 and s_i > 0) else 1
+                out_ch = width if bt == "basic" else 4 * width
+                nm = f"s{s_i}b{b_i}"
+                if bt == "basic":
+                    c1 = Unit(nm + ".c1", D(hw, ch, width, 3, stride, 1), nm + ".b1a", None, nm + ".b1b")
+                    c2 = Unit(nm + ".c2", D(c1.desc.P, width, width, 3, 1, 1), nm + ".b2a", nm + ".g", nm + ".b2b")
+                    units = [c1, c2]
+                else:
+                    c1 = Unit(nm + ".c1", D(hw, ch, width, 1, 1, 0), nm + ".b1a", None, nm + ".b1b")
+                    c2 = Unit(nm + ".c2", D(hw, width, width, 3, stride, 1), nm + ".b2a", None, nm + ".b2b")
+                    c3 = Unit(nm + ".c3", D(c2.desc.P, width, out_ch, 1, 1, 0), nm + ".b3a", nm + ".g", nm + ".b3b")
+                    units = [c1, c2, c3]
+                ds = None
+                if stride != 1 or ch != out_ch:
+                    ds = Unit(nm + ".ds", D(hw, ch, out_ch, 1, stride, 0), None, None, None, relu=False)
+                self.blocks.append(Block(nm, units, ds))
+                hw, ch = units[-1].desc.P, out_ch
+        self.out_hw, self.out_ch = hw, ch
+        self.classes = cfg["classes"]
+
+        # ---- parameters ------------------------------------------------------------------------
+        all_units = ([self.stem] if self.stem else []) + [u for b in self.blocks for u in b.units + ([b.ds] if b.ds else [])]
+        self.all_units = all_units
+        for u in all_units:
+            for s in (u.b_pre, u.gamma, u.b_post):
+                if s and s not in self.scal_names:
+                    self.scal_names.append(s)
+        self.scal_idx = {n: i for i, n in enumerate(self.scal_names)}
+        init = np.array([128 if n.endswith(".g") else 0 for n in self.scal_names] + [0], dtype=np.int32)
+        self.scal = torch.from_numpy(init).to(self.dev)            # multiplier = 1 (code 128), biases = 0
+        branch = {u.name for b in self.blocks for u in b.units}
+        for u in all_units:
+            d = u.desc
+            z = si.standard_normal(seed, u.name + ".w", (d.K, d.R, d.S, d.C))
+            std = math.sqrt(2.0 / (d.C * d.R * d.S)) * (alpha if u.name in branch else 1.0)
+            wf = torch.from_numpy((z * std).astype(np.float32)).to(self.dev)
+            u.w = torch.empty((d.K, d.R, d.S, d.C), dtype=torch.int8, device=self.dev)
+            self.ctx.quantize(wf, eoq.CQ, 0, u.w)                  # Q_w = CQ (Eq.8)
+        if self.classes:
+            z = si.standard_normal(seed, "fc.w", (self.classes, ch))
+            self.Wfc = torch.from_numpy(z * math.sqrt(2.0 / ch)).to(self.dev)
+            self.bfc = torch.zeros(self.classes, dtype=torch.float64, device=self.dev)
+
+        # ---- buffers ---------------------------------------------------------------------------
+        i8 = lambda shape: torch.empty(shape, dtype=torch.int8, device=self.dev)
+        i32 = lambda shape: torch.empty(shape, dtype=torch.int32, device=self.dev)
+        for u in all_units:
+            n_out = int(np.prod(u.out_shape))
+            if u.relu:
+                u.mask = i32(((n_out + 31) // 32,))
+            if u.gamma or not u.relu:
+                u.t = i32(u.out_shape)
+        if self.stem:
+            self.a0 = i8(self.stem.in_shape)
+            self.stem.u = self.a0
+            if self.pool:
+                self.prepool = i8(self.stem.out_shape)
+        for bi, b in enumerate(self.blocks):
+            b.units[0].u = i8(b.units[0].in_shape)
+            if b.ds:
+                b.ds.u = b.units[0].u
+            for u in b.units[1:]:
+                u.u = i8(u.in_shape)
+            b.a_in = None if b.ds else i8(b.units[0].in_shape)       # block input kept only as an identity shortcut
+        self.y_out = i8(self.blocks[-1].units[-1].out_shape)
+        max_act = max(max(int(np.prod(u.out_shape)), int(np.prod(u.in_shape))) for u in all_units)
+        max_w = max(u.w.numel() for u in all_units)
+        self.ebuf = [i8((max_act,)) for _ in range(4)]
+        self.dacc = i32((max_act,))
+        self.gacc = i32((max_w,))
+        self.gq = i8((max_w,))
+        ws_bytes = 16
+        for u in all_units:
+            for op in (eoq.OP_CONV_FWD, eoq.OP_CONV_BWD_DATA, eoq.OP_CONV_BWD_WEIGHT):
+                ws_bytes = max(ws_bytes, eoq.Context.workspace_bytes(u.desc, op))
+        self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=self.dev)
+        # ---- slots -------------------------------------------------------------------------------
+        self.sl = _Slots()
+        self._plan_slots()
+        self.slots32 = torch.zeros((len(self.sl.names32) + 4,), dtype=torch.int32, device=self.dev)
+        self.sums64 = torch.zeros((len(self.sl.names64) + 4,), dtype=torch.int64, device=self.dev)
+        self.lr = torch.zeros((2,), dtype=torch.int32, device=self.dev)
+        self.sgrad_tab = eoq.scalar_grad_table(self.sgrad_entries, self.dev)
+        self.g_code = i32((len(self.sgrad_entries) + 1,))
+        self.g_exp = i32((len(self.sgrad_entries) + 1,))
+        if self.classes:
+            F, J = self.out_ch, self.classes
+            self.gap = i32((N, F))
+            self.loss = torch.zeros((1,), dtype=torch.float64, device=self.dev)
+            self.d32 = torch.empty((N, F), dtype=torch.float32, device=self.dev)
+            self.logits = torch.empty((N, J), dtype=torch.float64, device=self.dev)
+            self.head_codes = i8((N, F))
+            self.head_ws = torch.empty((eoq.Context.head_workspace_bytes(N, F, J) // 8 + 1,), dtype=torch.float64,
+                                       device=self.dev)
+            self.x_in = torch.empty(self.stem.in_shape, dtype=torch.float32, device=self.dev)
+            self.labels = torch.zeros((N,), dtype=torch.int32, device=self.dev)
+        torch.cuda.synchronize()
+
+    # ------------------------------------------------------------------------------------------
+    def _plan_slots(self):
+        """Name every device slot once and build the scalar-gradient table (Eq.4 for scalars)."""
+        sl = self.sl
+        entries: dict[str, list] = {}
+
+        def term(param, sum_name, exp_name, off):
+            entries.setdefault(param, []).append((sl.i64(sum_name), sl.i32(exp_name), off))
+
+        if self.classes:
+            e_name = "head.E"
+        else:
+            e_name = "ext.E"
+        sl.i32(e_name)
+        self.E_top = e_name
+        for b in reversed(self.blocks):
+            E0 = e_name
+            for i in range(len(b.units) - 1, -1, -1):
+                u = b.units[i]
+                u.E0 = e_name
+                term(u.b_post, u.name + ".S_e1", e_name, 0)
+                if u.gamma:
+                    term(u.gamma, u.name + ".S_e1t", e_name, -7)
+                    u.E3 = u.name + ".E3"
+                else:
+                    u.E3 = e_name
+                u.E4 = u.name + ".E4"
+                term(u.b_pre, u.name + ".S_e4", u.E4, 0)
+                for nm in (u.E3, u.E4, u.name + ".Eg", u.name + ".M_e1", u.name + ".M_D", u.name + ".M_G",
+                           u.name + ".gmax"):
+                    sl.i32(nm)
+                e_name = u.E4
+            if b.ds:
+                d = b.ds
+                d.E0 = d.E3 = E0
+                d.E4 = d.name + ".E4"
+                term(b.units[0].b_pre, d.name + ".S_e4", d.E4, 0)
+                for nm in (d.E4, d.name + ".Eg", d.name + ".M_D", d.name + ".M_G", d.name + ".gmax"):
+                    sl.i32(nm)
+            sl.i32(b.name + ".M_in")
+            e_name = b.name + ".E_in"
+            sl.i32(e_name)
+        if self.stem:
+            s = self.stem
+            if self.pool:
+                sl.i32("pool.M")
+                sl.i32("pool.E")
+                e_name = "pool.E"
+            s.E0 = s.E3 = e_name
+            term(s.b_post, s.name + ".S_e1", e_name, 0)
+            for nm in (s.name + ".Eg", s.name + ".M_e1", s.name + ".M_G", s.name + ".gmax"):
+                sl.i32(nm)
+        self.sgrad_params = list(entries.keys())
+        self.sgrad_entries = [(self.scal_idx[p], entries[p]) for p in self.sgrad_params]
+
+    def s32(self, name):
+        i = self.sl.names32[name]
+        return self.slots32[i:i + 1]
+
+    def s64(self, name):
+        i = self.sl.names64[name]
+        return self.sums64[i:i + 1]
+
+    def sc(self, name):
+        if name is None:
+            return None
+        i = self.scal_idx[name]
+        return self.scal[i:i + 1]
+
+    def _rec(self, name, t):
+        if self.tracing:
+            self.trace[name] = t.detach().clone()
+
+    def set_lr(self, m: int, j: int):
+        self.lr.copy_(torch.tensor([m, j], dtype=torch.int32))
+
+    # ------------------------------------------------------------------------------------------ forward
+    def _unit_fwd(self, u: Unit, skip=None, y=None, u_next=None, b_next=None):
+        c = self.ctx
+        if not u.relu:
+            ep = c.epilogue(relu=0, t_wide=u.t)
+        else:
+            ep = c.epilogue(gamma=self.sc(u.gamma), b_post=self.sc(u.b_post), skip=skip, relu=1,
+                            b_next_pre=self.sc(b_next), y=y, u_next=u_next, mask=u.mask, t_wide=u.t)
+        c.conv_fwd(u.desc, u.u, u.w, ep=ep, ws=self.ws)
+        if self.tracing:
+            self._rec(u.name + ".u", u.u)
+            if u.t is not None:
+                self._rec(u.name + ".t", u.t)
+            if u.relu:
+                self._rec(u.name + ".mask", u.mask)
+                if y is not None:
+                    self._rec(u.name + ".y", y)
+
+    def _forward_blocks(self):
+        for bi, b in enumerate(self.blocks):
+            nxt = self.blocks[bi + 1] if bi + 1 < len(self.blocks) else None
+            if b.ds:
+                self._unit_fwd(b.ds)
+            for i, u in enumerate(b.units):
+                last = i == len(b.units) - 1
+                if not last:
+                    n_u = b.units[i + 1]
+                    self._unit_fwd(u, u_next=n_u.u, b_next=n_u.b_pre, y=self._dbg_y(u))
+                else:
+                    skip = b.ds.t if b.ds else b.a_in
+                    if nxt is not None:
+                        self._unit_fwd(u, skip=skip, y=nxt.a_in if nxt.a_in is not None else self._dbg_y(u),
+                                       u_next=nxt.units[0].u, b_next=nxt.units[0].b_pre)
+                    else:
+                        self._unit_fwd(u, skip=skip, y=self.y_out)
+
+    def _dbg_y(self, u):
+        """Unbiased int8 output of an inner layer: only materialised when tracing (tests compare it)."""
+        if not self.tracing:
+            return None
+        return torch.empty(u.out_shape, dtype=torch.int8, device=self.dev)
+
+    def forward(self):
+        """x_in (fp32 NHWC) -> Q input, stem, (pool), blocks, pooled integer sums."""
+        c = self.ctx
+        b0 = self.blocks[0]
+        c.quantize(self.x_in, eoq.CQ, -2, self.a0)                  # network input: CQ(x / 4)
+        self._rec("in.a", self.a0)
+        s = self.stem
+        if self.pool:
+            self._unit_fwd(s, y=self.prepool)
+            self._rec("stem.prepool", self.prepool)
+            d = s.desc
+            yb = b0.a_in if b0.a_in is not None else (torch.empty(b0.units[0].in_shape, dtype=torch.int8, device=self.dev)
+                                                      if self.tracing else None)
+            c.maxpool_fwd(self.prepool, d.N, d.P, d.Q, d.K, 3, 3, 2, 1, yb, self.sc(b0.units[0].b_pre), b0.units[0].u)
+            if yb is not None:
+                self._rec("pool.y", yb)
+        else:
+            self._unit_fwd(s, y=b0.a_in if b0.a_in is not None else self._dbg_y(s), u_next=b0.units[0].u,
+                           b_next=b0.units[0].b_pre)
+        self._forward_blocks()
+        hw = self.out_hw * self.out_hw
+        c.gap_sum(self.y_out, self.N, hw, self.out_ch, self.gap)
+        self._rec("gap.sum", self.gap)
+
+    # ------------------------------------------------------------------------------------------ backward
+    def _grad_and_update(self, u: Unit, e3):
+        """g_w = Q_g(e3 * x1) (Eq.4, Eq.12) and W <- Q_w(W - Q_u(lr g)) (Eq.13)."""
+        c = self.ctx
+        n = u.w.numel()
+        G = self.gacc[:n]
+        c.conv_bwd_weight(u.desc, e3, u.u, G, self.s32(u.name + ".M_G"), self.ws)
+        g = self.gq[:n]
+        c.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=G, absmax=self.s32(u.name + ".M_G"), exp_in=self.s32(u.E3),
+                           exp_in_off=-7, out=g, exp_out=self.s32(u.name + ".Eg"),
+                           max_code_out=self.s32(u.name + ".gmax"))
+        if self.tracing:
+            self._rec(u.name + ".G", G.view(u.w.shape))
+            self._rec(u.name + ".gw", g.view(u.w.shape))
+        return g
+
+    def _unit_bwd(self, u: Unit, e0, bufs, need_dx=True):
+        """Eq.3 / Eq.4 for one layer; e0 is overwritten by e1.  Returns (e4 buffer or None, e1)."""
+        c = self.ctx
+        n_out = int(np.prod(u.out_shape))
+        e1 = e0
+        if u.relu:
+            c.relu_bwd(e0[:n_out], u.mask, u.t if u.gamma else None, e1[:n_out], self.s64(u.name + ".S_e1"),
+                       self.s64(u.name + ".S_e1t") if u.gamma else None, self.s32(u.name + ".M_e1"))
+        if u.gamma:
+            e3 = bufs.pop()
+            c.requant_epilogue(eoq.RQ_SQ_GAMMA, n_out, src_a=e1[:n_out], gamma=self.sc(u.gamma),
+                               absmax=self.s32(u.name + ".M_e1"), exp_in=self.s32(u.E0), out=e3[:n_out],
+                               exp_out=self.s32(u.E3))
+        else:
+            e3 = e1
+        if self.tracing:
+            self._rec(u.name + ".e3", e3[:n_out].view(u.out_shape))
+        g = self._grad_and_update(u, e3[:n_out])
+        e4 = None
+        if need_dx:
+            n_in = int(np.prod(u.in_shape))
+            Dacc = self.dacc[:n_in]
+            c.conv_bwd_data(u.desc, e3[:n_out], u.w, Dacc, self.s32(u.name + ".M_D"), self.ws)
+            e4 = bufs.pop()
+            c.requant_epilogue(eoq.RQ_SQ_ACC, n_in, acc=Dacc, absmax=self.s32(u.name + ".M_D"), exp_in=self.s32(u.E3),
+                               exp_in_off=-7, out=e4[:n_in], exp_out=self.s32(u.E4), sum_out=self.s64(u.name + ".S_e4"))
+            if self.tracing:
+                self._rec(u.name + ".e4", e4[:n_in].view(u.in_shape))
+        # all uses of the old weights are enqueued: update them
+        c.update_int8(u.w, g, self.s32(u.name + ".Eg"), self.s32(u.name + ".gmax"), self.lr)
+        if u.gamma:
+            bufs.append(e3)
+        return e4, e1
+
+    def _backward_blocks(self, e, bufs):
+        """e: buffer holding the error at the last block's output (exponent slot self.E_top)."""
+        c = self.ctx
+        for b in reversed(self.blocks):
+            last = b.units[-1]
+            e4, e_sk = self._unit_bwd(last, e, bufs)            # e now holds e1 of the last layer = shortcut error
+            E_sk = last.E0
+            cur = e4
+            for u in reversed(b.units[:-1]):
+                nxt, _ = self._unit_bwd(u, cur, bufs)
+                bufs.append(cur)
+                cur = nxt
+            first = b.units[0]
+            n_in = int(np.prod(first.in_shape))
+            if b.ds:
+                e4d, _ = self._unit_bwd(b.ds, e_sk, bufs)
+                other, E_other = e4d, b.ds.E4
+            else:
+                other, E_other = e_sk, E_sk
+            c.merge_absmax(cur[:n_in], self.s32(first.E4), other[:n_in], self.s32(E_other), self.s32(b.name + ".M_in"))
+            out = cur
+            c.requant_epilogue(eoq.RQ_SQ_MERGE, n_in, src_a=cur[:n_in], src_b=other[:n_in], exp_in=self.s32(first.E4),
+                               exp_b=self.s32(E_other), absmax=self.s32(b.name + ".M_in"), out=out[:n_in],
+                               exp_out=self.s32(b.name + ".E_in"))
+            if b.ds:
+                bufs.append(e4d)
+            bufs.append(e_sk)
+            if self.tracing:
+                self._rec(b.name + ".e_in", out[:n_in].view(first.in_shape))
+            e = out
+        return e
+
+    def _backward_stem(self, e, bufs):
+        c = self.ctx
+        s = self.stem
+        d = s.desc
+        if self.pool:
+            n = int(np.prod(s.out_shape))
+            Dacc = self.dacc[:n]
+            c.maxpool_bwd(self.prepool, e, d.N, d.P, d.Q, d.K, 3, 3, 2, 1, Dacc, self.s32("pool.M"))
+            e2 = bufs.pop()
+            c.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=Dacc, absmax=self.s32("pool.M"),
+                               exp_in=self.s32(self.blocks[0].name + ".E_in"), out=e2[:n], exp_out=self.s32("pool.E"))
+            bufs.append(e)
+            e = e2
+            if self.tracing:
+                self._rec("pool.e", e[:n].view(s.out_shape))
+        self._unit_bwd(s, e, bufs, need_dx=False)
+        bufs.append(e)
+
+    def _update_scalars(self):
+        self.ctx.update_scalars(self.scal, self.sgrad_tab, len(self.sgrad_entries), self.sums64, self.slots32, self.lr,
+                                self.g_code, self.g_exp)
+
+    # ------------------------------------------------------------------------------------------ whole steps
+    def _zero_stats(self):
+        self.ctx.fill_zero(self.slots32)
+        self.ctx.fill_zero(self.sums64)
+
+    def enqueue_step(self):
+        """One full training step on the resident batch (x_in, labels): forward, head, backward, update.
+        Only enqueues kernels; safe to capture into a HIP graph."""
+        c = self.ctx
+        self._zero_stats()
+        self.forward()
+        N, F, J = self.N, self.out_ch, self.classes
+        hw = self.out_hw * self.out_hw
+        c.head_fwd_bwd(N, F, J, hw, self.gap, self.Wfc, self.bfc, self.labels, self.lr, self.loss, self.d32,
+                       self.logits, self.head_ws)
+        c.quantize(self.d32, eoq.SQ, 0, self.head_codes, self.s32("head.E"))     # Q_e on the head's error
+        bufs = list(self.ebuf)
+        e = bufs.pop()
+        n_out = N * hw * F
+        c.broadcast_hw(self.head_codes, N, hw, F, e[:n_out])
+        if self.tracing:
+            self._rec("head.logits", self.logits)
+            self._rec("head.d", self.d32)
+            self._rec("head.e", e[:n_out].view(self.blocks[-1].units[-1].out_shape))
+        e = self._backward_blocks(e, bufs)
+        self._backward_stem(e, bufs)
+        self._update_scalars()
+        if self.tracing:
+            self._rec("slots32", self.slots32)
+            self._rec("g_code", self.g_code)
+            self._rec("g_exp", self.g_exp)
+
+    def step(self, x_f32: np.ndarray | torch.Tensor, labels, lr_m: int, lr_j: int) -> float:
+        """Convenience wrapper: upload a batch, run one step, return the loss (synchronises)."""
+        self.trace = {}
+        xt = torch.as_tensor(x_f32)
+        self.x_in.copy_(xt.to(self.dev, non_blocking=False))
+        self.labels.copy_(torch.as_tensor(labels).to(self.dev))
+        self.set_lr(lr_m, lr_j)
+        self.enqueue_step()
+        torch.cuda.synchronize()
+        return float(self.loss.item())
+
+    def block_step(self, a: np.ndarray, e0: np.ndarray, E0: int, lr_m: int, lr_j: int):
+        """A lone residual block (no stem, no head): int8 input codes, int8 error at the output with exponent E0."""
+        self.trace = {}
+        c = self.ctx
+        b0 = self.blocks[0]
+        self.set_lr(lr_m, lr_j)
+        self._zero_stats()
+        at = torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
+        if b0.a_in is not None:
+            b0.a_in.copy_(at)
+        c.pre_bias(at, self.sc(b0.units[0].b_pre), b0.units[0].u)            # Eq.2 line x1
+        self._forward_blocks()
+        bufs = list(self.ebuf)
+        e = bufs.pop()
+        n = e0.size
+        e[:n].copy_(torch.from_numpy(np.ascontiguousarray(e0)).to(self.dev).view(-1))
+        self.s32(self.E_top).fill_(E0)
+        e = self._backward_blocks(e, bufs)
+        self._update_scalars()
+        if self.tracing:
+            self._rec("slots32", self.slots32)
+            self._rec("g_code", self.g_code)
+            self._rec("g_exp", self.g_exp)
+        torch.cuda.synchronize()
+        n_in = int(np.prod(b0.units[0].in_shape))
+        return self.y_out, e[:n_in].view(b0.units[0].in_shape)
+
+    # ------------------------------------------------------------------------------------------ inspection
+    def slot_value(self, name) -> int:
+        return int(self.slots32[self.sl.names32[name]].item())
+
+    def scalars(self) -> dict:
+        v = self.scal.cpu().numpy()
+        return {n: int(v[i]) for n, i in self.scal_idx.items()}
+
+    def status(self) -> int:
+        return self.ctx.status()

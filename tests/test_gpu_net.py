@@ -1,0 +1,102 @@
+"""GPU parity of whole training steps: every tensor the HIP path produces (activations, masks,
+errors, gradients, exponents, updated parameters) against the CPU oracle, bit for bit; loss to 1e-5."""
+import numpy as np
+import pytest
+
+import seeded_inputs as si
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+from oracle.net import Net as OracleNet        # noqa: E402
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def compare_traces(gnet, onet, tag=""):
+    """Every name both sides recorded must agree exactly."""
+    T, G = onet.trace, gnet.trace
+    n_cmp = 0
+    sl = host(G["slots32"])
+    for name, want in T.items():
+        if isinstance(want, np.ndarray):
+            if name not in G:
+                continue
+            got = host(G[name])
+            if name.endswith(".mask"):
+                got = np.unpackbits(got.view(np.uint8), bitorder="little")[:want.size].astype(bool).reshape(want.shape)
+            if name in ("head.logits", "head.d"):
+                assert np.array_equal(got, want), (tag, name)
+            else:
+                assert got.shape == want.shape, (tag, name, got.shape, want.shape)
+                assert np.array_equal(got.astype(np.int64), want.astype(np.int64)), (tag, name)
+            n_cmp += 1
+        elif name.endswith((".E3", ".E4", ".Eg", ".E_in")) or name in ("head.E", "pool.E"):
+            key = name
+            if name.endswith(".E3"):
+                unit = name[:-3]
+                key = next(u for u in gnet.all_units if u.name == unit).E3
+            assert int(sl[gnet.sl.names32[key]]) == want, (tag, name)
+            n_cmp += 1
+    # scalar gradients
+    gc, ge = host(G["g_code"]), host(G["g_exp"])
+    for i, p in enumerate(gnet.sgrad_params):
+        assert int(gc[i]) == T[p + ".gs"] and int(ge[i]) == T[p + ".Egs"], (tag, p)
+    return n_cmp
+
+
+def compare_params(gnet, onet, tag=""):
+    for u in gnet.all_units:
+        assert np.array_equal(host(u.w), onet.W[u.name]), (tag, u.name)
+    assert gnet.scalars() == {k: onet.scal[k] for k in gnet.scalars()}, tag
+    if gnet.classes:
+        assert np.array_equal(host(gnet.Wfc), onet.Wfc), tag
+        assert np.array_equal(host(gnet.bfc), onet.bfc), tag
+
+
+def changed_fraction(before, after):
+    ch = sum(int((after[k] != before[k]).sum()) for k in before)
+    return ch / sum(v.size for v in before.values())
+
+
+def test_lone_block_config(request):
+    """One Fixup basic block 16->16 on 8x32x32x16: one full fwd + bwd + int8 update, seed 0."""
+    from paper_2105_13890_amd.net import FixupNet
+    cfg = si.WORKLOADS["block16"]
+    N = 8
+    a = si.uniform_int8(0, "block.a", (N, 32, 32, 16))
+    e0 = si.uniform_int8(0, "block.e0", (N, 32, 32, 16))
+    g, o = FixupNet(cfg, N, seed=0, trace=True), OracleNet(cfg, N, seed=0)
+    compare_params(g, o, "init")
+    W0 = {k: v.copy() for k, v in o.W.items()}
+    for step, (m, j) in enumerate([(1, 10), (3, 9)]):
+        yo, eo, Eo = o.block_step(a, e0, -7, m, j)
+        yg, eg = g.block_step(a, e0, -7, m, j)
+        assert np.array_equal(host(yg), yo)
+        assert np.array_equal(host(eg), eo) and g.slot_value("s0b0.E_in") == Eo
+        assert compare_traces(g, o, f"step{step}") > 10
+        compare_params(g, o, f"step{step}")
+        assert g.status() == 0
+    assert changed_fraction(W0, o.W) > 0.01
+
+
+@pytest.mark.parametrize("wl,N,steps,lr", [("tiny_basic", 4, 3, (1, 1)), ("tiny_bottleneck", 3, 3, (3, 2)),
+                                           ("resnet20", 128, 2, (1, -2))])
+def test_network_steps(wl, N, steps, lr):
+    from paper_2105_13890_amd.net import FixupNet
+    cfg = si.WORKLOADS[wl]
+    g, o = FixupNet(cfg, N, seed=0, trace=True), OracleNet(cfg, N, seed=0)
+    compare_params(g, o, "init")
+    W0 = {k: v.copy() for k, v in o.W.items()}
+    for step in range(steps):
+        x = si.batch_images(0, step, N, cfg["in_hw"])
+        lab = si.batch_labels(0, step, N, cfg["classes"])
+        lo = o.step(x, lab, *lr)
+        lg = g.step(x, lab, *lr)
+        assert lg == pytest.approx(lo, rel=1e-5)
+        assert compare_traces(g, o, f"{wl} step{step}") > 20
+        compare_params(g, o, f"{wl} step{step}")
+        assert g.status() == 0
+    assert changed_fraction(W0, o.W) > 0.01, "test would be vacuous: no weight code moved"
