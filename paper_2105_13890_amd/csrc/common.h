@@ -109,5 +109,34 @@ __device__ __forceinline__ void atomic_add_i64(int64_t *p, int64_t v)
     atomicAdd((unsigned long long *)p, (unsigned long long)v);
 }
 
+// ---- block-level combination (blocks of up to 256 threads = 4 waves): one atomic per block ----
+__device__ __forceinline__ void block_atomic_max_i32(int v, int32_t *slot)
+{
+    __shared__ int sm_max[4];
+    v = wave_max_i32(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    if (lane == 0) sm_max[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < nw; ++i) v = sm_max[i] > v ? sm_max[i] : v;
+        if (v) atomicMax(slot, v);
+    }
+    __syncthreads();   // the staging array may be reused by the next call
+}
+
+__device__ __forceinline__ void block_atomic_add_i64(int64_t v, int64_t *slot)
+{
+    __shared__ int64_t sm_sum[4];
+    v = wave_sum_i64(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    if (lane == 0) sm_sum[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < nw; ++i) v += sm_sum[i];
+        if (v) atomic_add_i64(slot, v);
+    }
+    __syncthreads();
+}
+
 static inline int conv_out_dim(int in, int pad, int k, int st) { return (in + 2 * pad - k) / st + 1; }
 static inline size_t round_up(size_t v, size_t m) { return (v + m - 1) / m * m; }

@@ -289,10 +289,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
         }
         __syncthreads();
     }
-    if (EPI == EPI_ACC && p.absmax) {
-        mx = wave_max_i32(mx);
-        if (lane == 0 && mx) atomicMax(p.absmax, mx);
-    }
+    if (EPI == EPI_ACC && p.absmax) block_atomic_max_i32(mx, p.absmax);
 }
 
 // ---- small layout kernels -------------------------------------------------------------------

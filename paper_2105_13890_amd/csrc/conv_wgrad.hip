@@ -231,8 +231,7 @@ __global__ void wgrad_finalize_kernel(const int32_t *part, size_t part_stride, i
         int ai = a > 2147483647LL ? 2147483647 : (int)a;
         mx = ai > mx ? ai : mx;
     }
-    mx = wave_max_i32(mx);
-    if ((threadIdx.x & 63) == 0 && mx) atomicMax(absmax, mx);
+    block_atomic_max_i32(mx, absmax);
     if (bad) atomicOr(status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);
 }
 

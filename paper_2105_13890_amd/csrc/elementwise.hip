@@ -11,7 +11,7 @@
 namespace {
 
 constexpr int EW_THREADS = 256;
-constexpr unsigned EW_MAX_BLOCKS = 256 * 8;
+constexpr unsigned EW_MAX_BLOCKS = 256 * 4;
 
 inline unsigned ew_blocks(size_t n_vec)
 {
@@ -161,14 +161,9 @@ __global__ void relu_bwd_kernel(const int8_t *e0, const uint16_t *mask16, const 
         mx = ae > mx ? ae : mx;
         if (t) st += (int64_t)e * (int64_t)t[j];
     }
-    s1 = wave_sum_i64(s1);
-    mx = wave_max_i32(mx);
-    if (t) st = wave_sum_i64(st);
-    if ((threadIdx.x & 63) == 0) {
-        if (sum_e1 && s1) atomic_add_i64(sum_e1, s1);
-        if (t && sum_e1t && st) atomic_add_i64(sum_e1t, st);
-        if (absmax && mx) atomicMax(absmax, mx);
-    }
+    if (sum_e1) block_atomic_add_i64(s1, sum_e1);
+    if (t && sum_e1t) block_atomic_add_i64(st, sum_e1t);
+    if (absmax) block_atomic_max_i32(mx, absmax);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -210,8 +205,7 @@ __global__ void merge_absmax_kernel(const int8_t *a, const int32_t *exp_a, const
         v = v < 0 ? -v : v;
         mx = v > mx ? v : mx;
     }
-    mx = wave_max_i32(mx);
-    if ((threadIdx.x & 63) == 0 && mx) atomicMax(absmax, mx);
+    block_atomic_max_i32(mx, absmax);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -298,10 +292,7 @@ __global__ void sq_pass_kernel(SqArgs p)
         p.out[j] = (int8_t)c;
         s += c;
     }
-    if (p.sum_out) {
-        s = wave_sum_i64(s);
-        if ((threadIdx.x & 63) == 0 && s) atomic_add_i64(p.sum_out, s);
-    }
+    if (p.sum_out) block_atomic_add_i64(s, p.sum_out);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -327,8 +318,7 @@ __global__ void absmax_i8_kernel(const int8_t *g, size_t n, int32_t *slot)
         a = a < 0 ? -a : a;
         mx = a > mx ? a : mx;
     }
-    mx = wave_max_i32(mx);
-    if ((threadIdx.x & 63) == 0 && mx) atomicMax(slot, mx);
+    block_atomic_max_i32(mx, slot);
 }
 
 // delta on the 2^-7 grid for one gradient code (Eq.13): u = SQ(m*g*2^(Eg-j)), d = R(u * 2^(Eu+7))

@@ -123,8 +123,7 @@ __global__ void maxpool_bwd_kernel(PoolGeom g, const int8_t *a, const int8_t *e,
             mx = av > mx ? av : mx;
         }
     }
-    mx = wave_max_i32(mx);
-    if ((threadIdx.x & 63) == 0 && mx) atomicMax(absmax, mx);
+    block_atomic_max_i32(mx, absmax);
 }
 
 __global__ void gap_sum_kernel(const int8_t *y, int N, int HW, int C, int32_t *sum)

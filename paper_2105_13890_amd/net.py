@@ -76,6 +76,7 @@ class FixupNet:
         self.dev = torch.device("cuda")
         self.ctx = eoq.Context()
         self.trace: dict[str, object] = {}
+        self.prof = None                   # list of (kind, unit, work, start event, end event) while profiling
         bt = cfg["block"]
         m = 2 if bt == "basic" else 3
         L = int(sum(cfg["depths"]))
@@ -271,12 +272,28 @@ class FixupNet:
         i = self.scal_idx[name]
         return self.scal[i:i + 1]
 
+    def _call(self, kind, unit, work, fn, *args, **kw):
+        """Run one library call; when profiling, bracket it with events on the stream it is enqueued on."""
+        if self.prof is None:
+            return fn(*args, **kw)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        r = fn(*args, **kw)
+        e1.record()
+        self.prof.append((kind, unit, work, e0, e1))
+        return r
+
     def _rec(self, name, t):
         if self.tracing:
             self.trace[name] = t.detach().clone()
 
     def set_lr(self, m: int, j: int):
         self.lr.copy_(torch.tensor([m, j], dtype=torch.int32))
+
+    @staticmethod
+    def _conv_work(u):
+        d = u.desc
+        return 2.0 * d.N * d.P * d.Q * d.K * d.C * d.R * d.S       # algorithmic ops (multiply-add = 2)
 
     # ------------------------------------------------------------------------------------------ forward
     def _unit_fwd(self, u: Unit, skip=None, y=None, u_next=None, b_next=None):
@@ -286,7 +303,7 @@ class FixupNet:
         else:
             ep = c.epilogue(gamma=self.sc(u.gamma), b_post=self.sc(u.b_post), skip=skip, relu=1,
                             b_next_pre=self.sc(b_next), y=y, u_next=u_next, mask=u.mask, t_wide=u.t)
-        c.conv_fwd(u.desc, u.u, u.w, ep=ep, ws=self.ws)
+        self._call("conv_fwd", u.name, self._conv_work(u), c.conv_fwd, u.desc, u.u, u.w, ep=ep, ws=self.ws)
         if self.tracing:
             self._rec(u.name + ".u", u.u)
             if u.t is not None:
@@ -350,7 +367,8 @@ class FixupNet:
         c = self.ctx
         n = u.w.numel()
         G = self.gacc[:n]
-        c.conv_bwd_weight(u.desc, e3, u.u, G, self.s32(u.name + ".M_G"), self.ws)
+        self._call("conv_bwd_weight", u.name, self._conv_work(u), c.conv_bwd_weight, u.desc, e3, u.u, G,
+                   self.s32(u.name + ".M_G"), self.ws)
         g = self.gq[:n]
         c.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=G, absmax=self.s32(u.name + ".M_G"), exp_in=self.s32(u.E3),
                            exp_in_off=-7, out=g, exp_out=self.s32(u.name + ".Eg"),
@@ -382,7 +400,8 @@ class FixupNet:
         if need_dx:
             n_in = int(np.prod(u.in_shape))
             Dacc = self.dacc[:n_in]
-            c.conv_bwd_data(u.desc, e3[:n_out], u.w, Dacc, self.s32(u.name + ".M_D"), self.ws)
+            self._call("conv_bwd_data", u.name, self._conv_work(u), c.conv_bwd_data, u.desc, e3[:n_out], u.w, Dacc,
+                       self.s32(u.name + ".M_D"), self.ws)
             e4 = bufs.pop()
             c.requant_epilogue(eoq.RQ_SQ_ACC, n_in, acc=Dacc, absmax=self.s32(u.name + ".M_D"), exp_in=self.s32(u.E3),
                                exp_in_off=-7, out=e4[:n_in], exp_out=self.s32(u.E4), sum_out=self.s64(u.name + ".S_e4"))

@@ -83,7 +83,9 @@ def test_lone_block_config(request):
 
 
 @pytest.mark.parametrize("wl,N,steps,lr", [("tiny_basic", 4, 3, (1, 1)), ("tiny_bottleneck", 3, 3, (3, 2)),
-                                           ("resnet20", 128, 2, (1, -2))])
+                                           ("resnet20", 128, 2, (1, -2)),
+                                           # the ImageNet-shaped nets at a batch the oracle finishes in seconds
+                                           ("resnet18", 2, 2, (1, 2)), ("resnet50", 2, 1, (1, 0))])
 def test_network_steps(wl, N, steps, lr):
     from paper_2105_13890_amd.net import FixupNet
     cfg = si.WORKLOADS[wl]
