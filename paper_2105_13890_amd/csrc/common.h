@@ -29,6 +29,7 @@ constexpr int CODE_MAX = 127;
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 // ---- rounding: v * 2^-s to nearest, ties to even (s >= 1); exact left shift for s <= 0 ----

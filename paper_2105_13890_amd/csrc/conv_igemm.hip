@@ -16,6 +16,9 @@
 // output channels of one pixel (16-byte int8 stores, 16-bit mask stores, 64-byte int32 stores).
 #include "common.h"
 
+#include <cstdio>
+#include <cstdlib>
+
 namespace {
 
 struct EpiDev {
@@ -108,91 +111,166 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
     if (ep.mask16) ep.mask16[off >> 4] = (uint16_t)mask;
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE, int EPI>
+template <int BM, int BN, int WGM, int WGN, int BK, bool UNI, int MODE, int EPI>
 __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
 {
     static_assert(WGM * WGN == 4, "4 waves");
+    static_assert(BK == 64 || BK == 128, "stage depth in bytes");
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     static_assert(TM >= 1 && TN >= 1, "tile");
-    constexpr int A_ROWS = (BM + 63) / 64, B_ROWS = (BN + 63) / 64;
-    constexpr int STAGE_BYTES = (BM + BN) * 64;
+    constexpr int CH = BK / 16;                 // k-chunks per LDS row
+    constexpr int RPP = 256 / CH;               // rows loaded per pass of the 256 threads
+    constexpr int RP = 16 / CH;                 // rows per 256 bytes of LDS (swizzle period)
+    constexpr int A_ROWS = (BM + RPP - 1) / RPP, B_ROWS = (BN + RPP - 1) / RPP;
+    constexpr int STAGE_BYTES = (BM + BN) * BK;
     constexpr int EPI_LD = WTN + 4;                       // int32 row stride of the epilogue staging
+    constexpr int D = 4;                                  // global-load stages in flight
 
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int tiles_n = (p.NOUT + BN - 1) / BN;
-    const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+    // consecutive workgroup ids go round-robin over the 8 XCDs: remap so that each XCD (own L2) works on
+    // a contiguous range of tiles, i.e. neighbouring tiles share their operands in one L2
+    int bid = blockIdx.x;
+    {
+        const int nb = gridDim.x, per = nb / 8;
+        if (bid < per * 8) bid = (bid % 8) * per + bid / 8;
+    }
+    const int tile_m = bid / tiles_n, tile_n = bid % tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     // ---- per-thread gather state: which rows / which k-chunk column this thread loads ----
-    const int kc = tid & 3, lrow = tid >> 2;
-    size_t a_base[A_ROWS];
-    int a_h0[A_ROWS], a_w0[A_ROWS];
-    bool a_ok[A_ROWS];
+    // Everything that depends on the row is folded once into a pointer and a 64-bit tap-validity mask, so the
+    // loop only adds a per-stage tap offset (the same for all rows of a thread) and tests one mask bit.
+    //   forward:       input pixel = (ho*stride - pad + r, wo*stride - pad + s)
+    //   backward data: error pixel = ((ho + pad - r)/stride, (wo + pad - s)/stride) where both divide; for those
+    //                  taps (ho+pad-r)/stride = floor((ho+pad)/stride) - floor(r/stride)
+    const int kc = tid % CH, lrow = tid / CH;
+    // Buffer descriptors: a lane whose tap falls into the padding (or past the end of the reduction) gets an
+    // offset beyond num_records and the hardware returns zeros -- no branch, no select.
+    const __amdgpu_buffer_rsrc_t rsrc_a =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.A, 0, p.N * p.H * p.W * p.C, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_b =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.B, 0, p.NOUT * p.nk16 * 16, 0x00020000);
+    constexpr int OOB = 0x7fffff00;
+    int a_off[A_ROWS];
+    unsigned long long a_mask[A_ROWS];
 #pragma unroll
     for (int i = 0; i < A_ROWS; ++i) {
-        int row = lrow + 64 * i;
-        int m = m0 + row;
-        a_ok[i] = (row < BM) && (m < p.M);
-        int mm = a_ok[i] ? m : 0;
-        int wo = mm % p.Q;
-        int t = mm / p.Q;
-        int ho = t % p.P, n = t / p.P;
-        a_base[i] = (size_t)n * p.H * p.W * p.C;
-        if (MODE == MODE_FWD) { a_h0[i] = ho * p.stride - p.pad; a_w0[i] = wo * p.stride - p.pad; }
-        else { a_h0[i] = ho + p.pad; a_w0[i] = wo + p.pad; }
+        const int row = lrow + RPP * i;
+        const int m = m0 + row;
+        const bool ok = (row < BM) && (m < p.M);
+        const int mm = ok ? m : 0;
+        const int wo = mm % p.Q;
+        const int t = mm / p.Q;
+        const int ho = t % p.P, n = t / p.P;
+        int hb, wb;
+        unsigned long long mask = 0;
+        if (MODE == MODE_FWD) {
+            hb = ho * p.stride - p.pad; wb = wo * p.stride - p.pad;
+            int tap = 0;
+            for (int rr = 0; rr < p.R; ++rr)
+                for (int ss = 0; ss < p.S; ++ss, ++tap)
+                    if ((unsigned)(hb + rr) < (unsigned)p.H && (unsigned)(wb + ss) < (unsigned)p.W) mask |= 1ull << tap;
+        } else {
+            const int hp = ho + p.pad, wp = wo + p.pad;
+            hb = hp / p.stride; wb = wp / p.stride;
+            const int hm = hp - hb * p.stride, wm_ = wp - wb * p.stride;
+            int tap = 0;
+            for (int rr = 0, rd = 0, rm = 0; rr < p.R; ++rr) {
+                for (int ss = 0, sd = 0, sm = 0; ss < p.S; ++ss, ++tap) {
+                    if (rm == hm && sm == wm_ && (unsigned)(hb - rd) < (unsigned)p.H && (unsigned)(wb - sd) < (unsigned)p.W)
+                        mask |= 1ull << tap;
+                    if (++sm == p.stride) { sm = 0; ++sd; }
+                }
+                if (++rm == p.stride) { rm = 0; ++rd; }
+            }
+        }
+        a_mask[i] = ok ? mask : 0ull;
+        a_off[i] = ((n * p.H + hb) * p.W + wb) * p.C + kc * 16;
     }
-    // tap / channel position of this thread's k-chunk
-    int kk = kc, r = 0, s = 0, cc = kc;
-    while (cc >= p.c16) { cc -= p.c16; if (++s == p.S) { s = 0; ++r; } }
+    int b_off[B_ROWS];
+    bool b_ok[B_ROWS];
+#pragma unroll
+    for (int i = 0; i < B_ROWS; ++i) {
+        const int row = lrow + RPP * i;
+        const int nr = n0 + row;
+        b_ok[i] = row < BN && nr < p.NOUT;
+        b_off[i] = b_ok[i] ? (nr * p.nk16 + kc) * 16 : 0;
+    }
+    const int wc_step = p.W * p.C;
+    // Position of the stage being loaded.  UNI (C a multiple of the stage depth): every chunk of a stage lies in
+    // one filter tap, so tap, channel base and offsets are wave-uniform scalars.  Otherwise (C = 16, 32) each
+    // thread derives its own tap from its chunk index.
+    int ld_r = 0, ld_s = 0, ld_cb = 0, ld_rd = 0, ld_rm = 0, ld_sd = 0, ld_sm = 0, ld_kk = 0;
 
-    v4i ra[A_ROWS], rb[B_ROWS];
-    auto load_stage = [&]() {
-        const bool tap_ok = kk < p.nk16;
+    auto load_stage = [&](v4i (&ra)[A_ROWS], v4i (&rb)[B_ROWS]) {
+        bool tap_ok;
+        int tap, toff;
+        if (UNI) {
+            tap_ok = ld_r < p.R;
+            tap = tap_ok ? ld_r * p.S + ld_s : 0;
+            if (MODE == MODE_FWD) toff = ld_r * wc_step + ld_s * p.C + ld_cb * 16;
+            else toff = -(ld_rd * wc_step + ld_sd * p.C) + ld_cb * 16;
+        } else {
+            const int kk = ld_kk + kc;
+            tap_ok = kk < p.nk16;
+            const int tp = kk / p.c16, cc = kk - tp * p.c16;
+            const int rr = tp / p.S, ss = tp - rr * p.S;
+            tap = tap_ok ? tp : 0;
+            if (MODE == MODE_FWD) toff = rr * wc_step + ss * p.C + cc * 16;
+            else toff = -((rr / p.stride) * wc_step + (ss / p.stride) * p.C) + cc * 16;
+            toff -= kc * 16;                      // a_off already carries the thread's chunk column
+        }
 #pragma unroll
         for (int i = 0; i < A_ROWS; ++i) {
-            bool v = a_ok[i] && tap_ok;
-            int hin, win;
-            if (MODE == MODE_FWD) { hin = a_h0[i] + r; win = a_w0[i] + s; }
-            else {
-                int th = a_h0[i] - r, tw = a_w0[i] - s;
-                if (p.stride == 1) { hin = th; win = tw; }
-                else {
-                    v = v && th >= 0 && tw >= 0 && (th % p.stride == 0) && (tw % p.stride == 0);
-                    hin = th / p.stride; win = tw / p.stride;
+            const bool v = tap_ok && ((a_mask[i] >> tap) & 1ull);
+            const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, v ? a_off[i] + toff : OOB, 0, 0);
+            ra[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
+        }
+#pragma unroll
+        for (int i = 0; i < B_ROWS; ++i) {
+            const v4u x =
+                __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, (tap_ok && b_ok[i]) ? b_off[i] + ld_kk * 16 : OOB, 0, 0);
+            rb[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
+        }
+        ld_kk += CH;
+        if (UNI) {
+            ld_cb += CH;
+            if (ld_cb == p.c16) {
+                ld_cb = 0;
+                ++ld_s;
+                if (++ld_sm == p.stride) { ld_sm = 0; ++ld_sd; }
+                if (ld_s == p.S) {
+                    ld_s = 0; ld_sd = 0; ld_sm = 0;
+                    ++ld_r;
+                    if (++ld_rm == p.stride) { ld_rm = 0; ++ld_rd; }
                 }
             }
-            v = v && (unsigned)hin < (unsigned)p.H && (unsigned)win < (unsigned)p.W;
-            v4i z = {0, 0, 0, 0};
-            ra[i] = v ? *(const v4i *)(p.A + a_base[i] + ((size_t)hin * p.W + win) * p.C + cc * 16) : z;
         }
-#pragma unroll
-        for (int i = 0; i < B_ROWS; ++i) {
-            int row = lrow + 64 * i;
-            int nr = n0 + row;
-            bool v = tap_ok && row < BN && nr < p.NOUT;
-            v4i z = {0, 0, 0, 0};
-            rb[i] = v ? *(const v4i *)(p.B + ((size_t)nr * p.nk16 + kk) * 16) : z;
-        }
-        kk += 4;
-        cc += 4;
-        while (cc >= p.c16) { cc -= p.c16; if (++s == p.S) { s = 0; ++r; } }
     };
-    auto store_stage = [&](int buf) {
-        int8_t *As = lds + buf * STAGE_BYTES, *Bs = As + BM * 64;
+    int wr_a[A_ROWS], wr_b[B_ROWS];
 #pragma unroll
-        for (int i = 0; i < A_ROWS; ++i) {
-            int row = lrow + 64 * i;
-            if (row < BM) *(v4i *)(As + row * 64 + ((kc ^ ((row >> 2) & 3)) << 4)) = ra[i];
-        }
+    for (int i = 0; i < A_ROWS; ++i) {
+        const int row = lrow + RPP * i;
+        wr_a[i] = row < BM ? row * BK + ((kc ^ ((row / RP) % CH)) << 4) : -1;
+    }
 #pragma unroll
-        for (int i = 0; i < B_ROWS; ++i) {
-            int row = lrow + 64 * i;
-            if (row < BN) *(v4i *)(Bs + row * 64 + ((kc ^ ((row >> 2) & 3)) << 4)) = rb[i];
-        }
+    for (int i = 0; i < B_ROWS; ++i) {
+        const int row = lrow + RPP * i;
+        wr_b[i] = row < BN ? BM * BK + row * BK + ((kc ^ ((row / RP) % CH)) << 4) : -1;
+    }
+    auto store_stage = [&](int buf, const v4i (&ra)[A_ROWS], const v4i (&rb)[B_ROWS]) {
+        int8_t *base = lds + buf;
+#pragma unroll
+        for (int i = 0; i < A_ROWS; ++i)
+            if (BM % RPP == 0 || wr_a[i] >= 0) *(v4i *)(base + wr_a[i]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < B_ROWS; ++i)
+            if (BN % RPP == 0 || wr_b[i] >= 0) *(v4i *)(base + wr_b[i]) = rb[i];
     };
 
     v16i acc[TM][TN];
@@ -203,37 +281,65 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
-    const int nstages = (p.nk16 + 3) / 4;
-    load_stage();
-    store_stage(0);
-    __syncthreads();
     const int lrow32 = lane & 31, lhalf = lane >> 5;
-    for (int st = 0; st < nstages; ++st) {
-        const bool more = st + 1 < nstages;
-        if (more) load_stage();
-        const int8_t *As = lds + (st & 1) * STAGE_BYTES, *Bs = As + BM * 64;
+    // LDS read offsets: the swizzle term is the same for every 32-row tile of a wave (32 is a multiple of the
+    // swizzle period), so one offset per reduction step and operand is enough; tiles add a constant.
+    int rd_a[CH / 2], rd_b[CH / 2];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int chunk = 2 * j + lhalf;
-            v4i a[TM], b[TN];
+    for (int j = 0; j < CH / 2; ++j) {
+        const int chunk = 2 * j + lhalf;
+        const int rowa = wm * WTM + lrow32, rowb = wn * WTN + lrow32;
+        rd_a[j] = rowa * BK + ((chunk ^ ((rowa / RP) % CH)) << 4);
+        rd_b[j] = BM * BK + rowb * BK + ((chunk ^ ((rowb / RP) % CH)) << 4);
+    }
+    // MFMA operands are double-buffered in registers: the fragments of stage st+1 are read from LDS while
+    // the MFMAs of stage st run, so neither the LDS latency nor the global latency sits on the critical path.
+    auto read_frags = [&](int buf, v4i (&fa)[CH / 2][TM], v4i (&fb)[CH / 2][TN]) {
+        const int8_t *base = lds + buf;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                int row = wm * WTM + i * 32 + lrow32;
-                a[i] = *(const v4i *)(As + row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4));
-            }
+        for (int j = 0; j < CH / 2; ++j) {
 #pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                int row = wn * WTN + i * 32 + lrow32;
-                b[i] = *(const v4i *)(Bs + row * 64 + ((chunk ^ ((row >> 2) & 3)) << 4));
-            }
+            for (int i = 0; i < TM; ++i) fa[j][i] = *(const v4i *)(base + rd_a[j] + i * 32 * BK);
+#pragma unroll
+            for (int i = 0; i < TN; ++i) fb[j][i] = *(const v4i *)(base + rd_b[j] + i * 32 * BK);
+        }
+    };
+    auto mfma_stage = [&](const v4i (&fa)[CH / 2][TM], const v4i (&fb)[CH / 2][TN]) {
+#pragma unroll
+        for (int j = 0; j < CH / 2; ++j)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int jn = 0; jn < TN; ++jn)
-                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[jn], acc[i][jn], 0, 0, 0);
+                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[j][i], fb[j][jn], acc[i][jn], 0, 0, 0);
+    };
+
+    // Software pipeline over the reduction, unrolled D (= 4) times so that the register rings are indexed
+    // statically.  Entering iteration st: fragments of stage st are in registers, LDS buffer (st+1)%2 holds
+    // stage st+1, global registers hold stages st+2 .. st+D-1.  The iteration reads the fragments of st+1,
+    // issues the global loads of st+D, multiplies stage st, and moves stage st+2 from registers into the LDS
+    // buffer stage st occupied (its fragments were read one iteration ago, before the last barrier).  Loads
+    // past the end of the reduction are out of range and return zeros; their MFMAs are skipped.
+    const int nstages = (p.nk16 + CH - 1) / CH;
+    v4i ra[D][A_ROWS], rb[D][B_ROWS];
+    v4i fa[2][CH / 2][TM], fb[2][CH / 2][TN];
+#pragma unroll
+    for (int d = 0; d < D; ++d) load_stage(ra[d], rb[d]);
+    store_stage(0, ra[0], rb[0]);
+    store_stage(STAGE_BYTES, ra[1], rb[1]);
+    __syncthreads();
+    read_frags(0, fa[0], fb[0]);
+    int cur = 0;                                   // LDS buffer of the stage being multiplied
+    for (int st = 0; st < nstages; st += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);   // stage st+d+1
+            load_stage(ra[d], rb[d]);                                           // stage st+d+D
+            if (st + d < nstages) mfma_stage(fa[d & 1], fb[d & 1]);             // stage st+d
+            store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);                 // stage st+d+2
+            __syncthreads();
+            cur = STAGE_BYTES - cur;
         }
-        if (more) store_stage((st + 1) & 1);
-        __syncthreads();
     }
 
     // ---- epilogue: per wave, 32 rows at a time through LDS ----
@@ -369,13 +475,13 @@ inline unsigned grid_for(size_t total)
     return (unsigned)b;
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE, int EPI>
-int launch_igemm(eoq_ctx *c, const IgemmParams &p)
+template <int BM, int BN, int WGM, int WGN, int BK, bool UNI, int MODE, int EPI>
+int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
 {
-    constexpr int main_bytes = 2 * (BM + BN) * 64, epi_bytes = 4 * 32 * (BN / WGN + 4) * 4;
+    constexpr int main_bytes = 2 * (BM + BN) * BK, epi_bytes = 4 * 32 * (BN / WGN + 4) * 4;
     constexpr int lds_bytes = main_bytes > epi_bytes ? main_bytes : epi_bytes;
     static bool attr_done = false;
-    auto kern = igemm_kernel<BM, BN, WGM, WGN, MODE, EPI>;
+    auto kern = igemm_kernel<BM, BN, WGM, WGN, BK, UNI, MODE, EPI>;
     if (lds_bytes > 48 * 1024 && !attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
             return EOQ_ERR_HIP;
@@ -387,22 +493,62 @@ int launch_igemm(eoq_ctx *c, const IgemmParams &p)
     return EOQ_OK;
 }
 
+// EOQ_IGEMM_TILE=BMxBNxBK and EOQ_IGEMM_DEPTH=D (environment, read once) force a tile shape / pipeline depth:
+// tuning aids
+int forced_tile()
+{
+    static int v = -1;
+    if (v < 0) {
+        v = 0;
+        const char *e = getenv("EOQ_IGEMM_TILE");
+        int bm, bn, bk;
+        if (e && sscanf(e, "%dx%dx%d", &bm, &bn, &bk) == 3) v = bm * 1000000 + bn * 1000 + bk;
+    }
+    return v;
+}
+int forced_depth()
+{
+    static int v = -1;
+    if (v < 0) {
+        const char *e = getenv("EOQ_IGEMM_DEPTH");
+        v = e ? atoi(e) : 0;
+    }
+    return v;
+}
+
+template <int BM, int BN, int WGM, int WGN, int BK, int MODE, int EPI>
+int launch_igemm(eoq_ctx *c, const IgemmParams &p)
+{
+    if (p.c16 % (BK / 16) == 0) return launch_igemm_u<BM, BN, WGM, WGN, BK, true, MODE, EPI>(c, p);
+    return launch_igemm_u<BM, BN, WGM, WGN, BK, false, MODE, EPI>(c, p);
+}
+
 template <int MODE, int EPI>
 int dispatch_igemm(eoq_ctx *c, const IgemmParams &p)
 {
-    // widest column tile the output channels fill, then the tallest row tile that still gives the
-    // chip a few waves of workgroups
     const int nout = p.NOUT;
     auto wgs = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((nout + bn - 1) / bn); };
-    if (nout <= 32) return launch_igemm<128, 32, 4, 1, MODE, EPI>(c, p);
-    if (nout <= 64) {
-        if (wgs(256, 64) >= 512) return launch_igemm<256, 64, 4, 1, MODE, EPI>(c, p);
-        return launch_igemm<128, 64, 2, 2, MODE, EPI>(c, p);
+    switch (forced_tile()) {
+    case 256256064: return launch_igemm<256, 256, 2, 2, 64, MODE, EPI>(c, p);
+    case 256128064: return launch_igemm<256, 128, 2, 2, 64, MODE, EPI>(c, p);
+    case 128128064: return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
+    case 128128128: return launch_igemm<128, 128, 2, 2, 128, MODE, EPI>(c, p);
+    case 256064064: return launch_igemm<256, 64, 4, 1, 64, MODE, EPI>(c, p);
+    case 128064064: return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
+    case 128032064: return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p);
+    default: break;
     }
-    if (nout % 256 == 0 && wgs(256, 256) >= 512) return launch_igemm<256, 256, 2, 2, MODE, EPI>(c, p);
-    if (wgs(256, 128) >= 512) return launch_igemm<256, 128, 2, 2, MODE, EPI>(c, p);
-    if (wgs(128, 128) >= 256) return launch_igemm<128, 128, 2, 2, MODE, EPI>(c, p);
-    return launch_igemm<128, 64, 2, 2, MODE, EPI>(c, p);
+    // widest column tile the output channels fill, then the tallest row tile that still gives the
+    // chip a few waves of workgroups
+    if (nout <= 32) return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p);
+    if (nout <= 64) {
+        if (wgs(256, 64) >= 512) return launch_igemm<256, 64, 4, 1, 64, MODE, EPI>(c, p);
+        return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
+    }
+    if (nout % 256 == 0 && wgs(256, 256) >= 512) return launch_igemm<256, 256, 2, 2, 64, MODE, EPI>(c, p);
+    if (wgs(256, 128) >= 512) return launch_igemm<256, 128, 2, 2, 64, MODE, EPI>(c, p);
+    if (wgs(128, 128) >= 256) return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
+    return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
 }
 
 bool desc_ok(const eoq_conv_desc *d)
@@ -467,6 +613,7 @@ extern "C" int eoq_conv_fwd(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *u,
         if (int rc = fill_epi(ep, p.ep)) return rc;
     }
     if (d->C % 16 == 0) {
+        if (d->R * d->S > 64) return EOQ_ERR_SHAPE;      // the gather keeps one validity bit per filter tap
         p.A = u; p.B = w;
         p.N = d->N; p.H = d->H; p.W = d->W; p.C = d->C;
         p.R = d->R; p.S = d->S; p.stride = d->stride; p.pad = d->pad;
@@ -495,7 +642,7 @@ extern "C" int eoq_conv_bwd_data(eoq_ctx *c, const eoq_conv_desc *d, const int8_
 {
     if (!c || !e || !w || !d_acc || !absmax_slot) return EOQ_ERR_ARG;
     if (!desc_ok(d)) return EOQ_ERR_SHAPE;
-    if (d->K % 16 || d->C % 16) return EOQ_ERR_SHAPE;
+    if (d->K % 16 || d->C % 16 || d->R * d->S > 64) return EOQ_ERR_SHAPE;
     if (((uintptr_t)e | (uintptr_t)w | (uintptr_t)d_acc) & 15) return EOQ_ERR_ARG;
     if (!ws || ws_bytes < eoq_workspace_bytes(d, EOQ_OP_CONV_BWD_DATA) || ((uintptr_t)ws & 15)) return EOQ_ERR_WORKSPACE;
     const int P = conv_out_dim(d->H, d->pad, d->R, d->stride), Q = conv_out_dim(d->W, d->pad, d->S, d->stride);

@@ -10,7 +10,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libeoq.so")
+LIB_PATH = os.environ.get("EOQ_LIB_PATH") or os.path.join(_HERE, "libeoq.so")
 
 OK, ERR_ARG, ERR_SHAPE, ERR_WORKSPACE, ERR_RANGE, ERR_HIP = range(6)
 FLAG_ACC_OVERFLOW, FLAG_EXP_GAP, FLAG_NONFINITE, FLAG_SHIFT_RANGE = 1, 2, 4, 8
