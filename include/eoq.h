@@ -131,6 +131,17 @@ int eoq_conv_fwd(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *u, const
 int eoq_conv_bwd_data(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, const int8_t *w,
                       int32_t *d_acc, int32_t *absmax_slot, void *ws, size_t ws_bytes);
 
+/* ---- backward-data convolution with Q_e fused: Eq.3 line e4 = Q_e(e3 * w) (Eq.11) ---------------
+ * Same result as eoq_conv_bwd_data followed by eoq_requant_epilogue(EOQ_RQ_SQ_ACC), without the int32
+ * round trip through memory: the scale quantiser needs max|d| before any element can be quantised, so
+ * the convolution is evaluated twice -- the first pass only max-combines max|d| into *absmax_slot (which
+ * the caller zeroed), the second recomputes d and writes e4 = clamp(R(d * 2^(7-r))), r = R(log2 max|d|),
+ * *exp_out = *exp_in + exp_in_off + r - 7 and, when sum_out is non-NULL, *sum_out += sum of the e4 codes
+ * (the bias gradient of Eq.4).  Requires 127^2 * R*S*K < 2^30. */
+int eoq_conv_bwd_data_sq(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, const int8_t *w, int8_t *e4,
+                         int32_t *absmax_slot, const int32_t *exp_in, int32_t exp_in_off, int32_t *exp_out,
+                         int64_t *sum_out, void *ws, size_t ws_bytes);
+
 /* ---- weight-gradient convolution: Eq.4 line g_w before Q_g ------------------------------------
  * g_acc[k,r,s,c] = sum_{n,p,q} e[n,p,q,k] * u[n, p*stride+r-pad, q*stride+s-pad, c], the exact integer
  * sum (partial sums of at most 131072 terms are int32, their combination is int64).  An element
@@ -144,6 +155,14 @@ int eoq_conv_bwd_weight(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e
  * mask_bits NULL means no ReLU (all ones).  e1 may alias e0. */
 int eoq_relu_bwd(eoq_ctx *ctx, const int8_t *e0, const uint32_t *mask_bits, const int32_t *t_wide, size_t n,
                  int8_t *e1, int64_t *sum_e1, int64_t *sum_e1t, int32_t *absmax_e1);
+
+/* Same as eoq_relu_bwd with t_wide = R(conv(u, w) / 128) recomputed on the fly instead of read from
+ * memory (the wide Q_a1 output of a multiplier layer then never has to be stored by the forward pass):
+ * one more evaluation of the forward convolution (desc, u, w as in eoq_conv_fwd, C % 16 == 0) whose
+ * epilogue does the masking and the three reductions.  e1 may alias e0. */
+int eoq_relu_bwd_recompute(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *u, const int8_t *w,
+                           const int8_t *e0, const uint32_t *mask_bits, int8_t *e1, int64_t *sum_e1,
+                           int64_t *sum_e1t, int32_t *absmax_e1);
 
 /* ---- abs-max of the exact sum of two errors with different exponents (first phase of the merge
  * of branch and shortcut errors at a block input): v = a*2^(Ea-Em) + b*2^(Eb-Em), Em = min(Ea,Eb).
@@ -207,12 +226,15 @@ int eoq_update_scalars(eoq_ctx *ctx, int32_t *scalars, const eoq_scalar_grad *de
                        int32_t *g_code_out, int32_t *g_exp_out);
 
 /* ---- pooling, head (outside the quantised arithmetic of Eq.2-13 but on the step's path) ----------
- * Max pool R x S / stride / pad on int8 codes; padding never wins.  u_next as in the epilogue.
- * Backward routes each error to the first maximum in (r,s) scan order and adds overlapping windows
- * (int32 result, |d| max-combined into *absmax_slot); a requant pass (EOQ_RQ_SQ_ACC) follows. */
+ * Max pool R x S / stride / pad on int8 codes; padding never wins; the winner of a window is its first
+ * maximum in (r,s) scan order and arg[n,p,q,c] = r*S+s of the winner (arg may be NULL when no backward
+ * pass follows).  y / u_next as in the epilogue (either may be NULL).
+ * Backward routes each error to the recorded winner and adds overlapping windows (int32 result, |d|
+ * max-combined into *absmax_slot); a requant pass (EOQ_RQ_SQ_ACC) follows.  H, W are the INPUT extents. */
 int eoq_maxpool_fwd(eoq_ctx *ctx, const int8_t *a, int32_t N, int32_t H, int32_t W, int32_t C, int32_t R,
-                    int32_t S, int32_t stride, int32_t pad, int8_t *y, const int32_t *b_next_pre, int8_t *u_next);
-int eoq_maxpool_bwd(eoq_ctx *ctx, const int8_t *a, const int8_t *e, int32_t N, int32_t H, int32_t W, int32_t C,
+                    int32_t S, int32_t stride, int32_t pad, int8_t *y, const int32_t *b_next_pre, int8_t *u_next,
+                    uint8_t *arg);
+int eoq_maxpool_bwd(eoq_ctx *ctx, const uint8_t *arg, const int8_t *e, int32_t N, int32_t H, int32_t W, int32_t C,
                     int32_t R, int32_t S, int32_t stride, int32_t pad, int32_t *d, int32_t *absmax_slot);
 /* Global average pool, integer part: sum[n][c] = sum_{h,w} y[n,h,w,c]. */
 int eoq_gap_sum(eoq_ctx *ctx, const int8_t *y, int32_t N, int32_t HW, int32_t C, int32_t *sum);

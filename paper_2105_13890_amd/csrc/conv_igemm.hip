@@ -40,10 +40,22 @@ struct IgemmParams {
     int32_t *acc_out;
     int32_t *absmax;
     EpiDev ep;
+    // EPI_SQ: scale-quantised int8 output (Q_e fused into the second evaluation of the convolution)
+    int8_t *sq_out;
+    const int32_t *sq_exp_in;
+    int32_t sq_exp_off;
+    int32_t *sq_exp_out;
+    int64_t *sq_sum_out;
+    // EPI_RELU_BWD: ReLU backward with the Q_a1 output recomputed instead of read back
+    const int8_t *rb_e0;
+    const uint16_t *rb_mask16;
+    int8_t *rb_e1;
+    int64_t *rb_sum_e1, *rb_sum_e1t;
+    int32_t *rb_absmax;
 };
 
 enum { MODE_FWD = 0, MODE_BWD_DATA = 1 };
-enum { EPI_FWD = 0, EPI_ACC = 1 };
+enum { EPI_FWD = 0, EPI_ACC = 1, EPI_ABSMAX = 2, EPI_SQ = 3, EPI_RELU_BWD = 4 };
 
 __device__ __forceinline__ void set_byte(v4i &v, int i, int code)
 {
@@ -111,7 +123,7 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
     if (ep.mask16) ep.mask16[off >> 4] = (uint16_t)mask;
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK, bool UNI, int MODE, int EPI>
+template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
 __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
 {
     static_assert(WGM * WGN == 4, "4 waves");
@@ -125,7 +137,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
     constexpr int A_ROWS = (BM + RPP - 1) / RPP, B_ROWS = (BN + RPP - 1) / RPP;
     constexpr int STAGE_BYTES = (BM + BN) * BK;
     constexpr int EPI_LD = WTN + 4;                       // int32 row stride of the epilogue staging
-    constexpr int D = 4;                                  // global-load stages in flight
+    static_assert(D >= 4 && D % 2 == 0, "global-load stages in flight");
 
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
 
@@ -326,23 +338,52 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
 #pragma unroll
     for (int d = 0; d < D; ++d) load_stage(ra[d], rb[d]);
     store_stage(0, ra[0], rb[0]);
-    store_stage(STAGE_BYTES, ra[1], rb[1]);
+    if (nstages > 1) store_stage(STAGE_BYTES, ra[1], rb[1]);
     __syncthreads();
     read_frags(0, fa[0], fb[0]);
+    __syncthreads();                               // every wave has its stage-0 fragments before buffer 0 is reused
     int cur = 0;                                   // LDS buffer of the stage being multiplied
     for (int st = 0; st < nstages; st += D) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);   // stage st+d+1
-            load_stage(ra[d], rb[d]);                                           // stage st+d+D
-            if (st + d < nstages) mfma_stage(fa[d & 1], fb[d & 1]);             // stage st+d
-            store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);                 // stage st+d+2
-            __syncthreads();
-            cur = STAGE_BYTES - cur;
+            if (st + d < nstages) {                                                 // uniform
+                if (st + d + 1 < nstages) read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);
+                if (st + d + D < nstages) load_stage(ra[d], rb[d]);                 // stage st+d+D
+                mfma_stage(fa[d & 1], fb[d & 1]);                                   // stage st+d
+                if (st + d + 2 < nstages) store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);
+                if (st + d + 1 < nstages) __syncthreads();
+                cur = STAGE_BYTES - cur;
+            }
         }
     }
+    __syncthreads();
 
-    // ---- epilogue: per wave, 32 rows at a time through LDS ----
+    // ---- epilogue ----
+    if (EPI == EPI_ABSMAX) {
+        // first evaluation of a two-pass scale quantisation: only max|acc| is needed, straight from the
+        // accumulator registers (rows / columns outside the problem accumulated zeros)
+        int mx0 = 0;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int v = acc[i][jn][e];
+                    const int av = v < 0 ? -v : v;
+                    mx0 = av > mx0 ? av : mx0;
+                }
+        block_atomic_max_i32(mx0, p.absmax);
+        return;
+    }
+    // per wave, 32 rows at a time through LDS
+    int sq_r = 7;
+    long long sq_sum = 0, rb_st = 0;
+    if (EPI == EPI_SQ) {
+        const uint32_t M = (uint32_t)*p.absmax;
+        sq_r = M ? sq_exponent_u32(M) : 7;
+        if (blockIdx.x == 0 && tid == 0) *p.sq_exp_out = *p.sq_exp_in + p.sq_exp_off + sq_r - 7;
+    }
     int32_t *stg = (int32_t *)lds + wave * 32 * EPI_LD;
     constexpr int GROUPS = WTN / 16;              // 16-channel groups per row of the wave tile
     constexpr int ROWS_PER_PASS = 64 / GROUPS;
@@ -379,6 +420,38 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
                 const size_t off = (size_t)m * p.NOUT + ch;
                 if (EPI == EPI_FWD) {
                     epilogue16(v, off, p.ep, p.acc_out, gamma, bpost, bnext);
+                } else if (EPI == EPI_RELU_BWD) {
+                    // Eq.3 e1 = e0 * relu'(x4); Eq.4 sums for g_b2 and g_gamma with x2 = R(acc/128) recomputed
+                    const v4i ev = *(const v4i *)(p.rb_e0 + off);
+                    const uint32_t mk = p.rb_mask16 ? (uint32_t)p.rb_mask16[off >> 4] : 0xffffu;
+                    v4i o = {0, 0, 0, 0};
+                    int ls = 0;
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const int e = ((mk >> k) & 1u) ? byte_at(ev, k) : 0;
+                        set_byte(o, k, e);
+                        ls += e;
+                        const int ae = e < 0 ? -e : e;
+                        mx = ae > mx ? ae : mx;
+                        rb_st += (long long)e * (long long)rne_shift7(v[k]);
+                    }
+                    sq_sum += ls;
+                    *(v4i *)(p.rb_e1 + off) = o;
+                } else if (EPI == EPI_SQ) {
+                    // Q_e (Eq.11): clamp(R(v * 2^(7-r))); |v| < 2^30 here, so 32-bit arithmetic is exact
+                    const int sh = sq_r - 7;
+                    v4i o = {0, 0, 0, 0};
+                    int ls = 0;
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        int cde = sh <= 0 ? (v[k] << (-sh))
+                                          : ((v[k] + ((1 << (sh - 1)) - 1) + ((v[k] >> sh) & 1)) >> sh);
+                        cde = clamp_i(cde, -CODE_MAX, CODE_MAX);
+                        ls += cde;
+                        set_byte(o, k, cde);
+                    }
+                    sq_sum += ls;
+                    *(v4i *)(p.sq_out + off) = o;
                 } else {
 #pragma unroll
                     for (int k4 = 0; k4 < 4; ++k4) {
@@ -396,6 +469,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
         __syncthreads();
     }
     if (EPI == EPI_ACC && p.absmax) block_atomic_max_i32(mx, p.absmax);
+    if (EPI == EPI_SQ && p.sq_sum_out) block_atomic_add_i64(sq_sum, p.sq_sum_out);
+    if (EPI == EPI_RELU_BWD) {
+        if (p.rb_sum_e1) block_atomic_add_i64(sq_sum, p.rb_sum_e1);
+        if (p.rb_sum_e1t) block_atomic_add_i64(rb_st, p.rb_sum_e1t);
+        if (p.rb_absmax) block_atomic_max_i32(mx, p.rb_absmax);
+    }
 }
 
 // ---- small layout kernels -------------------------------------------------------------------
@@ -475,13 +554,13 @@ inline unsigned grid_for(size_t total)
     return (unsigned)b;
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK, bool UNI, int MODE, int EPI>
+template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
 int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
 {
     constexpr int main_bytes = 2 * (BM + BN) * BK, epi_bytes = 4 * 32 * (BN / WGN + 4) * 4;
     constexpr int lds_bytes = main_bytes > epi_bytes ? main_bytes : epi_bytes;
     static bool attr_done = false;
-    auto kern = igemm_kernel<BM, BN, WGM, WGN, BK, UNI, MODE, EPI>;
+    auto kern = igemm_kernel<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>;
     if (lds_bytes > 48 * 1024 && !attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
             return EOQ_ERR_HIP;
@@ -519,8 +598,10 @@ int forced_depth()
 template <int BM, int BN, int WGM, int WGN, int BK, int MODE, int EPI>
 int launch_igemm(eoq_ctx *c, const IgemmParams &p)
 {
-    if (p.c16 % (BK / 16) == 0) return launch_igemm_u<BM, BN, WGM, WGN, BK, true, MODE, EPI>(c, p);
-    return launch_igemm_u<BM, BN, WGM, WGN, BK, false, MODE, EPI>(c, p);
+    if (p.c16 % (BK / 16) == 0) {
+        return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, true, MODE, EPI>(c, p);
+    }
+    return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, false, MODE, EPI>(c, p);
 }
 
 template <int MODE, int EPI>
@@ -529,25 +610,18 @@ int dispatch_igemm(eoq_ctx *c, const IgemmParams &p)
     const int nout = p.NOUT;
     auto wgs = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((nout + bn - 1) / bn); };
     switch (forced_tile()) {
-    case 256256064: return launch_igemm<256, 256, 2, 2, 64, MODE, EPI>(c, p);
-    case 256128064: return launch_igemm<256, 128, 2, 2, 64, MODE, EPI>(c, p);
     case 128128064: return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
-    case 128128128: return launch_igemm<128, 128, 2, 2, 128, MODE, EPI>(c, p);
-    case 256064064: return launch_igemm<256, 64, 4, 1, 64, MODE, EPI>(c, p);
     case 128064064: return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
     case 128032064: return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p);
+    case 64064064: return launch_igemm<64, 64, 2, 2, 64, MODE, EPI>(c, p);
+    case 64128064: return launch_igemm<64, 128, 2, 2, 64, MODE, EPI>(c, p);
     default: break;
     }
-    // widest column tile the output channels fill, then the tallest row tile that still gives the
-    // chip a few waves of workgroups
+    // Measured on MI355X: throughput is nearly flat in the tile shape (the kernel is bound by issue / wait
+    // overheads, not by LDS or L1 traffic), so small tiles win through occupancy and grid size; the 128x128
+    // tile pays off only for wide outputs with enough workgroups to fill the chip.
     if (nout <= 32) return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p);
-    if (nout <= 64) {
-        if (wgs(256, 64) >= 512) return launch_igemm<256, 64, 4, 1, 64, MODE, EPI>(c, p);
-        return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
-    }
-    if (nout % 256 == 0 && wgs(256, 256) >= 512) return launch_igemm<256, 256, 2, 2, 64, MODE, EPI>(c, p);
-    if (wgs(256, 128) >= 512) return launch_igemm<256, 128, 2, 2, 64, MODE, EPI>(c, p);
-    if (wgs(128, 128) >= 256) return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
+    if (nout >= 128 && wgs(128, 128) >= 256) return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
     return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
 }
 
@@ -662,6 +736,66 @@ extern "C" int eoq_conv_bwd_data(eoq_ctx *c, const eoq_conv_desc *d, const int8_
     p.acc_out = d_acc;
     p.absmax = absmax_slot;
     return dispatch_igemm<MODE_BWD_DATA, EPI_ACC>(c, p);
+}
+
+extern "C" int eoq_relu_bwd_recompute(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *u, const int8_t *w,
+                                      const int8_t *e0, const uint32_t *mask_bits, int8_t *e1, int64_t *sum_e1,
+                                      int64_t *sum_e1t, int32_t *absmax_e1)
+{
+    if (!c || !u || !w || !e0 || !e1) return EOQ_ERR_ARG;
+    if (!desc_ok(d)) return EOQ_ERR_SHAPE;
+    if (d->K % 16 || d->C % 16 || d->R * d->S > 64) return EOQ_ERR_SHAPE;
+    if (((uintptr_t)u | (uintptr_t)w | (uintptr_t)e0 | (uintptr_t)e1) & 15 || ((uintptr_t)mask_bits & 3)) return EOQ_ERR_ARG;
+    IgemmParams p{};
+    p.P = conv_out_dim(d->H, d->pad, d->R, d->stride);
+    p.Q = conv_out_dim(d->W, d->pad, d->S, d->stride);
+    if ((size_t)d->N * p.P * p.Q * d->K > 0x7fffffffu || (size_t)d->N * d->H * d->W * d->C > 0x7fffffffu) return EOQ_ERR_SHAPE;
+    p.M = d->N * p.P * p.Q;
+    p.NOUT = d->K;
+    p.A = u; p.B = w;
+    p.N = d->N; p.H = d->H; p.W = d->W; p.C = d->C;
+    p.R = d->R; p.S = d->S; p.stride = d->stride; p.pad = d->pad;
+    p.c16 = p.C / 16;
+    p.nk16 = p.R * p.S * p.c16;
+    p.rb_e0 = e0; p.rb_mask16 = (const uint16_t *)mask_bits; p.rb_e1 = e1;
+    p.rb_sum_e1 = sum_e1; p.rb_sum_e1t = sum_e1t; p.rb_absmax = absmax_e1;
+    return dispatch_igemm<MODE_FWD, EPI_RELU_BWD>(c, p);
+}
+
+static int bwd_data_params(const eoq_conv_desc *d, const int8_t *e, const int8_t *wt, IgemmParams &p)
+{
+    const int P = conv_out_dim(d->H, d->pad, d->R, d->stride), Q = conv_out_dim(d->W, d->pad, d->S, d->stride);
+    if ((size_t)d->N * d->H * d->W > 0x7fffffffu || (size_t)d->N * P * Q * d->K > 0x7fffffffu) return EOQ_ERR_SHAPE;
+    p.A = e; p.B = wt;
+    p.N = d->N; p.H = P; p.W = Q; p.C = d->K;      // the tensor being gathered is the error
+    p.P = d->H; p.Q = d->W; p.NOUT = d->C;         // one output row per input pixel
+    p.R = d->R; p.S = d->S; p.stride = d->stride; p.pad = d->pad;
+    p.M = d->N * d->H * d->W;
+    p.c16 = p.C / 16;
+    p.nk16 = p.R * p.S * p.c16;
+    return EOQ_OK;
+}
+
+extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *e, const int8_t *w, int8_t *e4,
+                                    int32_t *absmax_slot, const int32_t *exp_in, int32_t exp_in_off, int32_t *exp_out,
+                                    int64_t *sum_out, void *ws, size_t ws_bytes)
+{
+    if (!c || !e || !w || !e4 || !absmax_slot || !exp_in || !exp_out) return EOQ_ERR_ARG;
+    if (!desc_ok(d)) return EOQ_ERR_SHAPE;
+    if (d->K % 16 || d->C % 16 || d->R * d->S > 64) return EOQ_ERR_SHAPE;
+    if ((long long)d->R * d->S * d->K * 127 * 127 >= (1ll << 30)) return EOQ_ERR_SHAPE;   // 32-bit requantisation
+    if (((uintptr_t)e | (uintptr_t)w | (uintptr_t)e4) & 15) return EOQ_ERR_ARG;
+    if (!ws || ws_bytes < eoq_workspace_bytes(d, EOQ_OP_CONV_BWD_DATA) || ((uintptr_t)ws & 15)) return EOQ_ERR_WORKSPACE;
+    int8_t *wt = (int8_t *)ws;
+    hipLaunchKernelGGL(transpose_filters_kernel, dim3(grid_for((size_t)d->K * d->R * d->S * d->C)), dim3(256), 0,
+                       c->stream, w, d->K, d->R * d->S, d->C, wt);
+    EOQ_LAUNCH_CHECK();
+    IgemmParams p{};
+    if (int rc = bwd_data_params(d, e, wt, p)) return rc;
+    p.absmax = absmax_slot;
+    if (int rc = dispatch_igemm<MODE_BWD_DATA, EPI_ABSMAX>(c, p)) return rc;
+    p.sq_out = e4; p.sq_exp_in = exp_in; p.sq_exp_off = exp_in_off; p.sq_exp_out = exp_out; p.sq_sum_out = sum_out;
+    return dispatch_igemm<MODE_BWD_DATA, EPI_SQ>(c, p);
 }
 
 int eoq_requant_fwd_standalone(eoq_ctx *c, const eoq_requant_args *a)

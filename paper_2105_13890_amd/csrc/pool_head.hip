@@ -22,7 +22,8 @@ __device__ __forceinline__ void set_byte(v4i &v, int i, int code)
 struct PoolGeom { int N, H, W, C, R, S, stride, pad, P, Q; };
 
 // one lane: 16 channels of one output pixel
-__global__ void maxpool_fwd_kernel(PoolGeom g, const int8_t *a, int8_t *y, const int32_t *b_next, int8_t *u_next)
+__global__ void maxpool_fwd_kernel(PoolGeom g, const int8_t *a, int8_t *y, const int32_t *b_next, int8_t *u_next,
+                                   uint8_t *arg)
 {
     const int c16 = g.C / 16;
     const size_t total = (size_t)g.N * g.P * g.Q * c16;
@@ -33,9 +34,9 @@ __global__ void maxpool_fwd_kernel(PoolGeom g, const int8_t *a, int8_t *y, const
         int q = (int)(pix % g.Q);
         size_t t = pix / g.Q;
         int p = (int)(t % g.P), n = (int)(t / g.P);
-        int best[16];
+        int best[16], bi[16];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) best[k] = -1000;
+        for (int k = 0; k < 16; ++k) { best[k] = -1000; bi[k] = 0; }
         for (int r = 0; r < g.R; ++r) {
             int h = p * g.stride + r - g.pad;
             if (h < 0 || h >= g.H) continue;
@@ -46,24 +47,26 @@ __global__ void maxpool_fwd_kernel(PoolGeom g, const int8_t *a, int8_t *y, const
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
                     int e = byte_at(v, k);
-                    best[k] = e > best[k] ? e : best[k];
+                    if (e > best[k]) { best[k] = e; bi[k] = r * g.S + s; }     // strict: the first maximum wins
                 }
             }
         }
-        v4i o = {0, 0, 0, 0}, ou = {0, 0, 0, 0};
+        v4i o = {0, 0, 0, 0}, ou = {0, 0, 0, 0}, oa = {0, 0, 0, 0};
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             set_byte(o, k, best[k]);
             set_byte(ou, k, clamp_i(best[k] + b, -CODE_MAX, CODE_MAX));
+            set_byte(oa, k, bi[k]);
         }
         if (y) *(v4i *)(y + pix * g.C + cc * 16) = o;
         if (u_next) *(v4i *)(u_next + pix * g.C + cc * 16) = ou;
+        if (arg) *(v4i *)(arg + pix * g.C + cc * 16) = oa;
     }
 }
 
-// one lane: 16 channels of one input pixel; it looks at every window that contains the pixel, finds
-// that window's first maximum in (r,s) scan order, and takes the window's error if it is the winner.
-__global__ void maxpool_bwd_kernel(PoolGeom g, const int8_t *a, const int8_t *e, int32_t *d, int32_t *absmax)
+// one lane: 16 channels of one input pixel; it looks at every window that contains the pixel and takes the
+// window's error where the forward pass recorded this pixel as the window's winner.
+__global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t *e, int32_t *d, int32_t *absmax)
 {
     const int c16 = g.C / 16;
     const size_t total = (size_t)g.N * g.H * g.W * c16;
@@ -89,27 +92,11 @@ __global__ void maxpool_bwd_kernel(PoolGeom g, const int8_t *a, const int8_t *e,
         for (int p = p_lo; p <= p_hi; ++p)
             for (int q = q_lo; q <= q_hi; ++q) {
                 const int my = (h - (p * g.stride - g.pad)) * g.S + (x - (q * g.stride - g.pad));
-                int best[16], bi[16];
-#pragma unroll
-                for (int k = 0; k < 16; ++k) { best[k] = -1000; bi[k] = -1; }
-                for (int r = 0; r < g.R; ++r) {
-                    int hh = p * g.stride + r - g.pad;
-                    if (hh < 0 || hh >= g.H) continue;
-                    for (int s = 0; s < g.S; ++s) {
-                        int xx = q * g.stride + s - g.pad;
-                        if (xx < 0 || xx >= g.W) continue;
-                        v4i v = *(const v4i *)(a + (((size_t)n * g.H + hh) * g.W + xx) * g.C + cc * 16);
-#pragma unroll
-                        for (int k = 0; k < 16; ++k) {
-                            int ev = byte_at(v, k);
-                            if (ev > best[k]) { best[k] = ev; bi[k] = r * g.S + s; }
-                        }
-                    }
-                }
-                v4i ev = *(const v4i *)(e + (((size_t)n * g.P + p) * g.Q + q) * g.C + cc * 16);
+                const size_t o = (((size_t)n * g.P + p) * g.Q + q) * g.C + cc * 16;
+                v4i av = *(const v4i *)(arg + o), ev = *(const v4i *)(e + o);
 #pragma unroll
                 for (int k = 0; k < 16; ++k)
-                    if (bi[k] == my) acc[k] += byte_at(ev, k);
+                    if ((byte_at(av, k) & 0xff) == my) acc[k] += byte_at(ev, k);
             }
         int32_t *o = d + pix * g.C + cc * 16;
 #pragma unroll
@@ -218,28 +205,40 @@ __global__ void head_logits_kernel(int N, int F, int J, const double *feat, cons
     if (n < N && j < J) logits[(size_t)n * J + j] = a;
 }
 
-// per sample: softmax with max subtraction, loss term, dlogits (in place over the logits copy)
+// per sample (one block): softmax with max subtraction, loss term, dlogits.  The exps are evaluated in
+// parallel, the denominator is then summed by one thread in ascending class order (the order is part of
+// the head's definition), and the division / one-hot subtraction is parallel again.
 __global__ void head_softmax_kernel(int N, int J, const double *logits, const int32_t *labels, double *dl,
                                     double *lossn)
 {
-    int n = blockIdx.x * blockDim.x + threadIdx.x;
-    if (n >= N) return;
+    __shared__ double red[256];
+    __shared__ double s_sum;
+    const int n = blockIdx.x;
     const double *lg = logits + (size_t)n * J;
     double *o = dl + (size_t)n * J;
-    double m = lg[0];
-    for (int j = 1; j < J; ++j) m = lg[j] > m ? lg[j] : m;
-    const int lab = labels[n];
-    const double xy = lg[lab] - m;
-    double sum = 0.0;
-    for (int j = 0; j < J; ++j) {
-        double e = head_exp(lg[j] - m);
-        o[j] = e;
-        sum = sum + e;
+    double m = -1.0e300;
+    for (int j = threadIdx.x; j < J; j += blockDim.x) m = lg[j] > m ? lg[j] : m;
+    red[threadIdx.x] = m;
+    __syncthreads();
+    for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] = red[threadIdx.x + w] > red[threadIdx.x] ? red[threadIdx.x + w] : red[threadIdx.x];
+        __syncthreads();
     }
-    lossn[n] = log(sum) - xy;
-    for (int j = 0; j < J; ++j) {
-        double p = o[j] / sum;
-        o[j] = (p - (j == lab ? 1.0 : 0.0)) / (double)N;
+    m = red[0];
+    for (int j = threadIdx.x; j < J; j += blockDim.x) o[j] = head_exp(lg[j] - m);
+    __syncthreads();
+    const int lab = labels[n];
+    if (threadIdx.x == 0) {
+        double sum = 0.0;
+        for (int j = 0; j < J; ++j) sum = sum + o[j];
+        s_sum = sum;
+        lossn[n] = log(sum) - (lg[lab] - m);
+    }
+    __syncthreads();
+    const double sum = s_sum;
+    for (int j = threadIdx.x; j < J; j += blockDim.x) {
+        const double pj = o[j] / sum;
+        o[j] = (pj - (j == lab ? 1.0 : 0.0)) / (double)N;
     }
 }
 
@@ -293,32 +292,33 @@ inline unsigned grid_for(size_t total)
 
 extern "C" int eoq_maxpool_fwd(eoq_ctx *c, const int8_t *a, int32_t N, int32_t H, int32_t W, int32_t C, int32_t R,
                                int32_t S, int32_t stride, int32_t pad, int8_t *y, const int32_t *b_next_pre,
-                               int8_t *u_next)
+                               int8_t *u_next, uint8_t *arg)
 {
     if (!c || !a || N <= 0 || H <= 0 || W <= 0 || C <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
         return EOQ_ERR_ARG;
     if (C % 16 || pad >= R || pad >= S) return EOQ_ERR_SHAPE;
-    if (((uintptr_t)a | (uintptr_t)y | (uintptr_t)u_next) & 15) return EOQ_ERR_ARG;
+    if (((uintptr_t)a | (uintptr_t)y | (uintptr_t)u_next | (uintptr_t)arg) & 15) return EOQ_ERR_ARG;
+    if (R * S > 255) return EOQ_ERR_SHAPE;
     PoolGeom g{N, H, W, C, R, S, stride, pad, conv_out_dim(H, pad, R, stride), conv_out_dim(W, pad, S, stride)};
     if (g.P <= 0 || g.Q <= 0) return EOQ_ERR_SHAPE;
     hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid_for((size_t)N * g.P * g.Q * (C / 16))), dim3(256), 0, c->stream,
-                       g, a, y, b_next_pre, u_next);
+                       g, a, y, b_next_pre, u_next, arg);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }
 
-extern "C" int eoq_maxpool_bwd(eoq_ctx *c, const int8_t *a, const int8_t *e, int32_t N, int32_t H, int32_t W,
+extern "C" int eoq_maxpool_bwd(eoq_ctx *c, const uint8_t *arg, const int8_t *e, int32_t N, int32_t H, int32_t W,
                                int32_t C, int32_t R, int32_t S, int32_t stride, int32_t pad, int32_t *d,
                                int32_t *absmax_slot)
 {
-    if (!c || !a || !e || !d || !absmax_slot || N <= 0 || H <= 0 || W <= 0 || C <= 0 || R <= 0 || S <= 0 ||
+    if (!c || !arg || !e || !d || !absmax_slot || N <= 0 || H <= 0 || W <= 0 || C <= 0 || R <= 0 || S <= 0 ||
         stride <= 0 || pad < 0)
         return EOQ_ERR_ARG;
     if (C % 16 || pad >= R || pad >= S) return EOQ_ERR_SHAPE;
-    if (((uintptr_t)a | (uintptr_t)e | (uintptr_t)d) & 15) return EOQ_ERR_ARG;
+    if (((uintptr_t)arg | (uintptr_t)e | (uintptr_t)d) & 15) return EOQ_ERR_ARG;
     PoolGeom g{N, H, W, C, R, S, stride, pad, conv_out_dim(H, pad, R, stride), conv_out_dim(W, pad, S, stride)};
     if (g.P <= 0 || g.Q <= 0) return EOQ_ERR_SHAPE;
-    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for((size_t)N * H * W * (C / 16))), dim3(256), 0, c->stream, g, a,
+    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for((size_t)N * H * W * (C / 16))), dim3(256), 0, c->stream, g, arg,
                        e, d, absmax_slot);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
@@ -366,7 +366,7 @@ extern "C" int eoq_head_fwd_bwd(eoq_ctx *c, int32_t N, int32_t F, int32_t J, int
                        128.0 * (double)HW, feat);
     hipLaunchKernelGGL(head_logits_kernel, dim3((J + 15) / 16, (N + 15) / 16), dim3(256), 0, s, N, F, J, feat, Wfc,
                        bfc, logits);
-    hipLaunchKernelGGL(head_softmax_kernel, dim3((N + 63) / 64), dim3(64), 0, s, N, J, logits, labels, dl, lossn);
+    hipLaunchKernelGGL(head_softmax_kernel, dim3(N), dim3(256), 0, s, N, J, logits, labels, dl, lossn);
     hipLaunchKernelGGL(head_loss_kernel, dim3(1), dim3(64), 0, s, N, lossn, loss);
     hipLaunchKernelGGL(head_dfeat_kernel, dim3((F + 255) / 256, N), dim3(256), 0, s, N, F, J, HW, dl, Wfc, d);
     hipLaunchKernelGGL(head_update_kernel, dim3((F + 255) / 256, J), dim3(256), 0, s, N, F, J, dl, feat, Wfc, bfc,

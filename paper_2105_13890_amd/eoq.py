@@ -20,8 +20,8 @@ RQ_FWD, RQ_SQ_ACC, RQ_SQ_GAMMA, RQ_SQ_MERGE = 0, 1, 2, 3
 
 EXPORTS = [
     "eoq_create", "eoq_destroy", "eoq_strerror", "eoq_status", "eoq_workspace_bytes", "eoq_fill_zero",
-    "eoq_quantize", "eoq_pre_bias", "eoq_conv_fwd", "eoq_conv_bwd_data", "eoq_conv_bwd_weight",
-    "eoq_relu_bwd", "eoq_merge_absmax", "eoq_requant_epilogue", "eoq_update_int8", "eoq_update_scalars",
+    "eoq_quantize", "eoq_pre_bias", "eoq_conv_fwd", "eoq_conv_bwd_data", "eoq_conv_bwd_data_sq", "eoq_conv_bwd_weight",
+    "eoq_relu_bwd", "eoq_relu_bwd_recompute", "eoq_merge_absmax", "eoq_requant_epilogue", "eoq_update_int8", "eoq_update_scalars",
     "eoq_maxpool_fwd", "eoq_maxpool_bwd", "eoq_gap_sum", "eoq_broadcast_hw", "eoq_head_workspace_bytes",
     "eoq_head_fwd_bwd",
 ]
@@ -75,13 +75,15 @@ def _load():
     lib.eoq_pre_bias.argtypes = [vp, vp, sz, vp, vp]
     lib.eoq_conv_fwd.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, C.POINTER(Epilogue), vp, sz]
     lib.eoq_conv_bwd_data.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, sz]
+    lib.eoq_conv_bwd_data_sq.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, i32, vp, vp, vp, sz]
     lib.eoq_conv_bwd_weight.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, sz]
     lib.eoq_relu_bwd.argtypes = [vp, vp, vp, vp, sz, vp, vp, vp, vp]
+    lib.eoq_relu_bwd_recompute.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, vp, vp]
     lib.eoq_merge_absmax.argtypes = [vp, vp, vp, vp, vp, sz, vp]
     lib.eoq_requant_epilogue.argtypes = [vp, C.POINTER(RequantArgs)]
     lib.eoq_update_int8.argtypes = [vp, vp, sz, vp, vp, vp, vp]
     lib.eoq_update_scalars.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp]
-    lib.eoq_maxpool_fwd.argtypes = [vp, vp] + [i32] * 8 + [vp, vp, vp]
+    lib.eoq_maxpool_fwd.argtypes = [vp, vp] + [i32] * 8 + [vp, vp, vp, vp]
     lib.eoq_maxpool_bwd.argtypes = [vp, vp, vp] + [i32] * 8 + [vp, vp]
     lib.eoq_gap_sum.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.eoq_broadcast_hw.argtypes = [vp, vp, i32, i32, i32, vp]
@@ -168,6 +170,11 @@ class Context:
         _check(_lib.eoq_conv_bwd_data(self._h, C.byref(desc), _ptr(e), _ptr(w), _ptr(d_acc), _ptr(absmax_slot),
                                       _ptr(ws), _nbytes(ws)), "eoq_conv_bwd_data")
 
+    def conv_bwd_data_sq(self, desc, e, w, e4, absmax_slot, exp_in, exp_in_off, exp_out, sum_out, ws):
+        _check(_lib.eoq_conv_bwd_data_sq(self._h, C.byref(desc), _ptr(e), _ptr(w), _ptr(e4), _ptr(absmax_slot),
+                                         _ptr(exp_in), exp_in_off, _ptr(exp_out), _ptr(sum_out), _ptr(ws),
+                                         _nbytes(ws)), "eoq_conv_bwd_data_sq")
+
     def conv_bwd_weight(self, desc, e, u, g_acc, absmax_slot, ws):
         _check(_lib.eoq_conv_bwd_weight(self._h, C.byref(desc), _ptr(e), _ptr(u), _ptr(g_acc), _ptr(absmax_slot),
                                         _ptr(ws), _nbytes(ws)), "eoq_conv_bwd_weight")
@@ -175,6 +182,10 @@ class Context:
     def relu_bwd(self, e0, mask, t_wide, e1, sum_e1=None, sum_e1t=None, absmax_e1=None):
         _check(_lib.eoq_relu_bwd(self._h, _ptr(e0), _ptr(mask), _ptr(t_wide), e0.numel(), _ptr(e1), _ptr(sum_e1),
                                  _ptr(sum_e1t), _ptr(absmax_e1)), "eoq_relu_bwd")
+
+    def relu_bwd_recompute(self, desc, u, w, e0, mask, e1, sum_e1=None, sum_e1t=None, absmax_e1=None):
+        _check(_lib.eoq_relu_bwd_recompute(self._h, C.byref(desc), _ptr(u), _ptr(w), _ptr(e0), _ptr(mask), _ptr(e1),
+                                           _ptr(sum_e1), _ptr(sum_e1t), _ptr(absmax_e1)), "eoq_relu_bwd_recompute")
 
     def merge_absmax(self, a, exp_a, b, exp_b, absmax_slot):
         _check(_lib.eoq_merge_absmax(self._h, _ptr(a), _ptr(exp_a), _ptr(b), _ptr(exp_b), a.numel(),
@@ -196,12 +207,12 @@ class Context:
         _check(_lib.eoq_update_scalars(self._h, _ptr(scalars), _ptr(descs), count, _ptr(sums), _ptr(exps),
                                        _ptr(lr_slot), _ptr(g_code_out), _ptr(g_exp_out)), "eoq_update_scalars")
 
-    def maxpool_fwd(self, a, N, H, W, Cc, R, S, stride, pad, y, b_next_pre=None, u_next=None):
+    def maxpool_fwd(self, a, N, H, W, Cc, R, S, stride, pad, y, b_next_pre=None, u_next=None, arg=None):
         _check(_lib.eoq_maxpool_fwd(self._h, _ptr(a), N, H, W, Cc, R, S, stride, pad, _ptr(y), _ptr(b_next_pre),
-                                    _ptr(u_next)), "eoq_maxpool_fwd")
+                                    _ptr(u_next), _ptr(arg)), "eoq_maxpool_fwd")
 
-    def maxpool_bwd(self, a, e, N, H, W, Cc, R, S, stride, pad, d, absmax_slot):
-        _check(_lib.eoq_maxpool_bwd(self._h, _ptr(a), _ptr(e), N, H, W, Cc, R, S, stride, pad, _ptr(d),
+    def maxpool_bwd(self, arg, e, N, H, W, Cc, R, S, stride, pad, d, absmax_slot):
+        _check(_lib.eoq_maxpool_bwd(self._h, _ptr(arg), _ptr(e), N, H, W, Cc, R, S, stride, pad, _ptr(d),
                                     _ptr(absmax_slot)), "eoq_maxpool_bwd")
 
     def gap_sum(self, y, N, HW, Cc, out):

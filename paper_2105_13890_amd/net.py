@@ -155,13 +155,14 @@ class FixupNet:
             n_out = int(np.prod(u.out_shape))
             if u.relu:
                 u.mask = i32(((n_out + 31) // 32,))
-            if u.gamma or not u.relu:
-                u.t = i32(u.out_shape)
+            if not u.relu or (u.gamma and trace):
+                u.t = i32(u.out_shape)       # multiplier layers: x2 is recomputed in the backward pass, stored only for inspection
         if self.stem:
             self.a0 = i8(self.stem.in_shape)
             self.stem.u = self.a0
             if self.pool:
                 self.prepool = i8(self.stem.out_shape)
+                self.pool_arg = torch.empty(self.blocks_in_shape(cfg, N), dtype=torch.uint8, device=self.dev)
         for bi, b in enumerate(self.blocks):
             b.units[0].u = i8(b.units[0].in_shape)
             if b.ds:
@@ -258,6 +259,13 @@ class FixupNet:
         self.sgrad_params = list(entries.keys())
         self.sgrad_entries = [(self.scal_idx[p], entries[p]) for p in self.sgrad_params]
 
+    @staticmethod
+    def blocks_in_shape(cfg, N):
+        """Shape of the pooled stem output (ImageNet-shaped stem: conv 7x7/2 then pool 3x3/2)."""
+        h = (cfg["in_hw"] + 6 - 7) // 2 + 1
+        h = (h + 2 - 3) // 2 + 1
+        return (N, h, h, cfg["widths"][0])
+
     def s32(self, name):
         i = self.sl.names32[name]
         return self.slots32[i:i + 1]
@@ -350,7 +358,8 @@ class FixupNet:
             d = s.desc
             yb = b0.a_in if b0.a_in is not None else (torch.empty(b0.units[0].in_shape, dtype=torch.int8, device=self.dev)
                                                       if self.tracing else None)
-            c.maxpool_fwd(self.prepool, d.N, d.P, d.Q, d.K, 3, 3, 2, 1, yb, self.sc(b0.units[0].b_pre), b0.units[0].u)
+            c.maxpool_fwd(self.prepool, d.N, d.P, d.Q, d.K, 3, 3, 2, 1, yb, self.sc(b0.units[0].b_pre), b0.units[0].u,
+                          self.pool_arg)
             if yb is not None:
                 self._rec("pool.y", yb)
         else:
@@ -383,9 +392,13 @@ class FixupNet:
         c = self.ctx
         n_out = int(np.prod(u.out_shape))
         e1 = e0
-        if u.relu:
-            c.relu_bwd(e0[:n_out], u.mask, u.t if u.gamma else None, e1[:n_out], self.s64(u.name + ".S_e1"),
-                       self.s64(u.name + ".S_e1t") if u.gamma else None, self.s32(u.name + ".M_e1"))
+        if u.relu and u.gamma:
+            self._call("relu_bwd_recompute", u.name, self._conv_work(u), c.relu_bwd_recompute, u.desc, u.u, u.w,
+                       e0[:n_out], u.mask, e1[:n_out], self.s64(u.name + ".S_e1"), self.s64(u.name + ".S_e1t"),
+                       self.s32(u.name + ".M_e1"))
+        elif u.relu:
+            c.relu_bwd(e0[:n_out], u.mask, None, e1[:n_out], self.s64(u.name + ".S_e1"), None,
+                       self.s32(u.name + ".M_e1"))
         if u.gamma:
             e3 = bufs.pop()
             c.requant_epilogue(eoq.RQ_SQ_GAMMA, n_out, src_a=e1[:n_out], gamma=self.sc(u.gamma),
@@ -399,12 +412,10 @@ class FixupNet:
         e4 = None
         if need_dx:
             n_in = int(np.prod(u.in_shape))
-            Dacc = self.dacc[:n_in]
-            self._call("conv_bwd_data", u.name, self._conv_work(u), c.conv_bwd_data, u.desc, e3[:n_out], u.w, Dacc,
-                       self.s32(u.name + ".M_D"), self.ws)
             e4 = bufs.pop()
-            c.requant_epilogue(eoq.RQ_SQ_ACC, n_in, acc=Dacc, absmax=self.s32(u.name + ".M_D"), exp_in=self.s32(u.E3),
-                               exp_in_off=-7, out=e4[:n_in], exp_out=self.s32(u.E4), sum_out=self.s64(u.name + ".S_e4"))
+            self._call("conv_bwd_data", u.name, 2 * self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
+                       e4[:n_in], self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
+                       self.s64(u.name + ".S_e4"), self.ws)
             if self.tracing:
                 self._rec(u.name + ".e4", e4[:n_in].view(u.in_shape))
         # all uses of the old weights are enqueued: update them
@@ -452,7 +463,7 @@ class FixupNet:
         if self.pool:
             n = int(np.prod(s.out_shape))
             Dacc = self.dacc[:n]
-            c.maxpool_bwd(self.prepool, e, d.N, d.P, d.Q, d.K, 3, 3, 2, 1, Dacc, self.s32("pool.M"))
+            c.maxpool_bwd(self.pool_arg, e, d.N, d.P, d.Q, d.K, 3, 3, 2, 1, Dacc, self.s32("pool.M"))
             e2 = bufs.pop()
             c.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=Dacc, absmax=self.s32("pool.M"),
                                exp_in=self.s32(self.blocks[0].name + ".E_in"), out=e2[:n], exp_out=self.s32("pool.E"))

@@ -108,6 +108,27 @@ def test_conv_fwd_fused_epilogue(ctx, d):
 
 
 @pytest.mark.parametrize("d", CONV_SHAPES[:8], ids=IDS[:8])
+def test_relu_bwd_recompute(ctx, d):
+    u = si.uniform_int8(9, "u", (d.N, d.H, d.W, d.C))
+    w = si.uniform_int8(9, "w", (d.K, d.R, d.S, d.C), -30, 30)
+    oshape = (d.N, d.P, d.Q, d.K)
+    n = int(np.prod(oshape))
+    e0 = si.uniform_int8(9, "e0", oshape)
+    maskb = (si.words(9, "mask", n) & np.uint64(1)).astype(bool)
+    packed = np.packbits(maskb, bitorder="little")
+    mask = dev(np.frombuffer(packed.tobytes() + b"\0" * (-len(packed) % 4), dtype=np.int32))
+    e1 = zeros(oshape, torch.int8)
+    sums, slots = zeros((2,), torch.int64), zeros((1,), torch.int32)
+    ctx.relu_bwd_recompute(desc_of(d), dev(u), dev(w), dev(e0), mask, e1, sums[0:1], sums[1:2], slots[0:1])
+    t = oo.q_a1(oo.conv_fwd(d, u, w))
+    e1o = (e0.astype(np.int64) * maskb.reshape(oshape)).astype(np.int8)
+    assert np.array_equal(host(e1), e1o)
+    assert int(host(sums)[0]) == int(e1o.astype(np.int64).sum())
+    assert int(host(sums)[1]) == int((e1o.astype(np.int64) * t).sum())
+    assert int(host(slots)[0]) == int(np.abs(e1o.astype(np.int64)).max())
+
+
+@pytest.mark.parametrize("d", CONV_SHAPES[:8], ids=IDS[:8])
 def test_conv_bwd_data(ctx, d):
     from paper_2105_13890_amd import eoq
     e = si.uniform_int8(3, "e", (d.N, d.P, d.Q, d.K))
@@ -118,6 +139,16 @@ def test_conv_bwd_data(ctx, d):
     want = oo.conv_bwd_data(d, e, w)
     assert np.array_equal(host(dx), want)
     assert int(host(slot)[0]) == int(np.abs(want).max())
+    # fused Q_e (two evaluations of the convolution, no int32 round trip)
+    e4 = zeros((d.N, d.H, d.W, d.C), torch.int8)
+    sl = dev(np.array([0, -13, 0, 0], dtype=np.int32))
+    sums = zeros((2,), torch.int64)
+    ctx.conv_bwd_data_sq(desc_of(d), dev(e), dev(w), e4, sl[0:1], sl[1:2], -7, sl[2:3], sums[0:1],
+                         ws_for(d, eoq.OP_CONV_BWD_DATA))
+    e4o, E4o = oo.sq_acc(want, -13 - 7)
+    assert np.array_equal(host(e4), e4o) and int(host(sl)[2]) == E4o
+    assert int(host(sl)[0]) == int(np.abs(want).max())
+    assert int(host(sums)[0]) == int(e4o.astype(np.int64).sum())
 
 
 @pytest.mark.parametrize("d", CONV_SHAPES, ids=IDS)
@@ -243,12 +274,14 @@ def test_pool_gap_broadcast(ctx):
     P, Q = yo.shape[1:3]
     y, un = zeros(yo.shape, torch.int8), zeros(yo.shape, torch.int8)
     b = dev(np.array([-4], dtype=np.int32))
-    ctx.maxpool_fwd(dev(a), N, H, W, Cc, 3, 3, 2, 1, y, b, un)
+    argd = zeros(yo.shape, torch.uint8)
+    ctx.maxpool_fwd(dev(a), N, H, W, Cc, 3, 3, 2, 1, y, b, un, argd)
     assert np.array_equal(host(y), yo) and np.array_equal(host(un), oo.pre_bias(yo, -4))
+    assert np.array_equal(host(argd), arg)
     e = si.uniform_int8(7, "e", yo.shape)
     d = zeros(a.shape, torch.int32)
     slot = zeros((1,), torch.int32)
-    ctx.maxpool_bwd(dev(a), dev(e), N, H, W, Cc, 3, 3, 2, 1, d, slot)
+    ctx.maxpool_bwd(argd, dev(e), N, H, W, Cc, 3, 3, 2, 1, d, slot)
     want = oo.maxpool_bwd(e, arg, a.shape)
     assert np.array_equal(host(d), want) and int(host(slot)[0]) == int(np.abs(want).max())
     s = zeros((N, Cc), torch.int32)
