@@ -1,0 +1,77 @@
+"""Small-batch online fine-tuning (Fixup ResNet-18 at batch 1, 2, 4): consecutive int8 update steps from one
+seeded initialisation with a fresh hashed batch per step; after EVERY step all int8 weight tensors, scalar
+codes and the float classifier of the HIP path must equal the oracle's, bit for bit.
+
+The suite runs short trajectories; the full 200-step runs are started by hand:
+    python tests/test_gpu_trajectory.py --batch 1 --steps 200
+and their summaries are kept in the design doc.
+"""
+import json
+import sys
+import time
+
+import numpy as np
+import pytest
+
+try:
+    import seeded_inputs as si
+except ImportError:                                  # run as a script
+    import os
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import seeded_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+def run_trajectory(batch, steps, lr_m, lr_j, workload="resnet18", verbose=False):
+    from oracle.net import Net as OracleNet
+    from paper_2105_13890_amd.net import FixupNet
+    cfg = si.WORKLOADS[workload]
+    g, o = FixupNet(cfg, batch, seed=0), OracleNet(cfg, batch, seed=0)
+    W0 = {k: v.copy() for k, v in o.W.items()}
+    total = sum(v.size for v in W0.values())
+    prev = {k: v.copy() for k, v in o.W.items()}
+    per_step = []
+    t0 = time.time()
+    for step in range(steps):
+        x = si.batch_images(0, step, batch, cfg["in_hw"])
+        lab = si.batch_labels(0, step, batch, cfg["classes"])
+        lo = o.step(x, lab, lr_m, lr_j)
+        lg = g.step(x, lab, lr_m, lr_j)
+        assert abs(lg - lo) <= 1e-5 * abs(lo), (step, lg, lo)
+        for u in g.all_units:
+            assert np.array_equal(u.w.cpu().numpy(), o.W[u.name]), (step, u.name)
+        assert g.scalars() == {k: o.scal[k] for k in g.scalars()}, step
+        assert np.array_equal(g.Wfc.cpu().numpy(), o.Wfc) and np.array_equal(g.bfc.cpu().numpy(), o.bfc), step
+        assert g.status() == 0, step
+        moved = sum(int((o.W[k] != prev[k]).sum()) for k in prev)
+        prev = {k: v.copy() for k, v in o.W.items()}
+        per_step.append(moved / total)
+        if verbose:
+            print(f"step {step:3d} loss {lo:.6f} weight codes moved this step {moved / total:.6f} "
+                  f"({time.time() - t0:.0f} s)", flush=True)
+    changed = sum(int((o.W[k] != W0[k]).sum()) for k in W0) / total
+    scal_moved = sum(1 for k, v in o.scal.items() if v != (128 if k.endswith(".g") else 0))
+    return dict(workload=workload, batch=batch, steps=steps, lr=f"{lr_m}*2^-{lr_j}", final_loss=lo,
+                weight_codes_changed_vs_init=changed, max_moved_in_one_step=max(per_step),
+                mean_moved_per_step=float(np.mean(per_step)), scalars_moved=scal_moved, scalars=len(o.scal))
+
+
+@pytest.mark.parametrize("batch,steps,lr", [(1, 8, (1, 4)), (2, 4, (1, 0)), (4, 2, (1, -1))])
+def test_short_trajectories(batch, steps, lr):
+    r = run_trajectory(batch, steps, *lr)
+    # the comparison is not vacuous: parameters did move
+    assert r["scalars_moved"] > r["scalars"] // 2
+    if lr[1] <= 0:
+        assert r["weight_codes_changed_vs_init"] > 0.01, r
+
+
+if __name__ == "__main__":
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--lr-m", type=int, default=1)
+    ap.add_argument("--lr-j", type=int, default=4)
+    a = ap.parse_args()
+    print(json.dumps(run_trajectory(a.batch, a.steps, a.lr_m, a.lr_j, verbose=True)))
