@@ -141,3 +141,13 @@ __device__ __forceinline__ void block_atomic_add_i64(int64_t v, int64_t *slot)
 
 static inline int conv_out_dim(int in, int pad, int k, int st) { return (in + 2 * pad - k) / st + 1; }
 static inline size_t round_up(size_t v, size_t m) { return (v + m - 1) / m * m; }
+
+// most partial-sum buffers the weight-gradient kernel may write for a filter of `elems` int32 elements:
+// as many as keep the chip busy for small filters, few enough for large ones that their traffic stays small
+static inline int wgrad_max_splits(size_t elems)
+{
+    size_t cap = ((size_t)48 << 20) / (elems * 4 + 1);
+    if (cap < 4) cap = 4;
+    if (cap > 1024) cap = 1024;
+    return (int)cap;
+}

@@ -662,7 +662,7 @@ extern "C" size_t eoq_workspace_bytes(const eoq_conv_desc *d, int op)
     case EOQ_OP_CONV_BWD_WEIGHT: {
         // split partial sums (int32) sized for the worst split count, see conv_wgrad.hip
         size_t kp = d->C % 16 ? (size_t)im2col_kp(d) : (size_t)d->R * d->S * d->C;
-        return im2col + round_up((size_t)d->K * kp * 4 * 64, 256);
+        return im2col + round_up((size_t)d->K * kp * 4 * wgrad_max_splits((size_t)d->K * kp), 256);
     }
     default: return 0;
     }

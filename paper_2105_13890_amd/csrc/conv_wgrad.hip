@@ -17,10 +17,11 @@
 // second kernel which also checks the int32 range and takes the abs-max for Q_g.
 #include "common.h"
 
+#include <cstdlib>
+
 namespace {
 
 constexpr int PIX = 64;          // pixel slots per LDS stage
-constexpr int MAX_SPLITS = 64;
 
 struct WgradParams {
     const int8_t *E;   // N x P x Q x K
@@ -41,7 +42,7 @@ __device__ __forceinline__ v2i lds_read_tr8(const int8_t *p)
     return __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3))) *)p);
 }
 
-template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS>
+template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL>
 __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
 {
     static_assert(WK * WC == 4, "4 waves");
@@ -49,10 +50,12 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
     constexpr int E_LD = KT + 16, U_LD = CT + 16;            // padded LDS row strides (bytes)
     constexpr int E_CH = KT / 16, U_CH = CT / 16;            // 16-byte chunks per row
     constexpr int E_LOADS = (PIX * E_CH + 255) / 256;
+    static_assert(PIX * E_CH % 256 == 0, "error tile loads divide evenly");
     constexpr int E_BYTES = PIX * E_LD;
     constexpr int U_ROWS = U_LOADS * 256 / U_CH;             // patch pixels that fit
     constexpr int U_BYTES = U_ROWS * U_LD;
     constexpr int STAGE_BYTES = E_BYTES + U_BYTES;
+    constexpr int OOB = 0x7fffff00;
 
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
 
@@ -66,43 +69,57 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
     const int split = bid / p.tap_groups;
     const int k0 = tile_k * KT, c0 = tile_c * CT, tap0 = tapg * TAPS;
 
-    // ---- loader state (fixed per thread) ----
-    int e_dp[E_LOADS], e_dq[E_LOADS], e_col[E_LOADS], e_dst[E_LOADS];
+    // Out-of-range offsets make the buffer loads return zeros: padding pixels, pixel slots beyond the
+    // chunk and channels beyond the tensor cost neither a branch nor a select.
+    const __amdgpu_buffer_rsrc_t rsrc_e =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.E, 0, p.N * p.P * p.Q * p.K, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_u =
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.U, 0, p.N * p.H * p.W * p.C, 0x00020000);
+
+    // ---- loader state (fixed per thread): offsets relative to the chunk origin ----
+    int e_dp[E_LOADS], e_dq[E_LOADS], e_off[E_LOADS], e_dst[E_LOADS];
 #pragma unroll
     for (int i = 0; i < E_LOADS; ++i) {
-        int idx = tid + 256 * i;
-        int slot = idx / E_CH;
-        e_col[i] = idx % E_CH;
-        bool ok = slot < PIX && slot < p.PR * p.PQ && (k0 + e_col[i] * 16) < p.K;
-        e_dp[i] = ok ? slot / p.PQ : -1;
+        const int idx = tid + 256 * i;
+        const int slot = idx / E_CH, col = idx % E_CH;
+        const bool ok = slot < p.PR * p.PQ && (k0 + col * 16) < p.K;
+        e_dp[i] = ok ? slot / p.PQ : 1 << 20;               // an invalid slot never passes the row test
         e_dq[i] = ok ? slot % p.PQ : 0;
-        e_dst[i] = slot < PIX ? slot * E_LD + e_col[i] * 16 : -1;
+        e_off[i] = ok ? (e_dp[i] * p.Q + e_dq[i]) * p.K + k0 + col * 16 : 0;
+        e_dst[i] = slot * E_LD + col * 16;
     }
-    int u_py[U_LOADS], u_px[U_LOADS], u_col[U_LOADS], u_dst[U_LOADS];
+    int u_py[U_LOADS], u_px[U_LOADS], u_off[U_LOADS], u_dst[U_LOADS];
     const int npatch = p.PH * p.PW;
 #pragma unroll
     for (int i = 0; i < U_LOADS; ++i) {
-        int idx = tid + 256 * i;
-        int pix = idx / U_CH;
-        u_col[i] = idx % U_CH;
-        bool ok = pix < npatch && (c0 + u_col[i] * 16) < p.C;
-        u_py[i] = ok ? pix / p.PW : -1;
-        u_px[i] = ok ? pix % p.PW : 0;
-        u_dst[i] = pix < npatch ? pix * U_LD + u_col[i] * 16 : -1;
+        const int idx = tid + 256 * i;
+        const int pix = idx / U_CH, col = idx % U_CH;
+        const bool ok = pix < npatch && (c0 + col * 16) < p.C;
+        u_py[i] = ok ? (pix / p.PW) * p.pstep : 1 << 20;
+        u_px[i] = ok ? (pix % p.PW) * p.pstep : 0;
+        u_off[i] = ok ? (u_py[i] * p.W + u_px[i]) * p.C + c0 + col * 16 : 0;
+        u_dst[i] = pix < U_ROWS ? E_BYTES + pix * U_LD + col * 16 : -1;
     }
 
     // ---- MFMA operand addressing (fixed per lane) ----
     const int g = lane >> 5, grp16 = (lane & 31) >> 4, L = lane & 15;
-    int a_off[4], b_pix[4];                       // index jh = 2*j + h : reduction step j, 8-slot half h
+    int a_off[4], b_off[4];                       // index jh = 2*j + h : reduction step j, 8-slot half h
 #pragma unroll
     for (int jh = 0; jh < 4; ++jh) {
-        int slot = (jh >> 1) * 32 + 16 * g + 8 * (jh & 1) + (L >> 1);
-        a_off[jh] = slot * E_LD + grp16 * 16 + 8 * (L & 1);
+        const int slot = (jh >> 1) * 32 + 16 * g + 8 * (jh & 1) + (L >> 1);
+        a_off[jh] = slot * E_LD + grp16 * 16 + 8 * (L & 1) + wk * TK * 32;
         int dp = 0, dq = 0;
         if (slot < p.PR * p.PQ) { dp = slot / p.PQ; dq = slot % p.PQ; }
-        b_pix[jh] = ((dp * p.stride) / p.pstep) * p.PW + (dq * p.stride) / p.pstep;
+        const int pix = ((dp * p.stride) / p.pstep) * p.PW + (dq * p.stride) / p.pstep;
+        b_off[jh] = E_BYTES + pix * U_LD + grp16 * 16 + 8 * (L & 1) + wc * TC * 32;
     }
-    const int b_lane = grp16 * 16 + 8 * (L & 1);
+    // LDS byte offset of each tap inside the patch (uniform)
+    int tap_off[TAPS];
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t) {
+        const int tap = tap0 + t;
+        tap_off[t] = (p.RS == 1 || tap >= p.RS) ? 0 : ((tap / p.S) * p.PW + (tap % p.S)) * U_LD;
+    }
 
     v16i acc[TK][TC][TAPS];
 #pragma unroll
@@ -117,68 +134,58 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
     const int ch_begin = split * p.chunks_per_split;
     int ch_end = ch_begin + p.chunks_per_split;
     if (ch_end > p.nchunks) ch_end = p.nchunks;
+    const int nch = ch_end - ch_begin;
 
-    v4i re[E_LOADS], ru[U_LOADS];
-    auto load_chunk = [&](int ch) {
-        int tq = ch % p.tiles_q;
-        int t = ch / p.tiles_q;
-        int tp = t % p.tiles_p, n = t / p.tiles_p;
-        const int p0 = tp * p.PR, q0 = tq * p.PQ;
-        const v4i z = {0, 0, 0, 0};
+    // chunk being loaded: (image, chunk row, chunk column), advanced without divisions (all uniform)
+    int ld_q = ch_begin % p.tiles_q;
+    int ld_p = (ch_begin / p.tiles_q) % p.tiles_p, ld_n = ch_begin / (p.tiles_q * p.tiles_p);
+
+    auto load_chunk = [&](v4i (&re)[E_LOADS], v4i (&ru)[U_LOADS]) {
+        const int p0 = ld_p * p.PR, q0 = ld_q * p.PQ;
+        const int base_e = ((ld_n * p.P + p0) * p.Q + q0) * p.K;
 #pragma unroll
         for (int i = 0; i < E_LOADS; ++i) {
-            int pp = p0 + e_dp[i], qq = q0 + e_dq[i];
-            bool ok = e_dp[i] >= 0 && pp < p.P && qq < p.Q;
-            re[i] = ok ? *(const v4i *)(p.E + (((size_t)n * p.P + pp) * p.Q + qq) * p.K + k0 + e_col[i] * 16) : z;
+            const bool ok = p0 + e_dp[i] < p.P && q0 + e_dq[i] < p.Q;
+            const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_e, ok ? base_e + e_off[i] : OOB, 0, 0);
+            re[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
         }
         const int h0 = p0 * p.stride - p.pad, w0 = q0 * p.stride - p.pad;
+        const int base_u = ((ld_n * p.H + h0) * p.W + w0) * p.C;
 #pragma unroll
         for (int i = 0; i < U_LOADS; ++i) {
-            int hh = h0 + u_py[i] * p.pstep, ww = w0 + u_px[i] * p.pstep;
-            bool ok = u_py[i] >= 0 && (unsigned)hh < (unsigned)p.H && (unsigned)ww < (unsigned)p.W;
-            ru[i] = ok ? *(const v4i *)(p.U + (((size_t)n * p.H + hh) * p.W + ww) * p.C + c0 + u_col[i] * 16) : z;
+            const bool ok = (unsigned)(h0 + u_py[i]) < (unsigned)p.H && (unsigned)(w0 + u_px[i]) < (unsigned)p.W;
+            const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, ok ? base_u + u_off[i] : OOB, 0, 0);
+            ru[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
         }
+        if (++ld_q == p.tiles_q) { ld_q = 0; if (++ld_p == p.tiles_p) { ld_p = 0; ++ld_n; } }
     };
-    auto store_chunk = [&](int buf) {
-        int8_t *Es = lds + buf * STAGE_BYTES, *Us = Es + E_BYTES;
+    auto store_chunk = [&](int buf, const v4i (&re)[E_LOADS], const v4i (&ru)[U_LOADS]) {
+        int8_t *base = lds + buf;
 #pragma unroll
-        for (int i = 0; i < E_LOADS; ++i)
-            if (e_dst[i] >= 0) *(v4i *)(Es + e_dst[i]) = re[i];
+        for (int i = 0; i < E_LOADS; ++i) *(v4i *)(base + e_dst[i]) = re[i];
 #pragma unroll
         for (int i = 0; i < U_LOADS; ++i)
-            if (u_dst[i] >= 0) *(v4i *)(Us + u_dst[i]) = ru[i];
+            if (u_dst[i] >= 0) *(v4i *)(base + u_dst[i]) = ru[i];
     };
-
-    if (ch_begin < ch_end) {
-        load_chunk(ch_begin);
-        store_chunk(0);
-    }
-    __syncthreads();
-    for (int ch = ch_begin; ch < ch_end; ++ch) {
-        const bool more = ch + 1 < ch_end;
-        if (more) load_chunk(ch + 1);
-        const int8_t *Es = lds + ((ch - ch_begin) & 1) * STAGE_BYTES, *Us = Es + E_BYTES;
+    auto compute_chunk = [&](int buf) {
+        const int8_t *base = lds + buf;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             v4i a[TK];
 #pragma unroll
             for (int tk = 0; tk < TK; ++tk) {
-                const int kb = (wk * TK + tk) * 32;
-                v2i lo = lds_read_tr8(Es + a_off[2 * j] + kb);
-                v2i hi = lds_read_tr8(Es + a_off[2 * j + 1] + kb);
+                const v2i lo = lds_read_tr8(base + a_off[2 * j] + tk * 32);
+                const v2i hi = lds_read_tr8(base + a_off[2 * j + 1] + tk * 32);
                 a[tk] = v4i{lo[0], lo[1], hi[0], hi[1]};
             }
 #pragma unroll
             for (int t = 0; t < TAPS; ++t) {
-                const int tap = tap0 + t;
-                if (tap < p.RS) {
-                    const int toff = (p.RS == 1) ? 0 : ((tap / p.S) * p.PW + (tap % p.S));
+                if (FULL || tap0 + t < p.RS) {
 #pragma unroll
                     for (int tc = 0; tc < TC; ++tc) {
-                        const int cb = (wc * TC + tc) * 32 + b_lane;
-                        v2i lo = lds_read_tr8(Us + (b_pix[2 * j] + toff) * U_LD + cb);
-                        v2i hi = lds_read_tr8(Us + (b_pix[2 * j + 1] + toff) * U_LD + cb);
-                        v4i b = v4i{lo[0], lo[1], hi[0], hi[1]};
+                        const v2i lo = lds_read_tr8(base + b_off[2 * j] + tap_off[t] + tc * 32);
+                        const v2i hi = lds_read_tr8(base + b_off[2 * j + 1] + tap_off[t] + tc * 32);
+                        const v4i b = v4i{lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
                         for (int tk = 0; tk < TK; ++tk)
                             acc[tk][tc][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[tk], b, acc[tk][tc][t], 0, 0, 0);
@@ -186,8 +193,27 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
                 }
             }
         }
-        if (more) store_chunk(((ch - ch_begin) + 1) & 1);
+    };
+
+    // Software pipeline over the pixel chunks, unrolled twice for the two register sets: entering iteration i,
+    // LDS buffer i%2 holds chunk i and one register set holds chunk i+1; the iteration issues the loads of
+    // chunk i+2 into the other set, multiplies chunk i, and moves chunk i+1 into the other LDS buffer.
+    v4i re0[E_LOADS], ru0[U_LOADS], re1[E_LOADS], ru1[U_LOADS];
+    if (nch > 0) load_chunk(re0, ru0);
+    if (nch > 1) load_chunk(re1, ru1);
+    if (nch > 0) store_chunk(0, re0, ru0);
+    __syncthreads();
+    for (int i = 0; i < nch; i += 2) {
+        if (i + 2 < nch) load_chunk(re0, ru0);
+        compute_chunk(0);
+        if (i + 1 < nch) store_chunk(STAGE_BYTES, re1, ru1);
         __syncthreads();
+        if (i + 1 < nch) {
+            if (i + 3 < nch) load_chunk(re1, ru1);
+            compute_chunk(STAGE_BYTES);
+            if (i + 2 < nch) store_chunk(0, re0, ru0);
+            __syncthreads();
+        }
     }
 
     // ---- write this range's partial sums: part[split][k][tap][c] ----
@@ -214,22 +240,65 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
 
 // exact combination of the partial sums; int32 range check; abs-max for Q_g.
 // ld_in is the row length of the partial buffers (padded reduction for the im2col path), ld_out the
-// true R*S*C of the filter.
+// true R*S*C of the filter.  A block covers 64 consecutive filter elements (256-byte rows of the partial
+// buffers); its 4 thread rows each sum every fourth partial buffer in int64, combined through LDS.
 __global__ void wgrad_finalize_kernel(const int32_t *part, size_t part_stride, int splits, int K, int ld_in, int ld_out,
                                       int32_t *g, int32_t *absmax, uint32_t *status)
 {
+    __shared__ long long red[4][64];
     const size_t total = (size_t)K * ld_out;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     int mx = 0;
     bool bad = false;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        size_t k = i / ld_out, j = i % ld_out;
-        int64_t s = 0;
-        for (int sp = 0; sp < splits; ++sp) s += part[(size_t)sp * part_stride + k * ld_in + j];
-        if (s > 2147483647LL || s < -2147483648LL) { bad = true; s = s > 0 ? 2147483647LL : -2147483647LL; }
-        g[i] = (int32_t)s;
-        int64_t a = s < 0 ? -s : s;
-        int ai = a > 2147483647LL ? 2147483647 : (int)a;
-        mx = ai > mx ? ai : mx;
+    for (size_t i0 = (size_t)blockIdx.x * 64; i0 < total; i0 += (size_t)gridDim.x * 64) {
+        const size_t i = i0 + tx;
+        long long s = 0;
+        if (i < total) {
+            const size_t k = i / ld_out, j = i % ld_out;
+            const int32_t *src = part + k * ld_in + j;
+            for (int sp = ty; sp < splits; sp += 4) s += src[(size_t)sp * part_stride];
+        }
+        red[ty][tx] = s;
+        __syncthreads();
+        if (ty == 0 && i < total) {
+            s += red[1][tx] + red[2][tx] + red[3][tx];
+            if (s > 2147483647LL || s < -2147483648LL) { bad = true; s = s > 0 ? 2147483647LL : -2147483647LL; }
+            g[i] = (int32_t)s;
+            const long long a = s < 0 ? -s : s;
+            const int ai = a > 2147483647LL ? 2147483647 : (int)a;
+            mx = ai > mx ? ai : mx;
+        }
+        __syncthreads();
+    }
+    block_atomic_max_i32(mx, absmax);
+    if (bad) atomicOr(status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);
+}
+
+// the same for few partial buffers and contiguous rows: one lane owns 4 consecutive elements and issues
+// the loads of all buffers back to back
+__global__ void wgrad_finalize_direct_kernel(const int32_t *part, size_t part_stride, int splits, size_t total4,
+                                             int32_t *g, int32_t *absmax, uint32_t *status)
+{
+    int mx = 0;
+    bool bad = false;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total4; i += (size_t)gridDim.x * blockDim.x) {
+        long long s[4] = {0, 0, 0, 0};
+        for (int sp = 0; sp < splits; ++sp) {
+            const v4i v = *(const v4i *)(part + (size_t)sp * part_stride + i * 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] += v[e];
+        }
+        v4i o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            long long t = s[e];
+            if (t > 2147483647LL || t < -2147483648LL) { bad = true; t = t > 0 ? 2147483647LL : -2147483647LL; }
+            o[e] = (int)t;
+            const long long a = t < 0 ? -t : t;
+            const int ai = a > 2147483647LL ? 2147483647 : (int)a;
+            mx = ai > mx ? ai : mx;
+        }
+        *(v4i *)(g + i * 4) = o;
     }
     block_atomic_max_i32(mx, absmax);
     if (bad) atomicOr(status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);
@@ -308,24 +377,35 @@ int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int *splits_out)
     p.nchunks = p.N * p.tiles_p * p.tiles_q;
     p.tap_groups = (RS + TAPS - 1) / TAPS;
     const int tiles = ((p.K + KT - 1) / KT) * ((p.C + CT - 1) / CT) * p.tap_groups;
-    int splits = 1024 / tiles;
+    static int target_wgs = 0;
+    if (!target_wgs) {
+        const char *e = getenv("EOQ_WGRAD_WGS");     // tuning aid: workgroups aimed for when splitting the reduction
+        target_wgs = e ? atoi(e) : 256;
+        if (target_wgs < 1) target_wgs = 256;
+    }
+    int splits = target_wgs / tiles;
     if (splits < 1) splits = 1;
-    if (splits > MAX_SPLITS) splits = MAX_SPLITS;
+    const int max_splits = wgrad_max_splits(p.part_stride);
+    if (splits > max_splits) splits = max_splits;
     if (splits > p.nchunks) splits = p.nchunks;
     p.chunks_per_split = (p.nchunks + splits - 1) / splits;
     if ((long)p.chunks_per_split * PIX > 131072) {           // keep every int32 partial sum exact
         p.chunks_per_split = 131072 / PIX;
     }
     splits = (p.nchunks + p.chunks_per_split - 1) / p.chunks_per_split;
-    if (splits > MAX_SPLITS) return EOQ_ERR_SHAPE;
+    if (splits > max_splits) return EOQ_ERR_SHAPE;
     static bool attr_done = false;
-    auto kern = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS>;
+    auto kern_full = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true>;
+    auto kern_part = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false>;
     if (lds_bytes > 48 * 1024 && !attr_done) {
-        if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+        if (hipFuncSetAttribute((const void *)kern_full, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess ||
+            hipFuncSetAttribute((const void *)kern_part, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
             return EOQ_ERR_HIP;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles * splits)), dim3(256), lds_bytes, c->stream, p);
+    if ((size_t)p.N * p.P * p.Q * p.K > 0x7fffff00u || (size_t)p.N * p.H * p.W * p.C > 0x7fffff00u) return EOQ_ERR_SHAPE;
+    hipLaunchKernelGGL(RS % TAPS == 0 ? kern_full : kern_part, dim3((unsigned)(tiles * splits)), dim3(256), lds_bytes,
+                       c->stream, p);
     EOQ_LAUNCH_CHECK();
     *splits_out = splits;   // number of partial buffers written
     return EOQ_OK;
@@ -377,14 +457,20 @@ extern "C" int eoq_conv_bwd_weight(eoq_ctx *c, const eoq_conv_desc *d, const int
     p.part_stride = (size_t)p.K * p.RS * p.C;
     int splits = 0, rc;
     if (p.RS == 1) {
-        if (p.K >= 128) rc = launch_wgrad<2, 2, 2, 2, 1, 4>(c, p, p.RS, &splits);
-        else rc = launch_wgrad<2, 2, 1, 2, 1, 4>(c, p, p.RS, &splits);
+        if (p.K >= 128) rc = launch_wgrad<2, 2, 2, 2, 1, 2>(c, p, p.RS, &splits);
+        else rc = launch_wgrad<2, 2, 1, 2, 1, 2>(c, p, p.RS, &splits);
     } else {
-        rc = launch_wgrad<2, 2, 1, 1, 9, 8>(c, p, p.RS, &splits);
+        if (p.R == 3 && p.S == 3 && p.stride == 1) rc = launch_wgrad<2, 2, 1, 1, 9, 2>(c, p, p.RS, &splits);
+        else rc = launch_wgrad<2, 2, 1, 1, 9, 5>(c, p, p.RS, &splits);
     }
     if (rc != EOQ_OK) return rc;
-    hipLaunchKernelGGL(wgrad_finalize_kernel, dim3(grid_for((size_t)d->K * rsc)), dim3(256), 0, c->stream, part,
-                       p.part_stride, splits, d->K, ld_in, rsc, g_acc, absmax_slot, c->d_status);
+    const size_t total = (size_t)d->K * rsc;
+    if (splits <= 16 && ld_in == rsc && total % 4 == 0)
+        hipLaunchKernelGGL(wgrad_finalize_direct_kernel, dim3(grid_for(total / 4)), dim3(256), 0, c->stream, part,
+                           p.part_stride, splits, total / 4, g_acc, absmax_slot, c->d_status);
+    else
+        hipLaunchKernelGGL(wgrad_finalize_kernel, dim3(grid_for(total * 4)), dim3(256), 0, c->stream, part,
+                           p.part_stride, splits, d->K, ld_in, rsc, g_acc, absmax_slot, c->d_status);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }
