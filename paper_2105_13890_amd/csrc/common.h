@@ -140,7 +140,30 @@ __device__ __forceinline__ void block_atomic_add_i64(int64_t v, int64_t *slot)
 }
 
 static inline int conv_out_dim(int in, int pad, int k, int st) { return (in + 2 * pad - k) / st + 1; }
+static inline int conv_out_dim_fwd(int in, int pad, int k, int st) { return (in + 2 * pad - k) / st + 1; }
 static inline size_t round_up(size_t v, size_t m) { return (v + m - 1) / m * m; }
+
+// ---- few-channel inputs (C <= 4, the network stem): the image is copied once into a zero-bordered buffer
+// with 4 bytes per pixel, so that 4 consecutive pixels of a row are one aligned-to-4, 16-byte k-chunk and the
+// filter's columns are walked 4 at a time (S4 groups).  No im2col matrix is materialised.
+struct Pad4Geom {
+    int Hp, Wp, S4, KP;      // padded extents (pixels), column groups per filter row, padded reduction bytes
+    size_t img_bytes, w_bytes;
+};
+static inline Pad4Geom pad4_geom(const eoq_conv_desc *d)
+{
+    Pad4Geom g;
+    const int Q = conv_out_dim_fwd(d->W, d->pad, d->S, d->stride);
+    g.S4 = (d->S + 3) / 4;
+    g.Hp = d->H + 2 * d->pad;
+    int wp = (Q - 1) * d->stride + 4 * g.S4;
+    if (wp < d->W + 2 * d->pad) wp = d->W + 2 * d->pad;
+    g.Wp = (wp + 3) / 4 * 4;
+    g.KP = d->R * g.S4 * 16;
+    g.img_bytes = (size_t)d->N * g.Hp * g.Wp * 4;
+    g.w_bytes = (size_t)d->K * g.KP;
+    return g;
+}
 
 // most partial-sum buffers the weight-gradient kernel may write for a filter of `elems` int32 elements:
 // as many as keep the chip busy for small filters, few enough for large ones that their traffic stays small

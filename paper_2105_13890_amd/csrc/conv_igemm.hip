@@ -37,6 +37,8 @@ struct IgemmParams {
     int P, Q, NOUT;
     int R, S, stride, pad;
     int M, nk16, c16;
+    int xstep;         // bytes per unit of the column origin (C, except for the 4-bytes-per-pixel stem layout)
+    int no_pad;        // every tap of every row is in range (physically padded input)
     int32_t *acc_out;
     int32_t *absmax;
     EpiDev ep;
@@ -201,8 +203,9 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
                 if (++rm == p.stride) { rm = 0; ++rd; }
             }
         }
+        if (p.no_pad) mask = ~0ull;
         a_mask[i] = ok ? mask : 0ull;
-        a_off[i] = ((n * p.H + hb) * p.W + wb) * p.C + kc * 16;
+        a_off[i] = (n * p.H + hb) * p.W * p.C + wb * p.xstep + kc * 16;
     }
     int b_off[B_ROWS];
     bool b_ok[B_ROWS];
@@ -521,6 +524,37 @@ __global__ void im2col_kernel(const int8_t *u, int N, int H, int W, int C, int P
     }
 }
 
+// input N x H x W x C (C <= 4)  ->  zero-bordered N x Hp x Wp x 4
+__global__ void pad4_input_kernel(const int8_t *u, int N, int H, int W, int C, int pad, int Hp, int Wp, uint32_t *up)
+{
+    const size_t total = (size_t)N * Hp * Wp;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int x = (int)(i % Wp) - pad;
+        const size_t t = i / Wp;
+        const int h = (int)(t % Hp) - pad, n = (int)(t / Hp);
+        uint32_t v = 0;
+        if ((unsigned)h < (unsigned)H && (unsigned)x < (unsigned)W) {
+            const int8_t *src = u + (((size_t)n * H + h) * W + x) * C;
+            for (int c = 0; c < C; ++c) v |= ((uint32_t)(uint8_t)src[c]) << (8 * c);
+        }
+        up[i] = v;
+    }
+}
+
+// filters K x R x S x C (C <= 4)  ->  K x R x S4 x (4 columns x 4 channels), zero padded
+__global__ void pad4_filters_kernel(const int8_t *w, int K, int R, int S, int C, int S4, int8_t *wp)
+{
+    const size_t total = (size_t)K * R * S4 * 16;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int c = (int)(i & 3), sl = (int)((i >> 2) & 3);
+        size_t t = i >> 4;
+        const int j = (int)(t % S4); t /= S4;
+        const int r = (int)(t % R), k = (int)(t / R);
+        const int s = 4 * j + sl;
+        wp[i] = (s < S && c < C) ? w[(((size_t)k * R + r) * S + s) * C + c] : (int8_t)0;
+    }
+}
+
 __global__ void pad_filters_kernel(const int8_t *w, int K, int rsc, int KP, int8_t *wp)
 {
     size_t total = (size_t)K * KP;
@@ -605,8 +639,10 @@ int launch_igemm(eoq_ctx *c, const IgemmParams &p)
 }
 
 template <int MODE, int EPI>
-int dispatch_igemm(eoq_ctx *c, const IgemmParams &p)
+int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in)
 {
+    IgemmParams p = p_in;
+    if (!p.xstep) p.xstep = p.C;
     const int nout = p.NOUT;
     auto wgs = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((nout + bn - 1) / bn); };
     switch (forced_tile()) {
@@ -654,16 +690,21 @@ extern "C" size_t eoq_workspace_bytes(const eoq_conv_desc *d, int op)
     const size_t P = conv_out_dim(d->H, d->pad, d->R, d->stride), Q = conv_out_dim(d->W, d->pad, d->S, d->stride);
     const size_t M = (size_t)d->N * P * Q;
     const size_t wbytes = (size_t)d->K * d->R * d->S * d->C;
-    size_t im2col = 0;
-    if (d->C % 16) im2col = round_up(M * im2col_kp(d), 256) + round_up((size_t)d->K * im2col_kp(d), 256);
+    size_t im2col = 0, kp = (size_t)d->R * d->S * d->C;
+    if (d->C % 16 && d->C <= 4) {
+        const Pad4Geom g = pad4_geom(d);
+        im2col = round_up(g.img_bytes, 256) + round_up(g.w_bytes, 256);
+        kp = (size_t)g.KP;
+    } else if (d->C % 16) {
+        im2col = round_up(M * im2col_kp(d), 256) + round_up((size_t)d->K * im2col_kp(d), 256);
+        kp = (size_t)im2col_kp(d);
+    }
     switch (op) {
     case EOQ_OP_CONV_FWD: return im2col;
     case EOQ_OP_CONV_BWD_DATA: return round_up(wbytes, 256);
-    case EOQ_OP_CONV_BWD_WEIGHT: {
-        // split partial sums (int32) sized for the worst split count, see conv_wgrad.hip
-        size_t kp = d->C % 16 ? (size_t)im2col_kp(d) : (size_t)d->R * d->S * d->C;
+    case EOQ_OP_CONV_BWD_WEIGHT:
+        // staged input + split partial sums (int32) sized for the worst split count, see conv_wgrad.hip
         return im2col + round_up((size_t)d->K * kp * 4 * wgrad_max_splits((size_t)d->K * kp), 256);
-    }
     default: return 0;
     }
 }
@@ -691,6 +732,23 @@ extern "C" int eoq_conv_fwd(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *u,
         p.A = u; p.B = w;
         p.N = d->N; p.H = d->H; p.W = d->W; p.C = d->C;
         p.R = d->R; p.S = d->S; p.stride = d->stride; p.pad = d->pad;
+    } else if (d->C <= 4) {
+        // few-channel input (the stem): zero-bordered 4-bytes-per-pixel copy, 4 pixels = one k-chunk
+        const Pad4Geom g = pad4_geom(d);
+        if (d->R * g.S4 > 64) return EOQ_ERR_SHAPE;
+        if (!ws || ws_bytes < eoq_workspace_bytes(d, EOQ_OP_CONV_FWD) || ((uintptr_t)ws & 15)) return EOQ_ERR_WORKSPACE;
+        if (g.img_bytes > 0x7fffff00u) return EOQ_ERR_SHAPE;
+        int8_t *up = (int8_t *)ws;
+        int8_t *wp = up + round_up(g.img_bytes, 256);
+        hipLaunchKernelGGL(pad4_input_kernel, dim3(grid_for(g.img_bytes / 4)), dim3(256), 0, c->stream, u, d->N, d->H, d->W,
+                           d->C, d->pad, g.Hp, g.Wp, (uint32_t *)up);
+        hipLaunchKernelGGL(pad4_filters_kernel, dim3(grid_for(g.w_bytes)), dim3(256), 0, c->stream, w, d->K, d->R, d->S,
+                           d->C, g.S4, wp);
+        EOQ_LAUNCH_CHECK();
+        p.A = up; p.B = wp;
+        p.N = d->N; p.H = g.Hp; p.W = g.Wp / 4; p.C = 16;       // rows of Wp/4 sixteen-byte units
+        p.R = d->R; p.S = g.S4; p.stride = d->stride; p.pad = 0;
+        p.xstep = 4; p.no_pad = 1;
     } else {
         const int KP = im2col_kp(d);
         if (!ws || ws_bytes < eoq_workspace_bytes(d, EOQ_OP_CONV_FWD) || ((uintptr_t)ws & 15)) return EOQ_ERR_WORKSPACE;
@@ -706,6 +764,7 @@ extern "C" int eoq_conv_fwd(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *u,
         p.P = 1; p.Q = p.M;
         p.R = 1; p.S = 1; p.stride = 1; p.pad = 0;
     }
+    if (!p.xstep) p.xstep = p.C;
     p.c16 = p.C / 16;
     p.nk16 = p.R * p.S * p.c16;
     return ep ? dispatch_igemm<MODE_FWD, EPI_FWD>(c, p) : dispatch_igemm<MODE_FWD, EPI_ACC>(c, p);
@@ -773,6 +832,7 @@ static int bwd_data_params(const eoq_conv_desc *d, const int8_t *e, const int8_t
     p.M = d->N * d->H * d->W;
     p.c16 = p.C / 16;
     p.nk16 = p.R * p.S * p.c16;
+    p.xstep = p.C;
     return EOQ_OK;
 }
 

@@ -35,6 +35,9 @@ struct WgradParams {
     int tap_groups;
     int32_t *part;     // [splits][K][RS][C]
     size_t part_stride;
+    // few-channel input staged as zero-bordered 4-bytes-per-pixel image: the "channels" of the 1x1 problem are
+    // the R*S4 sixteen-byte column groups of the filter window (pad4_S4 > 0 switches this addressing on)
+    int pad4_S4, pad4_R, pad4_Wp, pad4_stride;
 };
 
 __device__ __forceinline__ v2i lds_read_tr8(const int8_t *p)
@@ -74,7 +77,8 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
     const __amdgpu_buffer_rsrc_t rsrc_e =
         __builtin_amdgcn_make_buffer_rsrc((void *)p.E, 0, p.N * p.P * p.Q * p.K, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrc_u =
-        __builtin_amdgcn_make_buffer_rsrc((void *)p.U, 0, p.N * p.H * p.W * p.C, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void *)p.U, 0, p.pad4_S4 ? p.N * p.H * p.pad4_Wp * 4 : p.N * p.H * p.W * p.C,
+                                          0x00020000);
 
     // ---- loader state (fixed per thread): offsets relative to the chunk origin ----
     int e_dp[E_LOADS], e_dq[E_LOADS], e_off[E_LOADS], e_dst[E_LOADS];
@@ -97,7 +101,13 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
         const bool ok = pix < npatch && (c0 + col * 16) < p.C;
         u_py[i] = ok ? (pix / p.PW) * p.pstep : 1 << 20;
         u_px[i] = ok ? (pix % p.PW) * p.pstep : 0;
-        u_off[i] = ok ? (u_py[i] * p.W + u_px[i]) * p.C + c0 + col * 16 : 0;
+        if (p.pad4_S4) {
+            // slot (py,px) of the chunk, column group cg = (filter row r, 4-column group j)
+            const int cg = c0 / 16 + col, r = cg / p.pad4_S4, j = cg % p.pad4_S4;
+            u_off[i] = ok ? ((u_py[i] * p.pad4_stride + r) * p.pad4_Wp + u_px[i] * p.pad4_stride) * 4 + j * 16 : 0;
+        } else {
+            u_off[i] = ok ? (u_py[i] * p.W + u_px[i]) * p.C + c0 + col * 16 : 0;
+        }
         u_dst[i] = pix < U_ROWS ? E_BYTES + pix * U_LD + col * 16 : -1;
     }
 
@@ -150,10 +160,12 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
             re[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
         }
         const int h0 = p0 * p.stride - p.pad, w0 = q0 * p.stride - p.pad;
-        const int base_u = ((ld_n * p.H + h0) * p.W + w0) * p.C;
+        const int base_u = p.pad4_S4 ? ((ld_n * p.H + p0 * p.pad4_stride) * p.pad4_Wp + q0 * p.pad4_stride) * 4
+                                     : ((ld_n * p.H + h0) * p.W + w0) * p.C;
 #pragma unroll
         for (int i = 0; i < U_LOADS; ++i) {
-            const bool ok = (unsigned)(h0 + u_py[i]) < (unsigned)p.H && (unsigned)(w0 + u_px[i]) < (unsigned)p.W;
+            const bool ok = p.pad4_S4 ? (p0 + u_py[i] < p.P && q0 + u_px[i] < p.Q)
+                                      : ((unsigned)(h0 + u_py[i]) < (unsigned)p.H && (unsigned)(w0 + u_px[i]) < (unsigned)p.W);
             const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, ok ? base_u + u_off[i] : OOB, 0, 0);
             ru[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
         }
@@ -242,8 +254,10 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
 // ld_in is the row length of the partial buffers (padded reduction for the im2col path), ld_out the
 // true R*S*C of the filter.  A block covers 64 consecutive filter elements (256-byte rows of the partial
 // buffers); its 4 thread rows each sum every fourth partial buffer in int64, combined through LDS.
+// pad4_S (> 0): the partial rows hold R x S4 x (4 columns x 4 channel slots); element (r,s,c) of the S x pad4_C filter
+// row sits at r*S4*16 + s*4 + c.
 __global__ void wgrad_finalize_kernel(const int32_t *part, size_t part_stride, int splits, int K, int ld_in, int ld_out,
-                                      int32_t *g, int32_t *absmax, uint32_t *status)
+                                      int32_t *g, int32_t *absmax, uint32_t *status, int pad4_S, int pad4_C, int pad4_S4)
 {
     __shared__ long long red[4][64];
     const size_t total = (size_t)K * ld_out;
@@ -254,7 +268,12 @@ __global__ void wgrad_finalize_kernel(const int32_t *part, size_t part_stride, i
         const size_t i = i0 + tx;
         long long s = 0;
         if (i < total) {
-            const size_t k = i / ld_out, j = i % ld_out;
+            const size_t k = i / ld_out;
+            size_t j = i % ld_out;
+            if (pad4_S) {
+                const int c = (int)(j % pad4_C), sx = (int)((j / pad4_C) % pad4_S), r = (int)(j / ((size_t)pad4_C * pad4_S));
+                j = (size_t)r * pad4_S4 * 16 + sx * 4 + c;
+            }
             const int32_t *src = part + k * ld_in + j;
             for (int sp = ty; sp < splits; sp += 4) s += src[(size_t)sp * part_stride];
         }
@@ -302,6 +321,23 @@ __global__ void wgrad_finalize_direct_kernel(const int32_t *part, size_t part_st
     }
     block_atomic_max_i32(mx, absmax);
     if (bad) atomicOr(status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);
+}
+
+// input N x H x W x C (C <= 4)  ->  zero-bordered N x Hp x Wp x 4
+__global__ void wgrad_pad4_input_kernel(const int8_t *u, int N, int H, int W, int C, int pad, int Hp, int Wp, uint32_t *up)
+{
+    const size_t total = (size_t)N * Hp * Wp;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int x = (int)(i % Wp) - pad;
+        const size_t t = i / Wp;
+        const int h = (int)(t % Hp) - pad, n = (int)(t / Hp);
+        uint32_t v = 0;
+        if ((unsigned)h < (unsigned)H && (unsigned)x < (unsigned)W) {
+            const int8_t *src = u + (((size_t)n * H + h) * W + x) * C;
+            for (int c = 0; c < C; ++c) v |= ((uint32_t)(uint8_t)src[c]) << (8 * c);
+        }
+        up[i] = v;
+    }
 }
 
 // explicit im2col (shared shape with the forward path): col[m][KP]
@@ -431,11 +467,28 @@ extern "C" int eoq_conv_bwd_weight(eoq_ctx *c, const eoq_conv_desc *d, const int
     int32_t *part;
     const int rsc = d->R * d->S * d->C;
     int ld_in = rsc;
+    bool pad4 = false;
     if (d->C % 16 == 0) {
         p.U = u;
         p.N = d->N; p.H = d->H; p.W = d->W; p.C = d->C; p.P = P; p.Q = Q;
         p.R = d->R; p.S = d->S; p.stride = d->stride; p.pad = d->pad;
         part = (int32_t *)ws;
+    } else if (d->C <= 4) {
+        // few-channel input (the stem): zero-bordered 4-bytes-per-pixel copy; a 1x1 weight gradient whose
+        // "channels" are the R*S4 column groups of the filter window, gathered straight from that copy
+        const Pad4Geom g = pad4_geom(d);
+        if (g.img_bytes > 0x7fffff00u) return EOQ_ERR_SHAPE;
+        int8_t *up = (int8_t *)ws;
+        part = (int32_t *)((int8_t *)ws + round_up(g.img_bytes, 256) + round_up(g.w_bytes, 256));
+        hipLaunchKernelGGL(wgrad_pad4_input_kernel, dim3(grid_for(g.img_bytes / 4)), dim3(256), 0, c->stream, u, d->N, d->H,
+                           d->W, d->C, d->pad, g.Hp, g.Wp, (uint32_t *)up);
+        EOQ_LAUNCH_CHECK();
+        p.U = up;
+        p.N = d->N; p.H = g.Hp; p.W = g.Wp; p.C = g.KP; p.P = P; p.Q = Q;
+        p.R = 1; p.S = 1; p.stride = 1; p.pad = 0;
+        p.pad4_S4 = g.S4; p.pad4_R = d->R; p.pad4_Wp = g.Wp; p.pad4_stride = d->stride;
+        ld_in = g.KP;
+        pad4 = true;
     } else {
         // explicit im2col: a 1x1 weight gradient over M "pixels" with KP padded channels
         const size_t M = (size_t)d->N * P * Q;
@@ -470,7 +523,8 @@ extern "C" int eoq_conv_bwd_weight(eoq_ctx *c, const eoq_conv_desc *d, const int
                            p.part_stride, splits, total / 4, g_acc, absmax_slot, c->d_status);
     else
         hipLaunchKernelGGL(wgrad_finalize_kernel, dim3(grid_for(total * 4)), dim3(256), 0, c->stream, part,
-                           p.part_stride, splits, d->K, ld_in, rsc, g_acc, absmax_slot, c->d_status);
+                           p.part_stride, splits, d->K, ld_in, rsc, g_acc, absmax_slot, c->d_status, pad4 ? d->S : 0,
+                           d->C, pad4 ? p.pad4_S4 : 0);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }
