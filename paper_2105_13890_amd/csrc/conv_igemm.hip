@@ -71,6 +71,10 @@ __device__ __forceinline__ int byte_at(const v4i &v, int i)
 
 // Forward epilogue for 16 consecutive channels of one pixel (Eq.2 x2..x5 and the next layer's x1).
 // off = linear NPQK element offset of the first channel (a multiple of 16).
+// FAST: z = gamma*t + 128*(b + skip) is known to fit 32 bits (decided once per launch from the accumulator
+// bound and the scalar codes), so everything runs in full-rate 32-bit integer instructions; otherwise the
+// same arithmetic is carried out in 64 bits.
+template <bool FAST>
 __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const EpiDev &ep, int32_t *acc_out,
                                            int gamma, int bpost, int bnext)
 {
@@ -109,20 +113,40 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
 #pragma unroll
         for (int k = 0; k < 16; ++k) sk[k] = 0;
     }
-    v4i yv = {0, 0, 0, 0}, uv = {0, 0, 0, 0};
+    uint32_t yw[4] = {0, 0, 0, 0}, uw[4] = {0, 0, 0, 0};
     uint32_t mask = 0;
+    const int b128 = bpost << 7;
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
-        int64_t z = (int64_t)gamma * (int64_t)t[k] + 128 * ((int64_t)bpost + (int64_t)sk[k]);
-        mask |= (z > 0 ? 1u : 0u) << k;
-        int64_t yy = rne_shift64(z > 0 ? z : 0, 7);
-        int yc = (int)(yy > CODE_MAX ? CODE_MAX : yy);
-        set_byte(yv, k, yc);
-        set_byte(uv, k, clamp_i(yc + bnext, -CODE_MAX, CODE_MAX));
+        int yc;
+        if (FAST) {
+            const int z = gamma * t[k] + ((sk[k] << 7) + b128);
+            mask |= ((uint32_t)(-z) >> 31) << k;                 // z > 0  (z != INT_MIN here)
+            yc = rne_shift7(z);
+            yc = yc < 0 ? 0 : (yc > CODE_MAX ? CODE_MAX : yc);   // = clamp(R(max(z,0)/128)): R is monotone, R(0) = 0
+        } else {
+            const int64_t z = (int64_t)gamma * (int64_t)t[k] + 128 * ((int64_t)bpost + (int64_t)sk[k]);
+            mask |= (z > 0 ? 1u : 0u) << k;
+            const int64_t yy = rne_shift64(z > 0 ? z : 0, 7);
+            yc = (int)(yy > CODE_MAX ? CODE_MAX : yy);
+        }
+        const int uc = clamp_i(yc + bnext, -CODE_MAX, CODE_MAX);
+        yw[k >> 2] |= (uint32_t)yc << (8 * (k & 3));
+        uw[k >> 2] |= ((uint32_t)uc & 0xffu) << (8 * (k & 3));
     }
-    if (ep.y) *(v4i *)(ep.y + off) = yv;
-    if (ep.u_next) *(v4i *)(ep.u_next + off) = uv;
+    if (ep.y) *(v4i *)(ep.y + off) = v4i{(int)yw[0], (int)yw[1], (int)yw[2], (int)yw[3]};
+    if (ep.u_next) *(v4i *)(ep.u_next + off) = v4i{(int)uw[0], (int)uw[1], (int)uw[2], (int)uw[3]};
     if (ep.mask16) ep.mask16[off >> 4] = (uint16_t)mask;
+}
+
+// z fits 32 bits for every element of the launch?  |t| <= tmax (from the reduction length), int8 shortcut
+// codes are at most 127, wide shortcut values are Q_a1 outputs of another convolution (|.| < 2^22 assumed,
+// i.e. R*S*C of that convolution below 33000).
+__device__ __forceinline__ bool epilogue_fits32(const EpiDev &ep, int gamma, int bpost, long long tmax)
+{
+    const long long ag = gamma < 0 ? -(long long)gamma : gamma, ab = bpost < 0 ? -(long long)bpost : bpost;
+    const long long sk = ep.skip ? (ep.skip_wide ? (1ll << 22) : 127) : 0;
+    return ag < (1 << 23) && tmax < (1 << 23) && ag * tmax + 128 * (ab + sk) < (1ll << 31) - 256;
 }
 
 template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
@@ -392,10 +416,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
     constexpr int ROWS_PER_PASS = 64 / GROUPS;
     const int grp = lane % GROUPS, prow = lane / GROUPS;
     int gamma = 128, bpost = 0, bnext = 0;
+    bool fast = false;
     if (EPI == EPI_FWD) {
         if (p.ep.gamma) gamma = *p.ep.gamma;
         if (p.ep.b_post) bpost = *p.ep.b_post;
         if (p.ep.b_next) bnext = *p.ep.b_next;
+        fast = epilogue_fits32(p.ep, gamma, bpost, (127ll * 127 * 16 * p.nk16) / 128 + 1);
     }
     int mx = 0;
 #pragma unroll
@@ -422,7 +448,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
             if (m < p.M && ch < p.NOUT) {
                 const size_t off = (size_t)m * p.NOUT + ch;
                 if (EPI == EPI_FWD) {
-                    epilogue16(v, off, p.ep, p.acc_out, gamma, bpost, bnext);
+                    if (fast) epilogue16<true>(v, off, p.ep, p.acc_out, gamma, bpost, bnext);
+                    else epilogue16<false>(v, off, p.ep, p.acc_out, gamma, bpost, bnext);
                 } else if (EPI == EPI_RELU_BWD) {
                     // Eq.3 e1 = e0 * relu'(x4); Eq.4 sums for g_b2 and g_gamma with x2 = R(acc/128) recomputed
                     const v4i ev = *(const v4i *)(p.rb_e0 + off);
@@ -576,7 +603,7 @@ __global__ void requant_fwd_kernel(const int32_t *acc, size_t n16, EpiDev ep)
             v4i w = ((const v4i *)acc)[i * 4 + k4];
             v[4 * k4] = w[0]; v[4 * k4 + 1] = w[1]; v[4 * k4 + 2] = w[2]; v[4 * k4 + 3] = w[3];
         }
-        epilogue16(v, i * 16, ep, nullptr, gamma, bpost, bnext);
+        epilogue16<false>(v, i * 16, ep, nullptr, gamma, bpost, bnext);
     }
 }
 
