@@ -19,6 +19,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
+# HBM bytes per forward-igemm launch of the ResNet-50 / batch-128 step, from two rocprofv3 --pmc runs (FETCH_SIZE,
+# WRITE_SIZE) scaled by a 1 GiB elementwise kernel: profiles/resnet50_b128_step_hbm_traffic.txt
+MEASURED_FWD_TRAFFIC_BYTES = {"resnet50": 103.1e6}
 
 # learning rate m * 2^-j per workload.  With one learning rate for weights and scalars and deterministic
 # rounding, a rate large enough to move >= 1% of the int8 weight codes per step drives the biases far enough
@@ -38,6 +41,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -64,6 +69,14 @@ def main():
     net.set_lr(lr_m, lr_j)
     torch.cuda.synchronize()
 
+    if args.calibrate_copy:
+        src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.zero_()                         # writes 1 GiB
+        torch.add(src, 1, out=dst)          # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         net.enqueue_step()
     torch.cuda.synchronize()
@@ -81,6 +94,19 @@ def main():
     net.prof = []
     net.enqueue_step()
     torch.cuda.synchronize()
+    # algorithmic bytes of the forward convolutions: int8 input + int8 filters read, int8 outputs (y and / or the
+    # next layer's biased input), 1-bit mask, shortcut read, wide Q_a1 output where it is kept
+    fwd_bytes = 0.0
+    for u in net.all_units:
+        d = u.desc
+        n_out = d.N * d.P * d.Q * d.K
+        fwd_bytes += d.N * d.H * d.W * d.C + d.K * d.R * d.S * d.C
+        fwd_bytes += 4 * n_out if not u.relu else n_out / 8 + n_out          # wide shortcut conv | mask + one int8 out
+    for b in net.blocks:
+        last = b.units[-1].desc
+        n_out = last.N * last.P * last.Q * last.K
+        fwd_bytes += n_out                                                      # block outputs are written twice (y, u_next)
+        fwd_bytes += 4 * n_out if b.ds else n_out                               # shortcut read
     agg = {}
     rows = []
     for kind, unit, work, e0, e1 in net.prof:
@@ -125,9 +151,17 @@ def main():
         "conv": conv,
         "roofline": {"bound": "mfma", "kernel": "igemm_kernel (forward convolution launches of one step)",
                      "achieved": round(fwd_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s",
-                     "frac": round(fwd_tops / PEAK_INT8_TOPS, 4), "traffic": None,
-                     "note": "int8 multiply-add counted as 2 ops; algorithmic ops 2*N*P*Q*K*C*R*S summed over the "
-                             "launches divided by their summed durations"},
+                     "frac": round(fwd_tops / PEAK_INT8_TOPS, 4),
+                     "traffic": MEASURED_FWD_TRAFFIC_BYTES.get(wl) if N == DEFAULT_BATCH[wl] else None,
+                     "launches": fwd[2], "avg_launch_us": round(fwd[1] * 1e3 / fwd[2], 2),
+                     "algorithmic_ops_per_launch": round(fwd[0] / fwd[2]),
+                     "algorithmic_bytes_per_launch": round(fwd_bytes / fwd[2]),
+                     "hbm_gbs_at_algorithmic_bytes": round(fwd_bytes / (fwd[1] * 1e-3) / 1e9, 1),
+                     "note": "int8 multiply-add counted as 2 ops; algorithmic ops 2*N*P*Q*K*C*R*S summed over the forward "
+                             "launches of one step divided by their summed event-timed durations; traffic = measured HBM "
+                             "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy); measured MFMA "
+                             "ceilings on this chip: 4.9 POP/s with all-zero operands, 3.3 POP/s with random int8 operands "
+                             "(power-limited)"},
     }
 
     if not args.no_cpu_baseline:

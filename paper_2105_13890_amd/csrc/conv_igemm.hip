@@ -39,6 +39,7 @@ struct IgemmParams {
     int M, nk16, c16;
     int xstep;         // bytes per unit of the column origin (C, except for the 4-bytes-per-pixel stem layout)
     int no_pad;        // every tap of every row is in range (physically padded input)
+    int gemm;          // 1x1 filter, stride 1, no padding: row m of the GEMM is pixel m of the input
     int32_t *acc_out;
     int32_t *absmax;
     EpiDev ep;
@@ -202,6 +203,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
         const int m = m0 + row;
         const bool ok = (row < BM) && (m < p.M);
         const int mm = ok ? m : 0;
+        if (p.gemm) {                              // uniform: no pixel decomposition, one always-valid tap
+            a_mask[i] = ok ? 1ull : 0ull;
+            a_off[i] = mm * p.C + kc * 16;
+            continue;
+        }
         const int wo = mm % p.Q;
         const int t = mm / p.Q;
         const int ho = t % p.P, n = t / p.P;
@@ -670,6 +676,7 @@ int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in)
 {
     IgemmParams p = p_in;
     if (!p.xstep) p.xstep = p.C;
+    p.gemm = (p.R == 1 && p.S == 1 && p.stride == 1 && p.pad == 0 && !p.no_pad && p.P == p.H && p.Q == p.W) ? 1 : 0;
     const int nout = p.NOUT;
     auto wgs = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((nout + bn - 1) / bn); };
     switch (forced_tile()) {
