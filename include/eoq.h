@@ -49,7 +49,8 @@ enum eoq_status_code {
 };
 
 enum eoq_flag_bits {
-    EOQ_FLAG_ACC_OVERFLOW = 1, /* a weight-gradient element does not fit int32 */
+    EOQ_FLAG_ACC_OVERFLOW = 1, /* a weight-gradient element does not fit int32, or a wide shortcut value is outside
+                                * the range the forward epilogue computes exactly (see eoq_epilogue) */
     EOQ_FLAG_EXP_GAP = 2,      /* two exponents too far apart to align exactly */
     EOQ_FLAG_NONFINITE = 4,    /* eoq_quantize met a NaN or an infinity */
     EOQ_FLAG_SHIFT_RANGE = 8   /* an update would need a left shift beyond 24 bits */
@@ -98,7 +99,9 @@ int eoq_quantize(eoq_ctx *ctx, const float *x, size_t n, int mode, int pre_shift
  *              u_next = clamp(y + b_next_pre, -127, 127)   the next layer's x1 (Eq.2 line 2)
  *   relu = 0:  only t_wide is produced (1x1 shortcut convolution)
  * skip: the residual input of the block, NPQK layout, int8 codes (skip_is_wide = 0) or int32 codes on
- * the 2^-7 grid (skip_is_wide = 1).  Outputs that are NULL are not written.  relu_mask_bits holds one
+ * the 2^-7 grid (skip_is_wide = 1; |value| < 2^22, which every Q_a1 output of a convolution with
+ * R*S*C < 33000 satisfies -- a larger value sets EOQ_FLAG_ACC_OVERFLOW and the outputs of the call are
+ * not valid).  Outputs that are NULL are not written.  relu_mask_bits holds one
  * bit per output element: bit (i % 32) of word (i / 32), i = linear NPQK index.  Scalars are read from
  * device memory at kernel time. */
 typedef struct eoq_epilogue {

@@ -42,6 +42,7 @@ struct IgemmParams {
     int gemm;          // 1x1 filter, stride 1, no padding: row m of the GEMM is pixel m of the input
     int32_t *acc_out;
     int32_t *absmax;
+    uint32_t *status;  // device status word of the context
     EpiDev ep;
     // EPI_SQ: scale-quantised int8 output (Q_e fused into the second evaluation of the convolution)
     int8_t *sq_out;
@@ -77,7 +78,7 @@ __device__ __forceinline__ int byte_at(const v4i &v, int i)
 // same arithmetic is carried out in 64 bits.
 template <bool FAST>
 __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const EpiDev &ep, int32_t *acc_out,
-                                           int gamma, int bpost, int bnext)
+                                           int gamma, int bpost, int bnext, uint32_t &range_bad)
 {
     if (acc_out) {
 #pragma unroll
@@ -104,6 +105,12 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
             for (int k4 = 0; k4 < 4; ++k4) {
                 v4i w = ((const v4i *)((const int32_t *)ep.skip + off))[k4];
                 sk[4 * k4] = w[0]; sk[4 * k4 + 1] = w[1]; sk[4 * k4 + 2] = w[2]; sk[4 * k4 + 3] = w[3];
+            }
+            if (FAST) {
+                // the 32-bit path was chosen assuming |shortcut| < 2^22: anything a 23-bit signed field cannot
+                // hold is reported through the status word instead of silently wrapping
+#pragma unroll
+                for (int k = 0; k < 16; ++k) range_bad |= (uint32_t)(sk[k] ^ __builtin_amdgcn_sbfe(sk[k], 0, 23));
             }
         } else {
             v4i w = *(const v4i *)((const int8_t *)ep.skip + off);
@@ -141,8 +148,8 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
 }
 
 // z fits 32 bits for every element of the launch?  |t| <= tmax (from the reduction length), int8 shortcut
-// codes are at most 127, wide shortcut values are Q_a1 outputs of another convolution (|.| < 2^22 assumed,
-// i.e. R*S*C of that convolution below 33000).
+// codes are at most 127, wide shortcut values are Q_a1 outputs of another convolution (|.| < 2^22, i.e. R*S*C of
+// that convolution below 33000; the epilogue checks every value it reads and raises EOQ_FLAG_ACC_OVERFLOW).
 __device__ __forceinline__ bool epilogue_fits32(const EpiDev &ep, int gamma, int bpost, long long tmax)
 {
     const long long ag = gamma < 0 ? -(long long)gamma : gamma, ab = bpost < 0 ? -(long long)bpost : bpost;
@@ -430,6 +437,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
         fast = epilogue_fits32(p.ep, gamma, bpost, (127ll * 127 * 16 * p.nk16) / 128 + 1);
     }
     int mx = 0;
+    uint32_t range_bad = 0;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -454,8 +462,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
             if (m < p.M && ch < p.NOUT) {
                 const size_t off = (size_t)m * p.NOUT + ch;
                 if (EPI == EPI_FWD) {
-                    if (fast) epilogue16<true>(v, off, p.ep, p.acc_out, gamma, bpost, bnext);
-                    else epilogue16<false>(v, off, p.ep, p.acc_out, gamma, bpost, bnext);
+                    if (fast) epilogue16<true>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad);
+                    else epilogue16<false>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad);
                 } else if (EPI == EPI_RELU_BWD) {
                     // Eq.3 e1 = e0 * relu'(x4); Eq.4 sums for g_b2 and g_gamma with x2 = R(acc/128) recomputed
                     const v4i ev = *(const v4i *)(p.rb_e0 + off);
@@ -504,6 +512,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
         }
         __syncthreads();
     }
+    if (EPI == EPI_FWD && range_bad) atomicOr(p.status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);
     if (EPI == EPI_ACC && p.absmax) block_atomic_max_i32(mx, p.absmax);
     if (EPI == EPI_SQ && p.sq_sum_out) block_atomic_add_i64(sq_sum, p.sq_sum_out);
     if (EPI == EPI_RELU_BWD) {
@@ -609,7 +618,8 @@ __global__ void requant_fwd_kernel(const int32_t *acc, size_t n16, EpiDev ep)
             v4i w = ((const v4i *)acc)[i * 4 + k4];
             v[4 * k4] = w[0]; v[4 * k4 + 1] = w[1]; v[4 * k4 + 2] = w[2]; v[4 * k4 + 3] = w[3];
         }
-        epilogue16<false>(v, i * 16, ep, nullptr, gamma, bpost, bnext);
+        uint32_t unused = 0;
+        epilogue16<false>(v, i * 16, ep, nullptr, gamma, bpost, bnext, unused);
     }
 }
 
@@ -751,6 +761,7 @@ extern "C" int eoq_conv_fwd(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *u,
     if (d->K % 16) return EOQ_ERR_SHAPE;
     if (((uintptr_t)u | (uintptr_t)w | (uintptr_t)acc) & 15) return EOQ_ERR_ARG;
     IgemmParams p{};
+    p.status = c->d_status;
     p.P = conv_out_dim(d->H, d->pad, d->R, d->stride);
     p.Q = conv_out_dim(d->W, d->pad, d->S, d->stride);
     if ((size_t)d->N * p.P * p.Q > 0x7fffffffu || (size_t)d->H * d->W * d->C > 0x7fffffffu) return EOQ_ERR_SHAPE;
@@ -819,6 +830,7 @@ extern "C" int eoq_conv_bwd_data(eoq_ctx *c, const eoq_conv_desc *d, const int8_
                        c->stream, w, d->K, d->R * d->S, d->C, wt);
     EOQ_LAUNCH_CHECK();
     IgemmParams p{};
+    p.status = c->d_status;
     p.A = e; p.B = wt;
     p.N = d->N; p.H = P; p.W = Q; p.C = d->K;      // the tensor being gathered is the error
     p.P = d->H; p.Q = d->W; p.NOUT = d->C;         // one output row per input pixel
@@ -840,6 +852,7 @@ extern "C" int eoq_relu_bwd_recompute(eoq_ctx *c, const eoq_conv_desc *d, const 
     if (d->K % 16 || d->C % 16 || d->R * d->S > 64) return EOQ_ERR_SHAPE;
     if (((uintptr_t)u | (uintptr_t)w | (uintptr_t)e0 | (uintptr_t)e1) & 15 || ((uintptr_t)mask_bits & 3)) return EOQ_ERR_ARG;
     IgemmParams p{};
+    p.status = c->d_status;
     p.P = conv_out_dim(d->H, d->pad, d->R, d->stride);
     p.Q = conv_out_dim(d->W, d->pad, d->S, d->stride);
     if ((size_t)d->N * p.P * p.Q * d->K > 0x7fffffffu || (size_t)d->N * d->H * d->W * d->C > 0x7fffffffu) return EOQ_ERR_SHAPE;
@@ -885,6 +898,7 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
                        c->stream, w, d->K, d->R * d->S, d->C, wt);
     EOQ_LAUNCH_CHECK();
     IgemmParams p{};
+    p.status = c->d_status;
     if (int rc = bwd_data_params(d, e, wt, p)) return rc;
     p.absmax = absmax_slot;
     if (int rc = dispatch_igemm<MODE_BWD_DATA, EPI_ABSMAX>(c, p)) return rc;
