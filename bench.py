@@ -41,6 +41,7 @@ def main():
     ap.add_argument("--batch", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
+    ap.add_argument("--no-overlap", action="store_true", help="run the whole step on one stream")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -61,7 +62,7 @@ def main():
     N = args.batch or DEFAULT_BATCH[wl]
     lr_m, lr_j = LR[wl]
 
-    net = FixupNet(cfg, N, seed=0)
+    net = FixupNet(cfg, N, seed=0, overlap=not args.no_overlap)
     x = si.batch_images(0, 0, N, cfg["in_hw"])
     lab = si.batch_labels(0, 0, N, cfg["classes"])
     net.x_in.copy_(torch.from_numpy(x).cuda())
@@ -90,10 +91,13 @@ def main():
     loss = float(net.loss.item())
     flags = net.status()
 
-    # ---- one instrumented step: events around every convolution call ----
+    # ---- one instrumented step: events around every convolution call, on ONE stream so that a call's duration is
+    # its own (in the timed loop the weight-gradient chain overlaps the error chain on a second stream) ----
     net.prof = []
+    overlap, net.overlap = net.overlap, False
     net.enqueue_step()
     torch.cuda.synchronize()
+    net.overlap = overlap
     # algorithmic bytes of the forward convolutions: int8 input + int8 filters read, int8 outputs (y and / or the
     # next layer's biased input), 1-bit mask, shortcut read, wide Q_a1 output where it is kept
     fwd_bytes = 0.0

@@ -239,6 +239,12 @@ int eoq_maxpool_fwd(eoq_ctx *ctx, const int8_t *a, int32_t N, int32_t H, int32_t
                     uint8_t *arg);
 int eoq_maxpool_bwd(eoq_ctx *ctx, const uint8_t *arg, const int8_t *e, int32_t N, int32_t H, int32_t W, int32_t C,
                     int32_t R, int32_t S, int32_t stride, int32_t pad, int32_t *d, int32_t *absmax_slot);
+/* The same sums followed by Q_e (Eq.11) without the int32 tensor: the sums are formed twice, first for max|d|
+ * (max-combined into *absmax_slot, which must hold 0 or a valid partial maximum), then for the codes
+ * e_out = SQ(d) with *exp_out = *exp_in + R(log2 max|d|) - 7 (all-zero d: codes 0, exponent passed through). */
+int eoq_maxpool_bwd_sq(eoq_ctx *ctx, const uint8_t *arg, const int8_t *e, int32_t N, int32_t H, int32_t W, int32_t C,
+                       int32_t R, int32_t S, int32_t stride, int32_t pad, int8_t *e_out, int32_t *absmax_slot,
+                       const int32_t *exp_in, int32_t *exp_out);
 /* Global average pool, integer part: sum[n][c] = sum_{h,w} y[n,h,w,c]. */
 int eoq_gap_sum(eoq_ctx *ctx, const int8_t *y, int32_t N, int32_t HW, int32_t C, int32_t *sum);
 /* e[n,h,w,c] = codes[n][c] for all HW positions (error of the average pool, already quantised). */

@@ -356,44 +356,73 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
             for (int i = 0; i < TN; ++i) fb[j][i] = *(const v4i *)(base + rd_b[j] + i * 32 * BK);
         }
     };
-    auto mfma_stage = [&](const v4i (&fa)[CH / 2][TM], const v4i (&fb)[CH / 2][TN]) {
+    auto mfma_half = [&](int j, const v4i (&fa)[CH / 2][TM], const v4i (&fb)[CH / 2][TN]) {
 #pragma unroll
-        for (int j = 0; j < CH / 2; ++j)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int jn = 0; jn < TN; ++jn)
-                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[j][i], fb[j][jn], acc[i][jn], 0, 0, 0);
+            for (int jn = 0; jn < TN; ++jn)
+                acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[j][i], fb[j][jn], acc[i][jn], 0, 0, 0);
     };
 
     // Software pipeline over the reduction, unrolled D (= 4) times so that the register rings are indexed
     // statically.  Entering iteration st: fragments of stage st are in registers, LDS buffer (st+1)%2 holds
     // stage st+1, global registers hold stages st+2 .. st+D-1.  The iteration reads the fragments of st+1,
     // issues the global loads of st+D, multiplies stage st, and moves stage st+2 from registers into the LDS
-    // buffer stage st occupied (its fragments were read one iteration ago, before the last barrier).  Loads
-    // past the end of the reduction are out of range and return zeros; their MFMAs are skipped.
+    // buffer stage st occupied (its fragments were read one iteration ago, before the last barrier).
+    // Every step of an iteration is UNCONDITIONAL: loads past the end of the reduction are out of range, cost
+    // no memory traffic and return zeros, which are stored and read like real data and never multiplied.
+    // The number of loads in flight at each wait is therefore a compile-time constant, and the compiler can
+    // wait for exactly the oldest stage (a conditional load anywhere in the loop would force it to wait for
+    // everything, i.e. to expose the full memory latency in every iteration).
     const int nstages = (p.nk16 + CH - 1) / CH;
     v4i ra[D][A_ROWS], rb[D][B_ROWS];
     v4i fa[2][CH / 2][TM], fb[2][CH / 2][TN];
 #pragma unroll
     for (int d = 0; d < D; ++d) load_stage(ra[d], rb[d]);
     store_stage(0, ra[0], rb[0]);
-    if (nstages > 1) store_stage(STAGE_BYTES, ra[1], rb[1]);
+    store_stage(STAGE_BYTES, ra[1], rb[1]);
     __syncthreads();
     read_frags(0, fa[0], fb[0]);
     __syncthreads();                               // every wave has its stage-0 fragments before buffer 0 is reused
     int cur = 0;                                   // LDS buffer of the stage being multiplied
-    for (int st = 0; st < nstages; st += D) {
+    int st = 0;
+    // The order inside an iteration is pinned (scheduling barriers): LDS reads of the next stage and the global
+    // loads go first, so that their latency runs under this stage's MFMAs; the LDS writes sit between the two
+    // halves of the MFMAs, so that a wave that has to wait for its global data has already queued matrix work
+    // and the writes have landed by the time the last MFMA is issued and the barrier is reached.
+    for (; st + D <= nstages; st += D) {           // full groups: straight-line code, one exit
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            if (st + d < nstages) {                                                 // uniform
-                if (st + d + 1 < nstages) read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);
-                if (st + d + D < nstages) load_stage(ra[d], rb[d]);                 // stage st+d+D
-                mfma_stage(fa[d & 1], fb[d & 1]);                                   // stage st+d
-                if (st + d + 2 < nstages) store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);
-                if (st + d + 1 < nstages) __syncthreads();
-                cur = STAGE_BYTES - cur;
-            }
+            read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);        // stage st+d+1
+            __builtin_amdgcn_sched_barrier(0);
+            load_stage(ra[d], rb[d]);                                               // stage st+d+D
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_half(0, fa[d & 1], fb[d & 1]);                                     // stage st+d
+            __builtin_amdgcn_sched_barrier(0);
+            store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);                     // stage st+d+2
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 1; j < CH / 2; ++j) mfma_half(j, fa[d & 1], fb[d & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            cur = STAGE_BYTES - cur;
+        }
+    }
+    // the last nstages % D stages: everything they need is already in registers or in flight
+#pragma unroll
+    for (int d = 0; d < D - 1; ++d) {
+        if (st + d < nstages) {                                                     // uniform
+            read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_half(0, fa[d & 1], fb[d & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 1; j < CH / 2; ++j) mfma_half(j, fa[d & 1], fb[d & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            cur = STAGE_BYTES - cur;
         }
     }
     __syncthreads();
@@ -469,7 +498,10 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
                     const v4i ev = *(const v4i *)(p.rb_e0 + off);
                     const uint32_t mk = p.rb_mask16 ? (uint32_t)p.rb_mask16[off >> 4] : 0xffffu;
                     v4i o = {0, 0, 0, 0};
-                    int ls = 0;
+                    int ls = 0, lst = 0;
+                    // |x2| <= 127^2 * (reduction length) / 128 and |e| <= 127: for reductions of up to 8192
+                    // terms sixteen products sum to less than 2^31 and are added in 32 bits
+                    const bool narrow = p.nk16 <= 512;
 #pragma unroll
                     for (int k = 0; k < 16; ++k) {
                         const int e = ((mk >> k) & 1u) ? byte_at(ev, k) : 0;
@@ -477,9 +509,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
                         ls += e;
                         const int ae = e < 0 ? -e : e;
                         mx = ae > mx ? ae : mx;
-                        rb_st += (long long)e * (long long)rne_shift7(v[k]);
+                        if (narrow) lst += e * rne_shift7(v[k]);
+                        else rb_st += (long long)e * (long long)rne_shift7(v[k]);
                     }
                     sq_sum += ls;
+                    rb_st += lst;
                     *(v4i *)(p.rb_e1 + off) = o;
                 } else if (EPI == EPI_SQ) {
                     // Q_e (Eq.11): clamp(R(v * 2^(7-r))); |v| < 2^30 here, so 32-bit arithmetic is exact
@@ -649,8 +683,7 @@ int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
     return EOQ_OK;
 }
 
-// EOQ_IGEMM_TILE=BMxBNxBK and EOQ_IGEMM_DEPTH=D (environment, read once) force a tile shape / pipeline depth:
-// tuning aids
+// EOQ_IGEMM_TILE=BMxBNxBK (environment, read once) forces a tile shape: a tuning aid
 int forced_tile()
 {
     static int v = -1;
@@ -659,15 +692,6 @@ int forced_tile()
         const char *e = getenv("EOQ_IGEMM_TILE");
         int bm, bn, bk;
         if (e && sscanf(e, "%dx%dx%d", &bm, &bn, &bk) == 3) v = bm * 1000000 + bn * 1000 + bk;
-    }
-    return v;
-}
-int forced_depth()
-{
-    static int v = -1;
-    if (v < 0) {
-        const char *e = getenv("EOQ_IGEMM_DEPTH");
-        v = e ? atoi(e) : 0;
     }
     return v;
 }
@@ -697,9 +721,9 @@ int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in)
     case 64128064: return launch_igemm<64, 128, 2, 2, 64, MODE, EPI>(c, p);
     default: break;
     }
-    // Measured on MI355X: throughput is nearly flat in the tile shape (the kernel is bound by issue / wait
-    // overheads, not by LDS or L1 traffic), so small tiles win through occupancy and grid size; the 128x128
-    // tile pays off only for wide outputs with enough workgroups to fill the chip.
+    // Measured on MI355X: throughput is nearly flat in the tile shape and in the prefetch depth (4, 6, 8 stages),
+    // so small tiles win through occupancy and grid size; the 128x128 tile pays off only for wide outputs with
+    // enough workgroups to fill the chip.
     if (nout <= 32) return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p);
     if (nout >= 128 && wgs(128, 128) >= 256) return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
     return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);

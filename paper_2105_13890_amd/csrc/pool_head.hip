@@ -66,11 +66,21 @@ __global__ void maxpool_fwd_kernel(PoolGeom g, const int8_t *a, int8_t *y, const
 
 // one lane: 16 channels of one input pixel; it looks at every window that contains the pixel and takes the
 // window's error where the forward pass recorded this pixel as the window's winner.
-__global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t *e, int32_t *d, int32_t *absmax)
+// OUT 0: int32 sums + abs-max;  OUT 1: abs-max only;  OUT 2: Q_e codes (Eq.11) from the abs-max of an OUT 1 launch:
+// the sums are cheap to form twice (the gathered tensors are the small, pooled ones), so the wide tensor is never
+// written.
+template <int OUT>
+__global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t *e, int32_t *d, int32_t *absmax,
+                                   int8_t *q, const int32_t *exp_in, int32_t *exp_out)
 {
     const int c16 = g.C / 16;
     const size_t total = (size_t)g.N * g.H * g.W * c16;
-    int mx = 0;
+    int mx = 0, r = 7;
+    if (OUT == 2) {
+        const uint32_t M = (uint32_t)*absmax;
+        r = M ? sq_exponent_u32(M) : 7;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *exp_out = M ? *exp_in + r - 7 : *exp_in;
+    }
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         int cc = (int)(i % c16);
         size_t pix = i / c16;
@@ -90,27 +100,36 @@ __global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t 
         int q_hi = (x + g.pad) / g.stride;
         if (q_hi > g.Q - 1) q_hi = g.Q - 1;
         for (int p = p_lo; p <= p_hi; ++p)
-            for (int q = q_lo; q <= q_hi; ++q) {
-                const int my = (h - (p * g.stride - g.pad)) * g.S + (x - (q * g.stride - g.pad));
-                const size_t o = (((size_t)n * g.P + p) * g.Q + q) * g.C + cc * 16;
+            for (int qq = q_lo; qq <= q_hi; ++qq) {
+                const int my = (h - (p * g.stride - g.pad)) * g.S + (x - (qq * g.stride - g.pad));
+                const size_t o = (((size_t)n * g.P + p) * g.Q + qq) * g.C + cc * 16;
                 v4i av = *(const v4i *)(arg + o), ev = *(const v4i *)(e + o);
 #pragma unroll
                 for (int k = 0; k < 16; ++k)
                     if ((byte_at(av, k) & 0xff) == my) acc[k] += byte_at(ev, k);
             }
-        int32_t *o = d + pix * g.C + cc * 16;
+        if (OUT == 0) {
+            int32_t *o = d + pix * g.C + cc * 16;
 #pragma unroll
-        for (int k4 = 0; k4 < 4; ++k4) {
-            v4i w = {acc[4 * k4], acc[4 * k4 + 1], acc[4 * k4 + 2], acc[4 * k4 + 3]};
-            ((v4i *)o)[k4] = w;
+            for (int k4 = 0; k4 < 4; ++k4) {
+                v4i w = {acc[4 * k4], acc[4 * k4 + 1], acc[4 * k4 + 2], acc[4 * k4 + 3]};
+                ((v4i *)o)[k4] = w;
+            }
         }
+        if (OUT == 2) {
+            v4i o = {0, 0, 0, 0};
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            int av = acc[k] < 0 ? -acc[k] : acc[k];
-            mx = av > mx ? av : mx;
+            for (int k = 0; k < 16; ++k) set_byte(o, k, sq_code((int64_t)acc[k], r));
+            *(v4i *)(q + pix * g.C + cc * 16) = o;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                int av = acc[k] < 0 ? -acc[k] : acc[k];
+                mx = av > mx ? av : mx;
+            }
         }
     }
-    block_atomic_max_i32(mx, absmax);
+    if (OUT != 2) block_atomic_max_i32(mx, absmax);
 }
 
 __global__ void gap_sum_kernel(const int8_t *y, int N, int HW, int C, int32_t *sum)
@@ -175,34 +194,109 @@ __device__ double head_exp(double x)
     return ldexp(p, (int)k);
 }
 
+constexpr int HEAD_SOFTMAX_LDS = 4096;      // classes whose exps are staged in LDS (32 KB)
+
 __global__ void head_feat_kernel(const int32_t *gap, int n_elems, double denom, double *feat)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n_elems) feat[i] = (double)gap[i] / denom;
 }
 
-// logits[n][j] = b[j] + sum_k feat[n][k] W[j][k], one sequential fma chain per (n,j); tiles of
-// 16 x 16 outputs share their operands through LDS.
-__global__ void head_logits_kernel(int N, int F, int J, const double *feat, const double *W, const double *b,
-                                   double *logits)
+// The three matrix products of the head, each output one sequential fma chain in ascending reduction index
+// (the order is part of the head's definition):
+//     out(i,j) = init(j) + sum_k A(i,k) * B(j,k),    A(i,k) = A[i*sAi + k*sAk],  B(j,k) = B[j*sBj + k*sBk]
+//   logits : i = sample, j = class,   k = feature          init = bias
+//   dfeat  : i = sample, j = feature, k = class            out -> float(a / HW)
+//   update : i = class,  j = feature, k = sample           W(i,j) -= lr * a
+// A workgroup owns 32 x 32 outputs (2 x 2 per thread: four independent chains hide the fma latency) and walks
+// the reduction in chunks of 32 staged in LDS; the next chunk is fetched into registers while the current one
+// is multiplied, and every operand is fetched from memory once per 32 outputs instead of once per output.
+enum { HEAD_LOGITS = 0, HEAD_DFEAT = 1, HEAD_UPDATE = 2 };
+constexpr int HG_T = 32, HG_KC = 32, HG_LD = HG_KC + 2;
+
+struct HeadGemm {
+    int I, J, K;
+    const double *A, *B;
+    long sAi, sAk, sBj, sBk;
+    int a_kfast, b_kfast;        // which index is contiguous in memory (decides the loader's thread mapping)
+    const double *init;          // HEAD_LOGITS: bias
+    double *out;                 // HEAD_LOGITS: logits; HEAD_UPDATE: W (in place)
+    float *outf;                 // HEAD_DFEAT
+    long so;                     // row stride of the output
+    double denom;                // HEAD_DFEAT: HW
+    const int32_t *lr_slot;      // HEAD_UPDATE
+};
+
+template <int EPI>
+__global__ __launch_bounds__(256) void head_gemm_kernel(HeadGemm g)
 {
-    __shared__ double sf[16][33], sw[16][33];
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-    const int n = blockIdx.y * 16 + ty, j = blockIdx.x * 16 + tx;
-    double a = (j < J) ? b[j] : 0.0;
-    for (int k0 = 0; k0 < F; k0 += 32) {
-        for (int t = threadIdx.x; t < 16 * 32; t += 256) {
-            int row = t >> 5, col = t & 31;
-            int nn = blockIdx.y * 16 + row, jj = blockIdx.x * 16 + row;
-            sf[row][col] = (nn < N && k0 + col < F) ? feat[(size_t)nn * F + k0 + col] : 0.0;
-            sw[row][col] = (jj < J && k0 + col < F) ? W[(size_t)jj * F + k0 + col] : 0.0;
+    __shared__ __attribute__((aligned(16))) double sa[HG_T][HG_LD], sb[HG_T][HG_LD];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int i0 = blockIdx.y * HG_T, j0 = blockIdx.x * HG_T;
+    // loader: 4 elements of each operand per thread and chunk
+    int la_r[4], la_k[4], lb_r[4], lb_k[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int e = tid + 256 * r;
+        la_r[r] = g.a_kfast ? e >> 5 : e & 31; la_k[r] = g.a_kfast ? e & 31 : e >> 5;
+        lb_r[r] = g.b_kfast ? e >> 5 : e & 31; lb_k[r] = g.b_kfast ? e & 31 : e >> 5;
+    }
+    double ra[4], rb[4];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int ia = i0 + la_r[r], ka = k0 + la_k[r], jb = j0 + lb_r[r], kb = k0 + lb_k[r];
+            ra[r] = (ia < g.I && ka < g.K) ? g.A[ia * g.sAi + ka * g.sAk] : 0.0;
+            rb[r] = (jb < g.J && kb < g.K) ? g.B[jb * g.sBj + kb * g.sBk] : 0.0;
+        }
+    };
+    double a00 = 0.0, a01 = 0.0, a10 = 0.0, a11 = 0.0;
+    if (EPI == HEAD_LOGITS) {
+        a00 = a10 = (j0 + tx < g.J) ? g.init[j0 + tx] : 0.0;
+        a01 = a11 = (j0 + tx + 16 < g.J) ? g.init[j0 + tx + 16] : 0.0;
+    }
+    fetch(0);
+    for (int k0 = 0; k0 < g.K; k0 += HG_KC) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            sa[la_r[r]][la_k[r]] = ra[r];
+            sb[lb_r[r]][lb_k[r]] = rb[r];
         }
         __syncthreads();
-        const int kmax = F - k0 < 32 ? F - k0 : 32;
-        for (int k = 0; k < kmax; ++k) a = fma(sf[ty][k], sw[tx][k], a);
+        if (k0 + HG_KC < g.K) fetch(k0 + HG_KC);
+        const int kmax = g.K - k0 < HG_KC ? g.K - k0 : HG_KC;      // the chains never see a padded term
+        if (kmax == HG_KC) {
+#pragma unroll
+            for (int k = 0; k < HG_KC; ++k) {
+                const double x0 = sa[ty][k], x1 = sa[ty + 16][k], y0 = sb[tx][k], y1 = sb[tx + 16][k];
+                a00 = fma(x0, y0, a00); a01 = fma(x0, y1, a01);
+                a10 = fma(x1, y0, a10); a11 = fma(x1, y1, a11);
+            }
+        } else {
+            for (int k = 0; k < kmax; ++k) {
+                const double x0 = sa[ty][k], x1 = sa[ty + 16][k], y0 = sb[tx][k], y1 = sb[tx + 16][k];
+                a00 = fma(x0, y0, a00); a01 = fma(x0, y1, a01);
+                a10 = fma(x1, y0, a10); a11 = fma(x1, y1, a11);
+            }
+        }
         __syncthreads();
     }
-    if (n < N && j < J) logits[(size_t)n * J + j] = a;
+    double lr = 0.0;
+    if (EPI == HEAD_UPDATE) lr = ldexp((double)g.lr_slot[0], -g.lr_slot[1]);
+    auto finish = [&](int i, int j, double a) {
+        if (i >= g.I || j >= g.J) return;
+        const long o = i * g.so + j;
+        if (EPI == HEAD_LOGITS) g.out[o] = a;
+        else if (EPI == HEAD_DFEAT) g.outf[o] = (float)(a / g.denom);
+        else {
+            const double step = lr * a;
+            g.out[o] = g.out[o] - step;
+        }
+    };
+    finish(i0 + ty, j0 + tx, a00);
+    finish(i0 + ty, j0 + tx + 16, a01);
+    finish(i0 + ty + 16, j0 + tx, a10);
+    finish(i0 + ty + 16, j0 + tx + 16, a11);
 }
 
 // per sample (one block): softmax with max subtraction, loss term, dlogits.  The exps are evaluated in
@@ -211,11 +305,14 @@ __global__ void head_logits_kernel(int N, int F, int J, const double *feat, cons
 __global__ void head_softmax_kernel(int N, int J, const double *logits, const int32_t *labels, double *dl,
                                     double *lossn)
 {
+    extern __shared__ double s_exp[];          // J doubles when they fit, else the exps stay in global memory
     __shared__ double red[256];
     __shared__ double s_sum;
+    const bool staged = J <= HEAD_SOFTMAX_LDS;
     const int n = blockIdx.x;
     const double *lg = logits + (size_t)n * J;
     double *o = dl + (size_t)n * J;
+    double *ex = staged ? s_exp : o;
     double m = -1.0e300;
     for (int j = threadIdx.x; j < J; j += blockDim.x) m = lg[j] > m ? lg[j] : m;
     red[threadIdx.x] = m;
@@ -225,19 +322,27 @@ __global__ void head_softmax_kernel(int N, int J, const double *logits, const in
         __syncthreads();
     }
     m = red[0];
-    for (int j = threadIdx.x; j < J; j += blockDim.x) o[j] = head_exp(lg[j] - m);
+    for (int j = threadIdx.x; j < J; j += blockDim.x) ex[j] = head_exp(lg[j] - m);
     __syncthreads();
     const int lab = labels[n];
     if (threadIdx.x == 0) {
         double sum = 0.0;
-        for (int j = 0; j < J; ++j) sum = sum + o[j];
+        int j = 0;
+        for (; j + 8 <= J; j += 8) {           // loads first, then the additions in ascending order
+            double v[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) v[t] = ex[j + t];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) sum = sum + v[t];
+        }
+        for (; j < J; ++j) sum = sum + ex[j];
         s_sum = sum;
         lossn[n] = log(sum) - (lg[lab] - m);
     }
     __syncthreads();
     const double sum = s_sum;
     for (int j = threadIdx.x; j < J; j += blockDim.x) {
-        const double pj = o[j] / sum;
+        const double pj = ex[j] / sum;
         o[j] = (pj - (j == lab ? 1.0 : 0.0)) / (double)N;
     }
 }
@@ -251,33 +356,16 @@ __global__ void head_loss_kernel(int N, const double *lossn, double *loss)
     }
 }
 
-// d[n][k] = (float)((sum_j dl[n][j] W[j][k]) / HW), ascending j
-__global__ void head_dfeat_kernel(int N, int F, int J, int HW, const double *dl, const double *W, float *d)
+// b[j] -= lr * sum_n dl[n][j] (ascending n)
+__global__ void head_bias_update_kernel(int N, int J, const double *dl, double *b, const int32_t *lr_slot)
 {
-    int k = blockIdx.x * blockDim.x + threadIdx.x, n = blockIdx.y;
-    if (k >= F) return;
-    double a = 0.0;
-    for (int j = 0; j < J; ++j) a = fma(dl[(size_t)n * J + j], W[(size_t)j * F + k], a);
-    d[(size_t)n * F + k] = (float)(a / (double)HW);
-}
-
-// dW[j][k] = sum_n dl[n][j] feat[n][k] (ascending n), W -= lr dW; the k == 0 lane also does the bias
-__global__ void head_update_kernel(int N, int F, int J, const double *dl, const double *feat, double *W, double *b,
-                                   const int32_t *lr_slot)
-{
-    int k = blockIdx.x * blockDim.x + threadIdx.x, j = blockIdx.y;
-    if (k >= F) return;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= J) return;
     const double lr = ldexp((double)lr_slot[0], -lr_slot[1]);
-    double a = 0.0;
-    for (int n = 0; n < N; ++n) a = fma(dl[(size_t)n * J + j], feat[(size_t)n * F + k], a);
-    const double step = lr * a;
-    W[(size_t)j * F + k] = W[(size_t)j * F + k] - step;
-    if (k == 0) {
-        double s = 0.0;
-        for (int n = 0; n < N; ++n) s = s + dl[(size_t)n * J + j];
-        const double sb = lr * s;
-        b[j] = b[j] - sb;
-    }
+    double s = 0.0;
+    for (int n = 0; n < N; ++n) s = s + dl[(size_t)n * J + j];
+    const double sb = lr * s;
+    b[j] = b[j] - sb;
 }
 
 inline unsigned grid_for(size_t total)
@@ -318,8 +406,28 @@ extern "C" int eoq_maxpool_bwd(eoq_ctx *c, const uint8_t *arg, const int8_t *e, 
     if (((uintptr_t)arg | (uintptr_t)e | (uintptr_t)d) & 15) return EOQ_ERR_ARG;
     PoolGeom g{N, H, W, C, R, S, stride, pad, conv_out_dim(H, pad, R, stride), conv_out_dim(W, pad, S, stride)};
     if (g.P <= 0 || g.Q <= 0) return EOQ_ERR_SHAPE;
-    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid_for((size_t)N * H * W * (C / 16))), dim3(256), 0, c->stream, g, arg,
-                       e, d, absmax_slot);
+    hipLaunchKernelGGL(maxpool_bwd_kernel<0>, dim3(grid_for((size_t)N * H * W * (C / 16))), dim3(256), 0, c->stream, g,
+                       arg, e, d, absmax_slot, (int8_t *)nullptr, (const int32_t *)nullptr, (int32_t *)nullptr);
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}
+
+extern "C" int eoq_maxpool_bwd_sq(eoq_ctx *c, const uint8_t *arg, const int8_t *e, int32_t N, int32_t H, int32_t W,
+                                  int32_t C, int32_t R, int32_t S, int32_t stride, int32_t pad, int8_t *e_out,
+                                  int32_t *absmax_slot, const int32_t *exp_in, int32_t *exp_out)
+{
+    if (!c || !arg || !e || !e_out || !absmax_slot || !exp_in || !exp_out || N <= 0 || H <= 0 || W <= 0 || C <= 0 ||
+        R <= 0 || S <= 0 || stride <= 0 || pad < 0)
+        return EOQ_ERR_ARG;
+    if (C % 16 || pad >= R || pad >= S) return EOQ_ERR_SHAPE;
+    if (((uintptr_t)arg | (uintptr_t)e | (uintptr_t)e_out) & 15) return EOQ_ERR_ARG;
+    PoolGeom g{N, H, W, C, R, S, stride, pad, conv_out_dim(H, pad, R, stride), conv_out_dim(W, pad, S, stride)};
+    if (g.P <= 0 || g.Q <= 0) return EOQ_ERR_SHAPE;
+    const dim3 grid(grid_for((size_t)N * H * W * (C / 16)));
+    hipLaunchKernelGGL(maxpool_bwd_kernel<1>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr, absmax_slot,
+                       (int8_t *)nullptr, (const int32_t *)nullptr, (int32_t *)nullptr);
+    hipLaunchKernelGGL(maxpool_bwd_kernel<2>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr, absmax_slot,
+                       e_out, exp_in, exp_out);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }
@@ -364,13 +472,24 @@ extern "C" int eoq_head_fwd_bwd(eoq_ctx *c, int32_t N, int32_t F, int32_t J, int
     hipStream_t s = c->stream;
     hipLaunchKernelGGL(head_feat_kernel, dim3((N * F + 255) / 256), dim3(256), 0, s, gap_sum, N * F,
                        128.0 * (double)HW, feat);
-    hipLaunchKernelGGL(head_logits_kernel, dim3((J + 15) / 16, (N + 15) / 16), dim3(256), 0, s, N, F, J, feat, Wfc,
-                       bfc, logits);
-    hipLaunchKernelGGL(head_softmax_kernel, dim3(N), dim3(256), 0, s, N, J, logits, labels, dl, lossn);
+    const dim3 blk(256);
+    auto tiles = [](int v) { return (unsigned)((v + HG_T - 1) / HG_T); };
+    HeadGemm lg{};
+    lg.I = N; lg.J = J; lg.K = F; lg.A = feat; lg.sAi = F; lg.sAk = 1; lg.B = Wfc; lg.sBj = F; lg.sBk = 1;
+    lg.a_kfast = 1; lg.b_kfast = 1; lg.init = bfc; lg.out = logits; lg.so = J;
+    hipLaunchKernelGGL(head_gemm_kernel<HEAD_LOGITS>, dim3(tiles(J), tiles(N)), blk, 0, s, lg);
+    const size_t sm_bytes = J <= HEAD_SOFTMAX_LDS ? sizeof(double) * (size_t)J : 0;
+    hipLaunchKernelGGL(head_softmax_kernel, dim3(N), dim3(256), sm_bytes, s, N, J, logits, labels, dl, lossn);
     hipLaunchKernelGGL(head_loss_kernel, dim3(1), dim3(64), 0, s, N, lossn, loss);
-    hipLaunchKernelGGL(head_dfeat_kernel, dim3((F + 255) / 256, N), dim3(256), 0, s, N, F, J, HW, dl, Wfc, d);
-    hipLaunchKernelGGL(head_update_kernel, dim3((F + 255) / 256, J), dim3(256), 0, s, N, F, J, dl, feat, Wfc, bfc,
-                       lr_slot);
+    HeadGemm df{};
+    df.I = N; df.J = F; df.K = J; df.A = dl; df.sAi = J; df.sAk = 1; df.B = Wfc; df.sBj = 1; df.sBk = F;
+    df.a_kfast = 1; df.b_kfast = 0; df.outf = d; df.so = F; df.denom = (double)HW;
+    hipLaunchKernelGGL(head_gemm_kernel<HEAD_DFEAT>, dim3(tiles(F), tiles(N)), blk, 0, s, df);
+    HeadGemm up{};
+    up.I = J; up.J = F; up.K = N; up.A = dl; up.sAi = 1; up.sAk = J; up.B = feat; up.sBj = 1; up.sBk = F;
+    up.a_kfast = 0; up.b_kfast = 0; up.out = Wfc; up.so = F; up.lr_slot = lr_slot;
+    hipLaunchKernelGGL(head_gemm_kernel<HEAD_UPDATE>, dim3(tiles(F), tiles(J)), blk, 0, s, up);
+    hipLaunchKernelGGL(head_bias_update_kernel, dim3((J + 255) / 256), dim3(256), 0, s, N, J, dl, bfc, lr_slot);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }

@@ -22,7 +22,7 @@ EXPORTS = [
     "eoq_create", "eoq_destroy", "eoq_strerror", "eoq_status", "eoq_workspace_bytes", "eoq_fill_zero",
     "eoq_quantize", "eoq_pre_bias", "eoq_conv_fwd", "eoq_conv_bwd_data", "eoq_conv_bwd_data_sq", "eoq_conv_bwd_weight",
     "eoq_relu_bwd", "eoq_relu_bwd_recompute", "eoq_merge_absmax", "eoq_requant_epilogue", "eoq_update_int8", "eoq_update_scalars",
-    "eoq_maxpool_fwd", "eoq_maxpool_bwd", "eoq_gap_sum", "eoq_broadcast_hw", "eoq_head_workspace_bytes",
+    "eoq_maxpool_fwd", "eoq_maxpool_bwd", "eoq_maxpool_bwd_sq", "eoq_gap_sum", "eoq_broadcast_hw", "eoq_head_workspace_bytes",
     "eoq_head_fwd_bwd",
 ]
 
@@ -85,6 +85,7 @@ def _load():
     lib.eoq_update_scalars.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.eoq_maxpool_fwd.argtypes = [vp, vp] + [i32] * 8 + [vp, vp, vp, vp]
     lib.eoq_maxpool_bwd.argtypes = [vp, vp, vp] + [i32] * 8 + [vp, vp]
+    lib.eoq_maxpool_bwd_sq.argtypes = [vp, vp, vp] + [i32] * 8 + [vp, vp, vp, vp]
     lib.eoq_gap_sum.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.eoq_broadcast_hw.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.eoq_head_workspace_bytes.argtypes = [i32, i32, i32]
@@ -214,6 +215,10 @@ class Context:
     def maxpool_bwd(self, arg, e, N, H, W, Cc, R, S, stride, pad, d, absmax_slot):
         _check(_lib.eoq_maxpool_bwd(self._h, _ptr(arg), _ptr(e), N, H, W, Cc, R, S, stride, pad, _ptr(d),
                                     _ptr(absmax_slot)), "eoq_maxpool_bwd")
+
+    def maxpool_bwd_sq(self, arg, e, N, H, W, Cc, R, S, stride, pad, e_out, absmax_slot, exp_in, exp_out):
+        _check(_lib.eoq_maxpool_bwd_sq(self._h, _ptr(arg), _ptr(e), N, H, W, Cc, R, S, stride, pad, _ptr(e_out),
+                                       _ptr(absmax_slot), _ptr(exp_in), _ptr(exp_out)), "eoq_maxpool_bwd_sq")
 
     def gap_sum(self, y, N, HW, Cc, out):
         _check(_lib.eoq_gap_sum(self._h, _ptr(y), N, HW, Cc, _ptr(out)), "eoq_gap_sum")

@@ -8,10 +8,18 @@ convolution on the biased block input when the shape changes).  Everything a ste
 on the device: exponents, abs-max statistics, scalar-gradient sums and the learning rate live in
 device slots, so a step enqueues kernels without a single host synchronisation and can be
 captured into a HIP graph.
+
+The backward pass runs on two HIP streams of equal priority: the error chain (ReLU backward, Q_e,
+backward-data convolution, block merges) on the main stream, and each layer's parameter chain
+(weight-gradient convolution, Q_g, update) on a side stream, joined by events: the parameter chain
+of layer l starts when e3 of layer l exists, its update waits until the backward-data convolution has
+read the old weights, and an error buffer that the side stream still reads is not handed out again
+before that read has finished.  The two chains share no scratch memory.
 """
 from __future__ import annotations
 
 import math
+from collections import deque
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -70,11 +78,18 @@ class _Slots:
 
 
 class FixupNet:
-    def __init__(self, cfg: dict, batch: int, seed: int = 0, trace: bool = False):
+    N_EBUF = 8     # rotating error buffers: enough that the main stream rarely waits for the side stream's reads
+
+    def __init__(self, cfg: dict, batch: int, seed: int = 0, trace: bool = False, overlap: bool = True):
         assert torch.cuda.is_available(), "libeoq needs the GPU; there is no CPU path"
         self.cfg, self.N, self.seed, self.tracing = dict(cfg), batch, seed, trace
         self.dev = torch.device("cuda")
         self.ctx = eoq.Context()
+        self.overlap = overlap
+        self.main = torch.cuda.current_stream()
+        self.side = torch.cuda.Stream()            # default priority
+        self.ctx_w = eoq.Context(self.side)        # parameter chain: dW, Q_g, update
+        self._pending: dict[int, torch.cuda.Event] = {}     # error buffer -> last read of it on the side stream
         self.trace: dict[str, object] = {}
         self.prof = None                   # list of (kind, unit, work, start event, end event) while profiling
         bt = cfg["block"]
@@ -173,8 +188,7 @@ class FixupNet:
         self.y_out = i8(self.blocks[-1].units[-1].out_shape)
         max_act = max(max(int(np.prod(u.out_shape)), int(np.prod(u.in_shape))) for u in all_units)
         max_w = max(u.w.numel() for u in all_units)
-        self.ebuf = [i8((max_act,)) for _ in range(4)]
-        self.dacc = i32((max_act,))
+        self.ebuf = [i8((max_act,)) for _ in range(self.N_EBUF)]
         self.gacc = i32((max_w,))
         self.gq = i8((max_w,))
         ws_bytes = 16
@@ -182,6 +196,9 @@ class FixupNet:
             for op in (eoq.OP_CONV_FWD, eoq.OP_CONV_BWD_DATA, eoq.OP_CONV_BWD_WEIGHT):
                 ws_bytes = max(ws_bytes, eoq.Context.workspace_bytes(u.desc, op))
         self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=self.dev)
+        self.ws_w = torch.empty((ws_bytes,), dtype=torch.uint8, device=self.dev)     # the side stream's own scratch
+        for u in all_units:
+            u.ev_e3, u.ev_dx, u.ev_done = (torch.cuda.Event() for _ in range(3))
         # ---- slots -------------------------------------------------------------------------------
         self.sl = _Slots()
         self._plan_slots()
@@ -280,20 +297,31 @@ class FixupNet:
         i = self.scal_idx[name]
         return self.scal[i:i + 1]
 
-    def _call(self, kind, unit, work, fn, *args, **kw):
+    def _call(self, kind, unit, work, fn, *args, stream=None, **kw):
         """Run one library call; when profiling, bracket it with events on the stream it is enqueued on."""
         if self.prof is None:
             return fn(*args, **kw)
+        stream = stream or self.main
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
+        e0.record(stream)
         r = fn(*args, **kw)
-        e1.record()
+        e1.record(stream)
         self.prof.append((kind, unit, work, e0, e1))
         return r
 
     def _rec(self, name, t):
         if self.tracing:
+            if self.overlap:
+                torch.cuda.synchronize()      # inspection only: the copy below runs on the main stream
             self.trace[name] = t.detach().clone()
+
+    def _acquire(self, bufs):
+        """Next free error buffer; if the side stream still reads its previous content, the main stream waits."""
+        b = bufs.popleft()
+        ev = self._pending.pop(b.data_ptr(), None)
+        if ev is not None:
+            self.main.wait_event(ev)
+        return b
 
     def set_lr(self, m: int, j: int):
         self.lr.copy_(torch.tensor([m, j], dtype=torch.int32))
@@ -371,13 +399,16 @@ class FixupNet:
         self._rec("gap.sum", self.gap)
 
     # ------------------------------------------------------------------------------------------ backward
-    def _grad_and_update(self, u: Unit, e3):
-        """g_w = Q_g(e3 * x1) (Eq.4, Eq.12) and W <- Q_w(W - Q_u(lr g)) (Eq.13)."""
-        c = self.ctx
+    def _grad(self, u: Unit, e3):
+        """g_w = Q_g(e3 * x1) (Eq.4, Eq.12), on the side stream once e3 exists."""
+        c, ws, st = (self.ctx_w, self.ws_w, self.side) if self.overlap else (self.ctx, self.ws, self.main)
+        if self.overlap:
+            u.ev_e3.record(self.main)
+            self.side.wait_event(u.ev_e3)
         n = u.w.numel()
         G = self.gacc[:n]
         self._call("conv_bwd_weight", u.name, self._conv_work(u), c.conv_bwd_weight, u.desc, e3, u.u, G,
-                   self.s32(u.name + ".M_G"), self.ws)
+                   self.s32(u.name + ".M_G"), ws, stream=st)
         g = self.gq[:n]
         c.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=G, absmax=self.s32(u.name + ".M_G"), exp_in=self.s32(u.E3),
                            exp_in_off=-7, out=g, exp_out=self.s32(u.name + ".Eg"),
@@ -400,7 +431,7 @@ class FixupNet:
             c.relu_bwd(e0[:n_out], u.mask, None, e1[:n_out], self.s64(u.name + ".S_e1"), None,
                        self.s32(u.name + ".M_e1"))
         if u.gamma:
-            e3 = bufs.pop()
+            e3 = self._acquire(bufs)
             c.requant_epilogue(eoq.RQ_SQ_GAMMA, n_out, src_a=e1[:n_out], gamma=self.sc(u.gamma),
                                absmax=self.s32(u.name + ".M_e1"), exp_in=self.s32(u.E0), out=e3[:n_out],
                                exp_out=self.s32(u.E3))
@@ -408,18 +439,26 @@ class FixupNet:
             e3 = e1
         if self.tracing:
             self._rec(u.name + ".e3", e3[:n_out].view(u.out_shape))
-        g = self._grad_and_update(u, e3[:n_out])
+        g = self._grad(u, e3[:n_out])
         e4 = None
         if need_dx:
             n_in = int(np.prod(u.in_shape))
-            e4 = bufs.pop()
+            e4 = self._acquire(bufs)
             self._call("conv_bwd_data", u.name, 2 * self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
                        e4[:n_in], self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
                        self.s64(u.name + ".S_e4"), self.ws)
             if self.tracing:
                 self._rec(u.name + ".e4", e4[:n_in].view(u.in_shape))
-        # all uses of the old weights are enqueued: update them
-        c.update_int8(u.w, g, self.s32(u.name + ".Eg"), self.s32(u.name + ".gmax"), self.lr)
+        # W <- Q_w(W - Q_u(lr g)) (Eq.13) once every reader of the old weights has run
+        if self.overlap:
+            if need_dx:
+                u.ev_dx.record(self.main)
+                self.side.wait_event(u.ev_dx)
+            self.ctx_w.update_int8(u.w, g, self.s32(u.name + ".Eg"), self.s32(u.name + ".gmax"), self.lr)
+            u.ev_done.record(self.side)
+            self._pending[e3.data_ptr()] = u.ev_done       # e3 may not be overwritten before dW has read it
+        else:
+            c.update_int8(u.w, g, self.s32(u.name + ".Eg"), self.s32(u.name + ".gmax"), self.lr)
         if u.gamma:
             bufs.append(e3)
         return e4, e1
@@ -462,11 +501,9 @@ class FixupNet:
         d = s.desc
         if self.pool:
             n = int(np.prod(s.out_shape))
-            Dacc = self.dacc[:n]
-            c.maxpool_bwd(self.pool_arg, e, d.N, d.P, d.Q, d.K, 3, 3, 2, 1, Dacc, self.s32("pool.M"))
-            e2 = bufs.pop()
-            c.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=Dacc, absmax=self.s32("pool.M"),
-                               exp_in=self.s32(self.blocks[0].name + ".E_in"), out=e2[:n], exp_out=self.s32("pool.E"))
+            e2 = self._acquire(bufs)
+            c.maxpool_bwd_sq(self.pool_arg, e, d.N, d.P, d.Q, d.K, 3, 3, 2, 1, e2[:n], self.s32("pool.M"),
+                             self.s32(self.blocks[0].name + ".E_in"), self.s32("pool.E"))
             bufs.append(e)
             e = e2
             if self.tracing:
@@ -477,6 +514,12 @@ class FixupNet:
     def _update_scalars(self):
         self.ctx.update_scalars(self.scal, self.sgrad_tab, len(self.sgrad_entries), self.sums64, self.slots32, self.lr,
                                 self.g_code, self.g_exp)
+
+    def _join(self):
+        """End of a step: everything the side stream did is ordered before what the main stream does next."""
+        if self.overlap:
+            self.main.wait_stream(self.side)
+        self._pending.clear()
 
     # ------------------------------------------------------------------------------------------ whole steps
     def _zero_stats(self):
@@ -494,8 +537,8 @@ class FixupNet:
         c.head_fwd_bwd(N, F, J, hw, self.gap, self.Wfc, self.bfc, self.labels, self.lr, self.loss, self.d32,
                        self.logits, self.head_ws)
         c.quantize(self.d32, eoq.SQ, 0, self.head_codes, self.s32("head.E"))     # Q_e on the head's error
-        bufs = list(self.ebuf)
-        e = bufs.pop()
+        bufs = deque(self.ebuf)
+        e = self._acquire(bufs)
         n_out = N * hw * F
         c.broadcast_hw(self.head_codes, N, hw, F, e[:n_out])
         if self.tracing:
@@ -505,6 +548,7 @@ class FixupNet:
         e = self._backward_blocks(e, bufs)
         self._backward_stem(e, bufs)
         self._update_scalars()
+        self._join()
         if self.tracing:
             self._rec("slots32", self.slots32)
             self._rec("g_code", self.g_code)
@@ -533,13 +577,14 @@ class FixupNet:
             b0.a_in.copy_(at)
         c.pre_bias(at, self.sc(b0.units[0].b_pre), b0.units[0].u)            # Eq.2 line x1
         self._forward_blocks()
-        bufs = list(self.ebuf)
-        e = bufs.pop()
+        bufs = deque(self.ebuf)
+        e = self._acquire(bufs)
         n = e0.size
         e[:n].copy_(torch.from_numpy(np.ascontiguousarray(e0)).to(self.dev).view(-1))
         self.s32(self.E_top).fill_(E0)
         e = self._backward_blocks(e, bufs)
         self._update_scalars()
+        self._join()
         if self.tracing:
             self._rec("slots32", self.slots32)
             self._rec("g_code", self.g_code)
@@ -557,4 +602,4 @@ class FixupNet:
         return {n: int(v[i]) for n, i in self.scal_idx.items()}
 
     def status(self) -> int:
-        return self.ctx.status()
+        return self.ctx.status() | self.ctx_w.status()

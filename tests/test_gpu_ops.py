@@ -323,6 +323,13 @@ def test_pool_gap_broadcast(ctx):
     ctx.maxpool_bwd(argd, dev(e), N, H, W, Cc, 3, 3, 2, 1, d, slot)
     want = oo.maxpool_bwd(e, arg, a.shape)
     assert np.array_equal(host(d), want) and int(host(slot)[0]) == int(np.abs(want).max())
+    # the same sums followed by Q_e without the int32 tensor; also the all-zero error (exponent passes through)
+    for ee, E_in in ((e, -11), (np.zeros_like(e), 5)):
+        q, slot2 = zeros(a.shape, torch.int8), zeros((1,), torch.int32)
+        ex = dev(np.array([E_in, 99], dtype=np.int32))
+        ctx.maxpool_bwd_sq(argd, dev(ee), N, H, W, Cc, 3, 3, 2, 1, q, slot2, ex[0:1], ex[1:2])
+        codes, E_out = oq.sq_int(oo.maxpool_bwd(ee, arg, a.shape), E_in)
+        assert np.array_equal(host(q), codes) and int(host(ex)[1]) == E_out
     s = zeros((N, Cc), torch.int32)
     ctx.gap_sum(dev(a), N, H * W, Cc, s)
     assert np.array_equal(host(s), a.astype(np.int64).sum(axis=(1, 2)))
