@@ -150,12 +150,15 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
     int ld_q = ch_begin % p.tiles_q;
     int ld_p = (ch_begin / p.tiles_q) % p.tiles_p, ld_n = ch_begin / (p.tiles_q * p.tiles_p);
 
+    int ld_i = 0;                                  // chunks requested so far; past the range every load is out of range
     auto load_chunk = [&](v4i (&re)[E_LOADS], v4i (&ru)[U_LOADS]) {
+        const bool live = ld_i < nch;
+        ++ld_i;
         const int p0 = ld_p * p.PR, q0 = ld_q * p.PQ;
         const int base_e = ((ld_n * p.P + p0) * p.Q + q0) * p.K;
 #pragma unroll
         for (int i = 0; i < E_LOADS; ++i) {
-            const bool ok = p0 + e_dp[i] < p.P && q0 + e_dq[i] < p.Q;
+            const bool ok = live && p0 + e_dp[i] < p.P && q0 + e_dq[i] < p.Q;
             const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_e, ok ? base_e + e_off[i] : OOB, 0, 0);
             re[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
         }
@@ -164,8 +167,8 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
                                      : ((ld_n * p.H + h0) * p.W + w0) * p.C;
 #pragma unroll
         for (int i = 0; i < U_LOADS; ++i) {
-            const bool ok = p.pad4_S4 ? (p0 + u_py[i] < p.P && q0 + u_px[i] < p.Q)
-                                      : ((unsigned)(h0 + u_py[i]) < (unsigned)p.H && (unsigned)(w0 + u_px[i]) < (unsigned)p.W);
+            const bool ok = live && (p.pad4_S4 ? (p0 + u_py[i] < p.P && q0 + u_px[i] < p.Q)
+                                               : ((unsigned)(h0 + u_py[i]) < (unsigned)p.H && (unsigned)(w0 + u_px[i]) < (unsigned)p.W));
             const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, ok ? base_u + u_off[i] : OOB, 0, 0);
             ru[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
         }
@@ -179,51 +182,67 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
         for (int i = 0; i < U_LOADS; ++i)
             if (u_dst[i] >= 0) *(v4i *)(base + u_dst[i]) = ru[i];
     };
-    auto compute_chunk = [&](int buf) {
+    auto compute_half = [&](int buf, int j) {      // one of the two 32-pixel reduction steps of a chunk
         const int8_t *base = lds + buf;
+        v4i a[TK];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            v4i a[TK];
+        for (int tk = 0; tk < TK; ++tk) {
+            const v2i lo = lds_read_tr8(base + a_off[2 * j] + tk * 32);
+            const v2i hi = lds_read_tr8(base + a_off[2 * j + 1] + tk * 32);
+            a[tk] = v4i{lo[0], lo[1], hi[0], hi[1]};
+        }
 #pragma unroll
-            for (int tk = 0; tk < TK; ++tk) {
-                const v2i lo = lds_read_tr8(base + a_off[2 * j] + tk * 32);
-                const v2i hi = lds_read_tr8(base + a_off[2 * j + 1] + tk * 32);
-                a[tk] = v4i{lo[0], lo[1], hi[0], hi[1]};
-            }
+        for (int t = 0; t < TAPS; ++t) {
+            if (FULL || tap0 + t < p.RS) {
 #pragma unroll
-            for (int t = 0; t < TAPS; ++t) {
-                if (FULL || tap0 + t < p.RS) {
+                for (int tc = 0; tc < TC; ++tc) {
+                    const v2i lo = lds_read_tr8(base + b_off[2 * j] + tap_off[t] + tc * 32);
+                    const v2i hi = lds_read_tr8(base + b_off[2 * j + 1] + tap_off[t] + tc * 32);
+                    const v4i b = v4i{lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
-                    for (int tc = 0; tc < TC; ++tc) {
-                        const v2i lo = lds_read_tr8(base + b_off[2 * j] + tap_off[t] + tc * 32);
-                        const v2i hi = lds_read_tr8(base + b_off[2 * j + 1] + tap_off[t] + tc * 32);
-                        const v4i b = v4i{lo[0], lo[1], hi[0], hi[1]};
-#pragma unroll
-                        for (int tk = 0; tk < TK; ++tk)
-                            acc[tk][tc][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[tk], b, acc[tk][tc][t], 0, 0, 0);
-                    }
+                    for (int tk = 0; tk < TK; ++tk)
+                        acc[tk][tc][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[tk], b, acc[tk][tc][t], 0, 0, 0);
                 }
             }
         }
     };
 
-    // Software pipeline over the pixel chunks, unrolled twice for the two register sets: entering iteration i,
-    // LDS buffer i%2 holds chunk i and one register set holds chunk i+1; the iteration issues the loads of
-    // chunk i+2 into the other set, multiplies chunk i, and moves chunk i+1 into the other LDS buffer.
-    v4i re0[E_LOADS], ru0[U_LOADS], re1[E_LOADS], ru1[U_LOADS];
-    if (nch > 0) load_chunk(re0, ru0);
-    if (nch > 1) load_chunk(re1, ru1);
-    if (nch > 0) store_chunk(0, re0, ru0);
+    // Software pipeline over the pixel chunks with a ring of D register sets, unrolled D times so that the ring is
+    // indexed statically.  Entering step i: LDS buffer i%2 holds chunk i, the register sets hold chunks i+1 .. i+D-1
+    // (loaded or in flight).  The step requests chunk i+D, multiplies chunk i and moves chunk i+1 into the other LDS
+    // buffer.  Every load of a step is unconditional (past the range it is out of range: no traffic, zeros), so the
+    // number of loads in flight at the wait before the LDS stores is a compile-time constant and only the oldest
+    // set is waited for; the order of the phases is pinned with scheduling barriers.
+    constexpr int D = U_LOADS > 2 ? 2 : 4;
+    static_assert(D % 2 == 0, "buffer parity follows the chunk index");
+    v4i re[D][E_LOADS], ru[D][U_LOADS];
+#pragma unroll
+    for (int d = 0; d < D; ++d) load_chunk(re[d], ru[d]);
+    store_chunk(0, re[0], ru[0]);
     __syncthreads();
-    for (int i = 0; i < nch; i += 2) {
-        if (i + 2 < nch) load_chunk(re0, ru0);
-        compute_chunk(0);
-        if (i + 1 < nch) store_chunk(STAGE_BYTES, re1, ru1);
-        __syncthreads();
-        if (i + 1 < nch) {
-            if (i + 3 < nch) load_chunk(re1, ru1);
-            compute_chunk(STAGE_BYTES);
-            if (i + 2 < nch) store_chunk(0, re0, ru0);
+    int i = 0;
+    for (; i + D <= nch; i += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int buf = (d & 1) ? STAGE_BYTES : 0;
+            load_chunk(re[d], ru[d]);                                     // chunk i+d+D
+            __builtin_amdgcn_sched_barrier(0);
+            compute_half(buf, 0);                                         // chunk i+d
+            __builtin_amdgcn_sched_barrier(0);
+            store_chunk(STAGE_BYTES - buf, re[(d + 1) % D], ru[(d + 1) % D]);   // chunk i+d+1
+            __builtin_amdgcn_sched_barrier(0);
+            compute_half(buf, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < D - 1; ++d) {
+        if (i + d < nch) {                                                // uniform
+            const int buf = (d & 1) ? STAGE_BYTES : 0;
+            compute_half(buf, 0);
+            store_chunk(STAGE_BYTES - buf, re[(d + 1) % D], ru[(d + 1) % D]);
+            compute_half(buf, 1);
             __syncthreads();
         }
     }
