@@ -136,14 +136,21 @@ int eoq_conv_bwd_data(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, 
 
 /* ---- backward-data convolution with Q_e fused: Eq.3 line e4 = Q_e(e3 * w) (Eq.11) ---------------
  * Same result as eoq_conv_bwd_data followed by eoq_requant_epilogue(EOQ_RQ_SQ_ACC), without the int32
- * round trip through memory: the scale quantiser needs max|d| before any element can be quantised, so
- * the convolution is evaluated twice -- the first pass only max-combines max|d| into *absmax_slot (which
- * the caller zeroed), the second recomputes d and writes e4 = clamp(R(d * 2^(7-r))), r = R(log2 max|d|),
- * *exp_out = *exp_in + exp_in_off + r - 7 and, when sum_out is non-NULL, *sum_out += sum of the e4 codes
- * (the bias gradient of Eq.4).  Requires 127^2 * R*S*K < 2^30. */
+ * round trip through memory and with ONE evaluation of the convolution.  The scale quantiser needs max|d|
+ * before any element can be coded, so the convolution kernel max-combines max|d| into *absmax_slot (which
+ * the caller zeroed) and stores every sum as a 16-bit block-scaled value in the workspace (top 14 bits
+ * relative to the tile's own maximum plus a sticky bit); a second, streaming kernel rounds these to
+ * e4 = clamp(R(d * 2^(7-r))), r = R(log2 max|d|) -- exactly, because the rounding position is at least 6 bits
+ * above any dropped bit -- and sets *exp_out = *exp_in + exp_in_off + r - 7 (all-zero d: codes 0, exponent
+ * *exp_in + exp_in_off).  When sum_out is non-NULL, *sum_out += sum of the e4 codes (the bias gradient of Eq.4).
+ * Optionally the ReLU backward step of the layer whose output this input is (Eq.3 line e1) is applied in the
+ * same pass: with mask_bits (that layer's forward mask, one bit per element, NULL = all ones) and e1
+ * non-NULL, e1 = e4 where the bit is set and 0 elsewhere, *sum_e1 += sum(e1), *absmax_e1 max= max|e1|
+ * (each may be NULL).  e4 may be NULL when only e1 is wanted.  Requires 127^2 * R*S*K < 2^30. */
 int eoq_conv_bwd_data_sq(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, const int8_t *w, int8_t *e4,
                          int32_t *absmax_slot, const int32_t *exp_in, int32_t exp_in_off, int32_t *exp_out,
-                         int64_t *sum_out, void *ws, size_t ws_bytes);
+                         int64_t *sum_out, const uint32_t *mask_bits, int8_t *e1, int64_t *sum_e1,
+                         int32_t *absmax_e1, void *ws, size_t ws_bytes);
 
 /* ---- weight-gradient convolution: Eq.4 line g_w before Q_g ------------------------------------
  * g_acc[k,r,s,c] = sum_{n,p,q} e[n,p,q,k] * u[n, p*stride+r-pad, q*stride+s-pad, c], the exact integer

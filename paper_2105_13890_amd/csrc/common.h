@@ -11,9 +11,11 @@ struct eoq_ctx {
     int device;
     uint32_t *d_status;   // device status word (eoq_flag_bits)
     int32_t *d_scratch;   // EOQ_SCRATCH_SLOTS int32 slots for call-internal statistics
+    int64_t *d_partials;  // EOQ_PARTIAL_SLOTS int64 per-workgroup partial sums of the call in flight on this stream
 };
 
 constexpr int EOQ_SCRATCH_SLOTS = 64;
+constexpr int EOQ_PARTIAL_SLOTS = 2 * 32768;
 constexpr int CODE_MAX = 127;
 
 #define EOQ_HIP(expr)                                  \
@@ -110,24 +112,33 @@ __device__ __forceinline__ void atomic_add_i64(int64_t *p, int64_t v)
     atomicAdd((unsigned long long *)p, (unsigned long long)v);
 }
 
-// ---- block-level combination (blocks of up to 256 threads = 4 waves): one atomic per block ----
+// ---- block-level combination (blocks of up to 1024 threads = 16 waves): at most one atomic per block ----
+// Atomics on ONE address are served one after the other by the memory side (a few nanoseconds each), so a kernel
+// that ends with thousands of them spends longer there than on its data.  Hence: few, large blocks for kernels
+// that reduce; and a maximum is only sent when it would raise the value the slot already holds (the slot only
+// ever grows, so a stale read can at worst cause an unnecessary atomic).
+__device__ __forceinline__ void slot_atomic_max_i32(int32_t *slot, int v)
+{
+    if (v > *(volatile int32_t *)slot) atomicMax(slot, v);
+}
+
 __device__ __forceinline__ void block_atomic_max_i32(int v, int32_t *slot)
 {
-    __shared__ int sm_max[4];
+    __shared__ int sm_max[16];
     v = wave_max_i32(v);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
     if (lane == 0) sm_max[wave] = v;
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int i = 1; i < nw; ++i) v = sm_max[i] > v ? sm_max[i] : v;
-        if (v) atomicMax(slot, v);
+        slot_atomic_max_i32(slot, v);
     }
     __syncthreads();   // the staging array may be reused by the next call
 }
 
 __device__ __forceinline__ void block_atomic_add_i64(int64_t v, int64_t *slot)
 {
-    __shared__ int64_t sm_sum[4];
+    __shared__ int64_t sm_sum[16];
     v = wave_sum_i64(v);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
     if (lane == 0) sm_sum[wave] = v;
@@ -137,6 +148,20 @@ __device__ __forceinline__ void block_atomic_add_i64(int64_t v, int64_t *slot)
         if (v) atomic_add_i64(slot, v);
     }
     __syncthreads();
+}
+
+// block-wide sum, valid in thread 0 only
+__device__ __forceinline__ int64_t block_sum_i64(int64_t v)
+{
+    __shared__ int64_t sm_bs[16];
+    v = wave_sum_i64(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    if (lane == 0) sm_bs[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0)
+        for (int i = 1; i < nw; ++i) v += sm_bs[i];
+    __syncthreads();
+    return v;
 }
 
 static inline int conv_out_dim(int in, int pad, int k, int st) { return (in + 2 * pad - k) / st + 1; }

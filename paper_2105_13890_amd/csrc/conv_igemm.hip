@@ -50,16 +50,20 @@ struct IgemmParams {
     int32_t sq_exp_off;
     int32_t *sq_exp_out;
     int64_t *sq_sum_out;
+    // EPI_D16: 16-bit block-scaled output of the backward-data convolution (one shift per workgroup tile)
+    int16_t *d16;
+    int32_t *tile_shift;
     // EPI_RELU_BWD: ReLU backward with the Q_a1 output recomputed instead of read back
     const int8_t *rb_e0;
     const uint16_t *rb_mask16;
     int8_t *rb_e1;
     int64_t *rb_sum_e1, *rb_sum_e1t;
+    int64_t *rb_part;          // per-workgroup partial sums [tiles][2] (NULL: atomics on the two slots)
     int32_t *rb_absmax;
 };
 
 enum { MODE_FWD = 0, MODE_BWD_DATA = 1 };
-enum { EPI_FWD = 0, EPI_ACC = 1, EPI_ABSMAX = 2, EPI_SQ = 3, EPI_RELU_BWD = 4 };
+enum { EPI_FWD = 0, EPI_ACC = 1, EPI_ABSMAX = 2, EPI_SQ = 3, EPI_RELU_BWD = 4, EPI_D16 = 5 };
 
 __device__ __forceinline__ void set_byte(v4i &v, int i, int code)
 {
@@ -445,6 +449,40 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
         block_atomic_max_i32(mx0, p.absmax);
         return;
     }
+    // Block-scaled 16-bit output (the scale quantiser of Eq.11 needs max|d| of the WHOLE tensor before any element
+    // can be coded, so the exact 32-bit sums would have to be stored or recomputed).  Instead each workgroup keeps,
+    // relative to the largest magnitude of ITS tile, the top 14 bits of every sum plus a sticky bit (any dropped
+    // bit set) -- 16 bits per element.  The final rounding position r-7 (r from the global maximum) lies at least 6
+    // bits above the dropped bits of every tile, so round-half-even of the exact sum is recovered exactly from
+    // (kept bits, sticky bit): the rounding bit is a kept bit and the sticky bit joins the bits below it.
+    int d16_s = 0;
+    if (EPI == EPI_D16) {
+        int mx0 = 0;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int v = acc[i][jn][e];
+                    const int av = v < 0 ? -v : v;
+                    mx0 = av > mx0 ? av : mx0;
+                }
+        mx0 = wave_max_i32(mx0);
+        int *red = (int *)lds;                       // the main loop is done with LDS (barrier above)
+        if (lane == 0) red[wave] = mx0;
+        __syncthreads();
+        int tmax = red[0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) tmax = red[w] > tmax ? red[w] : tmax;
+        __syncthreads();                             // before the staging below overwrites red[]
+        const int ploc = tmax ? 31 - __clz(tmax) : 0;
+        d16_s = ploc > 13 ? ploc - 13 : 0;
+        if (tid == 0) {
+            slot_atomic_max_i32(p.absmax, tmax);
+            p.tile_shift[bid] = d16_s;
+        }
+    }
     // per wave, 32 rows at a time through LDS
     int sq_r = 7;
     long long sq_sum = 0, rb_st = 0;
@@ -515,6 +553,19 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
                     sq_sum += ls;
                     rb_st += lst;
                     *(v4i *)(p.rb_e1 + off) = o;
+                } else if (EPI == EPI_D16) {
+                    const int smask = (1 << d16_s) - 1;
+                    uint32_t w8[8];
+#pragma unroll
+                    for (int k = 0; k < 16; k += 2) {
+                        const int a = v[k], b = v[k + 1];
+                        const uint32_t qa = (uint32_t)(((a >> d16_s) << 1) | (((a & smask) + smask) >> d16_s));
+                        const uint32_t qb = (uint32_t)(((b >> d16_s) << 1) | (((b & smask) + smask) >> d16_s));
+                        w8[k >> 1] = (qa & 0xffffu) | (qb << 16);
+                    }
+                    v4i *dst = (v4i *)(p.d16 + off);
+                    dst[0] = v4i{(int)w8[0], (int)w8[1], (int)w8[2], (int)w8[3]};
+                    dst[1] = v4i{(int)w8[4], (int)w8[5], (int)w8[6], (int)w8[7]};
                 } else if (EPI == EPI_SQ) {
                     // Q_e (Eq.11): clamp(R(v * 2^(7-r))); |v| < 2^30 here, so 32-bit arithmetic is exact
                     const int sh = sq_r - 7;
@@ -550,8 +601,15 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
     if (EPI == EPI_ACC && p.absmax) block_atomic_max_i32(mx, p.absmax);
     if (EPI == EPI_SQ && p.sq_sum_out) block_atomic_add_i64(sq_sum, p.sq_sum_out);
     if (EPI == EPI_RELU_BWD) {
-        if (p.rb_sum_e1) block_atomic_add_i64(sq_sum, p.rb_sum_e1);
-        if (p.rb_sum_e1t) block_atomic_add_i64(rb_st, p.rb_sum_e1t);
+        if (p.rb_part) {
+            // thousands of workgroups adding to two slots would queue up behind each other: each stores its own
+            // pair, a one-block kernel adds them up afterwards
+            const int64_t a = block_sum_i64(sq_sum), b = block_sum_i64(rb_st);
+            if (tid == 0) { p.rb_part[2 * bid] = a; p.rb_part[2 * bid + 1] = b; }
+        } else {
+            if (p.rb_sum_e1) block_atomic_add_i64(sq_sum, p.rb_sum_e1);
+            if (p.rb_sum_e1t) block_atomic_add_i64(rb_st, p.rb_sum_e1t);
+        }
         if (p.rb_absmax) block_atomic_max_i32(mx, p.rb_absmax);
     }
 }
@@ -657,6 +715,108 @@ __global__ void requant_fwd_kernel(const int32_t *acc, size_t n16, EpiDev ep)
     }
 }
 
+// adds up per-workgroup pairs of partial sums (one block)
+__global__ __launch_bounds__(1024) void pair_reduce_kernel(const int64_t *part, int n, int64_t *sum0, int64_t *sum1)
+{
+    int64_t a = 0, b = 0;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) { a += part[2 * i]; b += part[2 * i + 1]; }
+    a = block_sum_i64(a);
+    b = block_sum_i64(b);
+    if (threadIdx.x == 0) {
+        if (sum0 && a) atomic_add_i64(sum0, a);
+        if (sum1 && b) atomic_add_i64(sum1, b);
+    }
+}
+
+// Second half of the fused backward-data + Q_e call: turns the block-scaled 16-bit sums into the final codes
+// e4 = clamp(R(d * 2^(7-r))), r = R(log2 max|d|) (Eq.11), and optionally applies the ReLU backward step of the layer
+// below (Eq.3: e1 = e4 * relu'(x4), mask bit per element) with its sums (Eq.4).  One lane: 16 channels of one pixel.
+struct D16Finish {
+    const int16_t *d16;
+    const int32_t *tile_shift;
+    int bm_shift, bn_shift, tiles_n;       // tile of element (m, c): (m >> bm_shift) * tiles_n + (c >> bn_shift)
+    size_t M;
+    int C;
+    const int32_t *absmax, *exp_in;
+    int32_t exp_in_off;
+    int32_t *exp_out;
+    int8_t *e4;
+    int64_t *sum_e4;
+    const uint16_t *mask16;
+    int8_t *e1;
+    int64_t *sum_e1;
+    int32_t *absmax_e1;
+};
+
+template <bool RELU>
+__global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
+{
+    const uint32_t Mx = (uint32_t)*p.absmax;
+    const int r = Mx ? sq_exponent_u32(Mx) : 7;
+    const int sh = r - 7;
+    if (blockIdx.x == 0 && threadIdx.x == 0) *p.exp_out = *p.exp_in + p.exp_in_off + (Mx ? sh : 0);
+    const uint32_t c16 = (uint32_t)p.C >> 4;
+    const uint32_t total = (uint32_t)p.M * c16;            // the host checked that this fits 32 bits
+    // (pixel, channel group) of this lane's element, advanced by the grid stride without a division per element
+    const uint32_t step = gridDim.x * blockDim.x;
+    const uint32_t dm = step / c16, dc = step - dm * c16;
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t m = i / c16, cg = i - m * c16;
+    int s4 = 0, s1 = 0, mx1 = 0;                           // a lane sees at most 2^27 / lanes elements of |code| <= 127
+    long long s4w = 0, s1w = 0;
+    int since = 0;
+    for (; i < total; i += step) {
+        const int c = (int)cg << 4;
+        const int s = p.tile_shift[(m >> p.bm_shift) * p.tiles_n + (c >> p.bn_shift)];
+        const int T = sh - s + 1;                          // rounding position inside the stored 16-bit value
+        const size_t off = (size_t)m * p.C + c;
+        const v4i lo = ((const v4i *)(p.d16 + off))[0], hi = ((const v4i *)(p.d16 + off))[1];
+        int v[16];
+#pragma unroll
+        for (int k = 0; k < 16; k += 2) {
+            const int w = k < 8 ? lo[k >> 1] : hi[(k - 8) >> 1];
+            v[k] = (int)(int16_t)(w & 0xffff);
+            v[k + 1] = w >> 16;
+        }
+        int code[16];
+        if (T >= 1) {
+            const int half = (1 << (T - 1)) - 1;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) code[k] = (v[k] + half + ((v[k] >> T) & 1)) >> T;
+        } else {                                           // every sum is below 2^7: the stored value is exactly 2*d
+#pragma unroll
+            for (int k = 0; k < 16; ++k) code[k] = (v[k] >> 1) << (-sh);
+        }
+        uint32_t o4[4] = {0, 0, 0, 0}, o1[4] = {0, 0, 0, 0};
+        uint32_t mk = 0xffffu;
+        if (RELU && p.mask16) mk = (uint32_t)p.mask16[off >> 4];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int cd = clamp_i(code[k], -CODE_MAX, CODE_MAX);
+            o4[k >> 2] |= ((uint32_t)cd & 0xffu) << (8 * (k & 3));
+            s4 += cd;
+            if (RELU) {
+                const int e = ((mk >> k) & 1u) ? cd : 0;
+                o1[k >> 2] |= ((uint32_t)e & 0xffu) << (8 * (k & 3));
+                s1 += e;
+                const int ae = e < 0 ? -e : e;
+                mx1 = ae > mx1 ? ae : mx1;
+            }
+        }
+        if (p.e4) *(v4i *)(p.e4 + off) = v4i{(int)o4[0], (int)o4[1], (int)o4[2], (int)o4[3]};
+        if (RELU) *(v4i *)(p.e1 + off) = v4i{(int)o1[0], (int)o1[1], (int)o1[2], (int)o1[3]};
+        if (++since == 1 << 16) { s4w += s4; s1w += s1; s4 = s1 = 0; since = 0; }      // long before 32 bits fill
+        m += dm; cg += dc;
+        if (cg >= c16) { cg -= c16; ++m; }
+    }
+    s4w += s4; s1w += s1;
+    if (p.sum_e4) block_atomic_add_i64(s4w, p.sum_e4);
+    if (RELU) {
+        if (p.sum_e1) block_atomic_add_i64(s1w, p.sum_e1);
+        if (p.absmax_e1) block_atomic_max_i32(mx1, p.absmax_e1);
+    }
+}
+
 inline unsigned grid_for(size_t total)
 {
     size_t b = (total + 255) / 256;
@@ -706,26 +866,28 @@ int launch_igemm(eoq_ctx *c, const IgemmParams &p)
 }
 
 template <int MODE, int EPI>
-int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in)
+int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in, int *bm_out = nullptr, int *bn_out = nullptr)
 {
+    auto chosen = [&](int bm, int bn) { if (bm_out) *bm_out = bm; if (bn_out) *bn_out = bn; };
     IgemmParams p = p_in;
     if (!p.xstep) p.xstep = p.C;
     p.gemm = (p.R == 1 && p.S == 1 && p.stride == 1 && p.pad == 0 && !p.no_pad && p.P == p.H && p.Q == p.W) ? 1 : 0;
     const int nout = p.NOUT;
     auto wgs = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((nout + bn - 1) / bn); };
     switch (forced_tile()) {
-    case 128128064: return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
-    case 128064064: return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
-    case 128032064: return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p);
-    case 64064064: return launch_igemm<64, 64, 2, 2, 64, MODE, EPI>(c, p);
-    case 64128064: return launch_igemm<64, 128, 2, 2, 64, MODE, EPI>(c, p);
+    case 128128064: chosen(128, 128); return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
+    case 128064064: chosen(128, 64); return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
+    case 128032064: chosen(128, 32); return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p);
+    case 64064064: chosen(64, 64); return launch_igemm<64, 64, 2, 2, 64, MODE, EPI>(c, p);
+    case 64128064: chosen(64, 128); return launch_igemm<64, 128, 2, 2, 64, MODE, EPI>(c, p);
     default: break;
     }
     // Measured on MI355X: throughput is nearly flat in the tile shape and in the prefetch depth (4, 6, 8 stages),
     // so small tiles win through occupancy and grid size; the 128x128 tile pays off only for wide outputs with
     // enough workgroups to fill the chip.
-    if (nout <= 32) return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p);
-    if (nout >= 128 && wgs(128, 128) >= 256) return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
+    if (nout <= 32) { chosen(128, 32); return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p); }
+    if (nout >= 128 && wgs(128, 128) >= 256) { chosen(128, 128); return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p); }
+    chosen(128, 64);
     return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
 }
 
@@ -769,7 +931,10 @@ extern "C" size_t eoq_workspace_bytes(const eoq_conv_desc *d, int op)
     }
     switch (op) {
     case EOQ_OP_CONV_FWD: return im2col;
-    case EOQ_OP_CONV_BWD_DATA: return round_up(wbytes, 256);
+    case EOQ_OP_CONV_BWD_DATA:
+        // transposed filters + 16-bit block-scaled sums + one shift per 64 x 32 tile (the smallest tile)
+        return round_up(wbytes, 256) + round_up(2 * (size_t)d->N * d->H * d->W * d->C, 256) +
+               round_up(4 * (((size_t)d->N * d->H * d->W + 63) / 64) * (((size_t)d->C + 31) / 32), 256);
     case EOQ_OP_CONV_BWD_WEIGHT:
         // staged input + split partial sums (int32) sized for the worst split count, see conv_wgrad.hip
         return im2col + round_up((size_t)d->K * kp * 4 * wgrad_max_splits((size_t)d->K * kp), 256);
@@ -889,7 +1054,17 @@ extern "C" int eoq_relu_bwd_recompute(eoq_ctx *c, const eoq_conv_desc *d, const 
     p.nk16 = p.R * p.S * p.c16;
     p.rb_e0 = e0; p.rb_mask16 = (const uint16_t *)mask_bits; p.rb_e1 = e1;
     p.rb_sum_e1 = sum_e1; p.rb_sum_e1t = sum_e1t; p.rb_absmax = absmax_e1;
-    return dispatch_igemm<MODE_FWD, EPI_RELU_BWD>(c, p);
+    // every tile shape the dispatcher may choose is at least 64 x 32
+    const long max_tiles = (long)((p.M + 63) / 64) * ((p.NOUT + 31) / 32);
+    if ((sum_e1 || sum_e1t) && 2 * max_tiles <= EOQ_PARTIAL_SLOTS) p.rb_part = c->d_partials;
+    int bm = 0, bn = 0;
+    if (int rc = dispatch_igemm<MODE_FWD, EPI_RELU_BWD>(c, p, &bm, &bn)) return rc;
+    if (p.rb_part) {
+        const int tiles = ((p.M + bm - 1) / bm) * ((p.NOUT + bn - 1) / bn);
+        hipLaunchKernelGGL(pair_reduce_kernel, dim3(1), dim3(1024), 0, c->stream, c->d_partials, tiles, sum_e1, sum_e1t);
+        EOQ_LAUNCH_CHECK();
+    }
+    return EOQ_OK;
 }
 
 static int bwd_data_params(const eoq_conv_desc *d, const int8_t *e, const int8_t *wt, IgemmParams &p)
@@ -909,15 +1084,19 @@ static int bwd_data_params(const eoq_conv_desc *d, const int8_t *e, const int8_t
 
 extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *e, const int8_t *w, int8_t *e4,
                                     int32_t *absmax_slot, const int32_t *exp_in, int32_t exp_in_off, int32_t *exp_out,
-                                    int64_t *sum_out, void *ws, size_t ws_bytes)
+                                    int64_t *sum_out, const uint32_t *mask_bits, int8_t *e1, int64_t *sum_e1,
+                                    int32_t *absmax_e1, void *ws, size_t ws_bytes)
 {
-    if (!c || !e || !w || !e4 || !absmax_slot || !exp_in || !exp_out) return EOQ_ERR_ARG;
+    if (!c || !e || !w || (!e4 && !e1) || !absmax_slot || !exp_in || !exp_out) return EOQ_ERR_ARG;
     if (!desc_ok(d)) return EOQ_ERR_SHAPE;
     if (d->K % 16 || d->C % 16 || d->R * d->S > 64) return EOQ_ERR_SHAPE;
-    if ((long long)d->R * d->S * d->K * 127 * 127 >= (1ll << 30)) return EOQ_ERR_SHAPE;   // 32-bit requantisation
-    if (((uintptr_t)e | (uintptr_t)w | (uintptr_t)e4) & 15) return EOQ_ERR_ARG;
+    if ((long long)d->R * d->S * d->K * 127 * 127 >= (1ll << 30)) return EOQ_ERR_SHAPE;   // sums stay below 2^30
+    if (((uintptr_t)e | (uintptr_t)w | (uintptr_t)e4 | (uintptr_t)e1) & 15 || ((uintptr_t)mask_bits & 3)) return EOQ_ERR_ARG;
     if (!ws || ws_bytes < eoq_workspace_bytes(d, EOQ_OP_CONV_BWD_DATA) || ((uintptr_t)ws & 15)) return EOQ_ERR_WORKSPACE;
+    const size_t M = (size_t)d->N * d->H * d->W;
     int8_t *wt = (int8_t *)ws;
+    int16_t *d16 = (int16_t *)(wt + round_up((size_t)d->K * d->R * d->S * d->C, 256));
+    int32_t *tile_shift = (int32_t *)((int8_t *)d16 + round_up(2 * M * d->C, 256));
     hipLaunchKernelGGL(transpose_filters_kernel, dim3(grid_for((size_t)d->K * d->R * d->S * d->C)), dim3(256), 0,
                        c->stream, w, d->K, d->R * d->S, d->C, wt);
     EOQ_LAUNCH_CHECK();
@@ -925,9 +1104,27 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
     p.status = c->d_status;
     if (int rc = bwd_data_params(d, e, wt, p)) return rc;
     p.absmax = absmax_slot;
-    if (int rc = dispatch_igemm<MODE_BWD_DATA, EPI_ABSMAX>(c, p)) return rc;
-    p.sq_out = e4; p.sq_exp_in = exp_in; p.sq_exp_off = exp_in_off; p.sq_exp_out = exp_out; p.sq_sum_out = sum_out;
-    return dispatch_igemm<MODE_BWD_DATA, EPI_SQ>(c, p);
+    p.d16 = d16;
+    p.tile_shift = tile_shift;
+    int bm = 0, bn = 0;
+    if (int rc = dispatch_igemm<MODE_BWD_DATA, EPI_D16>(c, p, &bm, &bn)) return rc;
+    D16Finish f{};
+    f.d16 = d16; f.tile_shift = tile_shift;
+    f.bm_shift = bm == 64 ? 6 : 7;
+    f.bn_shift = bn == 32 ? 5 : (bn == 64 ? 6 : 7);
+    f.tiles_n = (d->C + bn - 1) / bn;
+    f.M = M; f.C = d->C;
+    f.absmax = absmax_slot; f.exp_in = exp_in; f.exp_in_off = exp_in_off; f.exp_out = exp_out;
+    f.e4 = e4; f.sum_e4 = sum_out;
+    f.mask16 = (const uint16_t *)mask_bits; f.e1 = e1; f.sum_e1 = sum_e1; f.absmax_e1 = absmax_e1;
+    if (M * (d->C / 16) > 0x7fffffffu) return EOQ_ERR_SHAPE;
+    // few, large blocks: each ends with atomics on the same two or three slots
+    size_t fb = (M * (d->C / 16) + 1023) / 1024;
+    if (fb > 512) fb = 512;
+    if (e1) hipLaunchKernelGGL(d16_finish_kernel<true>, dim3((unsigned)fb), dim3(1024), 0, c->stream, f);
+    else hipLaunchKernelGGL(d16_finish_kernel<false>, dim3((unsigned)fb), dim3(1024), 0, c->stream, f);
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
 }
 
 int eoq_requant_fwd_standalone(eoq_ctx *c, const eoq_requant_args *a)

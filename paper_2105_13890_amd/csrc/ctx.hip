@@ -23,10 +23,17 @@ extern "C" int eoq_create(eoq_ctx **out, void *hip_stream)
         delete c;
         return EOQ_ERR_HIP;
     }
+    if (hipMalloc((void **)&c->d_partials, sizeof(int64_t) * EOQ_PARTIAL_SLOTS) != hipSuccess) {
+        (void)hipFree(c->d_status);
+        (void)hipFree(c->d_scratch);
+        delete c;
+        return EOQ_ERR_HIP;
+    }
     if (hipMemset(c->d_status, 0, 256) != hipSuccess ||
         hipMemset(c->d_scratch, 0, sizeof(int32_t) * EOQ_SCRATCH_SLOTS) != hipSuccess) {
         (void)hipFree(c->d_status);
         (void)hipFree(c->d_scratch);
+        (void)hipFree(c->d_partials);
         delete c;
         return EOQ_ERR_HIP;
     }
@@ -39,6 +46,7 @@ extern "C" int eoq_destroy(eoq_ctx *c)
     if (!c) return EOQ_ERR_ARG;
     (void)hipFree(c->d_status);
     (void)hipFree(c->d_scratch);
+    (void)hipFree(c->d_partials);
     delete c;
     return EOQ_OK;
 }

@@ -10,8 +10,8 @@
 
 namespace {
 
-constexpr int EW_THREADS = 256;
-constexpr unsigned EW_MAX_BLOCKS = 256 * 4;
+constexpr int EW_THREADS = 1024;          // few, large blocks: see the note on same-address atomics in common.h
+constexpr unsigned EW_MAX_BLOCKS = 256 * 2;
 
 inline unsigned ew_blocks(size_t n_vec)
 {

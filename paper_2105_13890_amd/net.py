@@ -418,12 +418,17 @@ class FixupNet:
             self._rec(u.name + ".gw", g.view(u.w.shape))
         return g
 
-    def _unit_bwd(self, u: Unit, e0, bufs, need_dx=True):
-        """Eq.3 / Eq.4 for one layer; e0 is overwritten by e1.  Returns (e4 buffer or None, e1)."""
+    def _unit_bwd(self, u: Unit, e0, bufs, need_dx=True, relu_done=False, fuse_below: Unit | None = None):
+        """Eq.3 / Eq.4 for one layer; e0 is overwritten by e1.  Returns (buffer with the error for the layer
+        below or None, e1).  relu_done: e0 already is e1 (the ReLU backward step was fused into the call that
+        produced it).  fuse_below: the layer whose output is this layer's input -- its ReLU backward step and
+        sums are applied by this layer's backward-data call, which then returns e1 of that layer instead of e4."""
         c = self.ctx
         n_out = int(np.prod(u.out_shape))
         e1 = e0
-        if u.relu and u.gamma:
+        if relu_done:
+            pass
+        elif u.relu and u.gamma:
             self._call("relu_bwd_recompute", u.name, self._conv_work(u), c.relu_bwd_recompute, u.desc, u.u, u.w,
                        e0[:n_out], u.mask, e1[:n_out], self.s64(u.name + ".S_e1"), self.s64(u.name + ".S_e1t"),
                        self.s32(u.name + ".M_e1"))
@@ -444,11 +449,22 @@ class FixupNet:
         if need_dx:
             n_in = int(np.prod(u.in_shape))
             e4 = self._acquire(bufs)
-            self._call("conv_bwd_data", u.name, 2 * self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
-                       e4[:n_in], self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
-                       self.s64(u.name + ".S_e4"), self.ws)
-            if self.tracing:
-                self._rec(u.name + ".e4", e4[:n_in].view(u.in_shape))
+            if fuse_below is not None:
+                assert fuse_below.relu and not fuse_below.gamma and fuse_below.out_shape == u.in_shape
+                e4_dbg = torch.empty(u.in_shape, dtype=torch.int8, device=self.dev) if self.tracing else None
+                f = fuse_below
+                self._call("conv_bwd_data", u.name, self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
+                           e4_dbg, self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
+                           self.s64(u.name + ".S_e4"), self.ws, mask=f.mask, e1=e4[:n_in],
+                           sum_e1=self.s64(f.name + ".S_e1"), absmax_e1=self.s32(f.name + ".M_e1"))
+                if self.tracing:
+                    self._rec(u.name + ".e4", e4_dbg)
+            else:
+                self._call("conv_bwd_data", u.name, self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
+                           e4[:n_in], self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
+                           self.s64(u.name + ".S_e4"), self.ws)
+                if self.tracing:
+                    self._rec(u.name + ".e4", e4[:n_in].view(u.in_shape))
         # W <- Q_w(W - Q_u(lr g)) (Eq.13) once every reader of the old weights has run
         if self.overlap:
             if need_dx:
@@ -468,11 +484,14 @@ class FixupNet:
         c = self.ctx
         for b in reversed(self.blocks):
             last = b.units[-1]
-            e4, e_sk = self._unit_bwd(last, e, bufs)            # e now holds e1 of the last layer = shortcut error
+            # e now holds e1 of the last layer = shortcut error; its backward-data call already applies the ReLU
+            # backward step of the layer below it, and so on down the branch
+            e4, e_sk = self._unit_bwd(last, e, bufs, fuse_below=b.units[-2] if len(b.units) > 1 else None)
             E_sk = last.E0
             cur = e4
-            for u in reversed(b.units[:-1]):
-                nxt, _ = self._unit_bwd(u, cur, bufs)
+            for idx in range(len(b.units) - 2, -1, -1):
+                nxt, _ = self._unit_bwd(b.units[idx], cur, bufs, relu_done=True,
+                                        fuse_below=b.units[idx - 1] if idx > 0 else None)
                 bufs.append(cur)
                 cur = nxt
             first = b.units[0]

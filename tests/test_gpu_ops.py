@@ -178,16 +178,54 @@ def test_conv_bwd_data(ctx, d):
     want = oo.conv_bwd_data(d, e, w)
     assert np.array_equal(host(dx), want)
     assert int(host(slot)[0]) == int(np.abs(want).max())
-    # fused Q_e (two evaluations of the convolution, no int32 round trip)
-    e4 = zeros((d.N, d.H, d.W, d.C), torch.int8)
+
+
+def _bwd_data_sq_case(ctx, d, e, w, with_mask):
+    """eoq_conv_bwd_data_sq against the oracle's exact sums followed by Q_e (and the ReLU backward step)."""
+    from paper_2105_13890_amd import eoq
+    want = oo.conv_bwd_data(d, e, w)
+    ishape = (d.N, d.H, d.W, d.C)
+    n = int(np.prod(ishape))
+    e4, e1 = zeros(ishape, torch.int8), zeros(ishape, torch.int8)
     sl = dev(np.array([0, -13, 0, 0], dtype=np.int32))
     sums = zeros((2,), torch.int64)
-    ctx.conv_bwd_data_sq(desc_of(d), dev(e), dev(w), e4, sl[0:1], sl[1:2], -7, sl[2:3], sums[0:1],
-                         ws_for(d, eoq.OP_CONV_BWD_DATA))
+    maskb = (si.words(5, "mask", n) & np.uint64(1)).astype(bool)
+    packed = np.packbits(maskb, bitorder="little")
+    mask = dev(np.frombuffer(packed.tobytes() + b"\0" * (-len(packed) % 4), dtype=np.int32))
+    if with_mask:
+        ctx.conv_bwd_data_sq(desc_of(d), dev(e), dev(w), e4, sl[0:1], sl[1:2], -7, sl[2:3], sums[0:1],
+                             ws_for(d, eoq.OP_CONV_BWD_DATA), mask=mask, e1=e1, sum_e1=sums[1:2], absmax_e1=sl[3:4])
+    else:
+        ctx.conv_bwd_data_sq(desc_of(d), dev(e), dev(w), e4, sl[0:1], sl[1:2], -7, sl[2:3], sums[0:1],
+                             ws_for(d, eoq.OP_CONV_BWD_DATA))
     e4o, E4o = oo.sq_acc(want, -13 - 7)
     assert np.array_equal(host(e4), e4o) and int(host(sl)[2]) == E4o
     assert int(host(sl)[0]) == int(np.abs(want).max())
     assert int(host(sums)[0]) == int(e4o.astype(np.int64).sum())
+    if with_mask:
+        e1o = (e4o.astype(np.int64) * maskb.reshape(ishape)).astype(np.int8)
+        assert np.array_equal(host(e1), e1o)
+        assert int(host(sums)[1]) == int(e1o.astype(np.int64).sum())
+        assert int(host(sl)[3]) == int(np.abs(e1o.astype(np.int64)).max())
+
+
+@pytest.mark.parametrize("d", CONV_SHAPES[:8], ids=IDS[:8])
+def test_conv_bwd_data_sq(ctx, d):
+    """One evaluation of the convolution, 16-bit block-scaled intermediate: the codes must equal Q_e of the exact
+    sums whatever the spread of magnitudes between tiles -- uniform errors, errors that are tiny in half of the
+    images (tiles whose own maximum is far below the tensor's), sums below 2^7 (no rounding at all), all zeros."""
+    e = si.uniform_int8(3, "e", (d.N, d.P, d.Q, d.K))
+    w = si.uniform_int8(3, "w", (d.K, d.R, d.S, d.C))
+    _bwd_data_sq_case(ctx, d, e, w, with_mask=True)
+    _bwd_data_sq_case(ctx, d, e, w, with_mask=False)
+    spread = e.copy()
+    spread[:, ::2] = np.clip(spread[:, ::2], -1, 1)            # every other row of every image carries tiny errors
+    spread[0] = np.clip(spread[0], -2, 2)
+    _bwd_data_sq_case(ctx, d, spread, w, with_mask=True)
+    tiny_e = np.clip(e, -1, 1)
+    tiny_w = np.where(si.words(3, "sparse", w.size).reshape(w.shape) % np.uint64(37) == 0, np.clip(w, -1, 1), 0).astype(np.int8)
+    _bwd_data_sq_case(ctx, d, tiny_e, tiny_w, with_mask=True)
+    _bwd_data_sq_case(ctx, d, np.zeros_like(e), w, with_mask=True)
 
 
 @pytest.mark.parametrize("d", CONV_SHAPES, ids=IDS)
