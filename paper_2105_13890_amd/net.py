@@ -573,6 +573,19 @@ class FixupNet:
             self._rec("g_code", self.g_code)
             self._rec("g_exp", self.g_exp)
 
+    def capture_step(self) -> "torch.cuda.CUDAGraph":
+        """Capture one training step (both streams) into a HIP graph; replaying it runs the step on whatever
+        x_in / labels / lr hold at that time.  The network must have been built, and at least one step run
+        eagerly, with a non-default stream current (the library's calls go to the stream that was current at
+        construction, and the default stream cannot be captured); that same stream must be current now."""
+        assert not self.tracing, "a traced step copies tensors out between calls and cannot be captured"
+        assert self.main != torch.cuda.default_stream(), "build the network under torch.cuda.stream(<own stream>)"
+        assert torch.cuda.current_stream() == self.main
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=self.main):
+            self.enqueue_step()
+        return g
+
     def step(self, x_f32: np.ndarray | torch.Tensor, labels, lr_m: int, lr_j: int) -> float:
         """Convenience wrapper: upload a batch, run one step, return the loss (synchronises)."""
         self.trace = {}

@@ -66,6 +66,40 @@ def test_short_trajectories(batch, steps, lr):
         assert r["weight_codes_changed_vs_init"] > 0.01, r
 
 
+def test_graph_replays_match_oracle():
+    """A step captured into a HIP graph (both streams) and replayed: every replay, with a fresh batch uploaded
+    by ordinary eager copies and a synchronisation in between, must leave the same parameters as the oracle's
+    step -- a replay that reused stale data, skipped a node or raced between the two streams would not."""
+    import torch
+    from oracle.net import Net as OracleNet
+    from paper_2105_13890_amd.net import FixupNet
+    cfg, batch, lr = si.WORKLOADS["resnet18"], 2, (1, 0)
+    o = OracleNet(cfg, batch, seed=0)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        g = FixupNet(cfg, batch, seed=0)
+        graph = None
+        for step in range(5):
+            x = si.batch_images(0, step, batch, cfg["in_hw"])
+            lab = si.batch_labels(0, step, batch, cfg["classes"])
+            lo = o.step(x, lab, *lr)
+            if step == 0:
+                lg = g.step(x, lab, *lr)                 # eager: sets one-time kernel attributes
+                graph = g.capture_step()                 # capturing runs nothing
+            else:
+                g.x_in.copy_(torch.from_numpy(x).cuda())
+                g.labels.copy_(torch.from_numpy(lab).cuda())
+                graph.replay()
+                torch.cuda.synchronize()
+                lg = float(g.loss.item())
+            assert abs(lg - lo) <= 1e-5 * abs(lo), (step, lg, lo)
+            for u in g.all_units:
+                assert np.array_equal(u.w.cpu().numpy(), o.W[u.name]), (step, u.name)
+            assert g.scalars() == {k: o.scal[k] for k in g.scalars()}, step
+            assert np.array_equal(g.Wfc.cpu().numpy(), o.Wfc), step
+            assert g.status() == 0, step
+
+
 if __name__ == "__main__":
     import argparse
     ap = argparse.ArgumentParser()
