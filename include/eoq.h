@@ -143,14 +143,26 @@ int eoq_conv_bwd_data(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, 
  * e4 = clamp(R(d * 2^(7-r))), r = R(log2 max|d|) -- exactly, because the rounding position is at least 6 bits
  * above any dropped bit -- and sets *exp_out = *exp_in + exp_in_off + r - 7 (all-zero d: codes 0, exponent
  * *exp_in + exp_in_off).  When sum_out is non-NULL, *sum_out += sum of the e4 codes (the bias gradient of Eq.4).
- * Optionally the ReLU backward step of the layer whose output this input is (Eq.3 line e1) is applied in the
- * same pass: with mask_bits (that layer's forward mask, one bit per element, NULL = all ones) and e1
- * non-NULL, e1 = e4 where the bit is set and 0 elsewhere, *sum_e1 += sum(e1), *absmax_e1 max= max|e1|
- * (each may be NULL).  e4 may be NULL when only e1 is wanted.  Requires 127^2 * R*S*K < 2^30. */
+ * `fuse` (may be NULL) adds work to the streaming kernel that would otherwise be a pass of its own:
+ *  - the ReLU backward step of the layer whose output this input is (Eq.3 line e1): with e1 non-NULL,
+ *    e1 = e4 where the bit of mask_bits (that layer's forward mask, one bit per element, NULL = all ones) is set
+ *    and 0 elsewhere, *sum_e1 += sum(e1), *absmax_e1 max= max|e1| (each may be NULL); e4 may then be NULL;
+ *  - the statistics of the block-input merge: with merge_other non-NULL (int8 codes of the other error, same
+ *    shape, exponent *merge_exp_other), *merge_absmax max= max|e4 * 2^(E4-Em) + other * 2^(Eo-Em)|,
+ *    Em = min(E4, Eo), what eoq_merge_absmax computes; needs e4 and excludes e1.
+ * Requires 127^2 * R*S*K < 2^30. */
+typedef struct eoq_bwd_fuse {
+    const uint32_t *mask_bits;
+    int8_t *e1;
+    int64_t *sum_e1;
+    int32_t *absmax_e1;
+    const int8_t *merge_other;
+    const int32_t *merge_exp_other;
+    int32_t *merge_absmax;
+} eoq_bwd_fuse;
 int eoq_conv_bwd_data_sq(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, const int8_t *w, int8_t *e4,
                          int32_t *absmax_slot, const int32_t *exp_in, int32_t exp_in_off, int32_t *exp_out,
-                         int64_t *sum_out, const uint32_t *mask_bits, int8_t *e1, int64_t *sum_e1,
-                         int32_t *absmax_e1, void *ws, size_t ws_bytes);
+                         int64_t *sum_out, const eoq_bwd_fuse *fuse, void *ws, size_t ws_bytes);
 
 /* ---- weight-gradient convolution: Eq.4 line g_w before Q_g ------------------------------------
  * g_acc[k,r,s,c] = sum_{n,p,q} e[n,p,q,k] * u[n, p*stride+r-pad, q*stride+s-pad, c], the exact integer

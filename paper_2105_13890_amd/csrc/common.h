@@ -164,6 +164,19 @@ __device__ __forceinline__ int64_t block_sum_i64(int64_t v)
     return v;
 }
 
+// ---- block-input merge: both errors are aligned on the finer of their two grids (Ea, Eb: exponents) ----
+__device__ __forceinline__ void merge_shifts(int Ea, int Eb, int &sa, int &sb, int &Em, uint32_t *status)
+{
+    Em = Ea < Eb ? Ea : Eb;
+    sa = Ea - Em;
+    sb = Eb - Em;
+    if (sa > 24 || sb > 24) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, (uint32_t)EOQ_FLAG_EXP_GAP);
+        sa = sa > 24 ? 24 : sa;
+        sb = sb > 24 ? 24 : sb;
+    }
+}
+
 static inline int conv_out_dim(int in, int pad, int k, int st) { return (in + 2 * pad - k) / st + 1; }
 static inline int conv_out_dim_fwd(int in, int pad, int k, int st) { return (in + 2 * pad - k) / st + 1; }
 static inline size_t round_up(size_t v, size_t m) { return (v + m - 1) / m * m; }

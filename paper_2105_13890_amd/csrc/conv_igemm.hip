@@ -80,9 +80,12 @@ __device__ __forceinline__ int byte_at(const v4i &v, int i)
 // FAST: z = gamma*t + 128*(b + skip) is known to fit 32 bits (decided once per launch from the accumulator
 // bound and the scalar codes), so everything runs in full-rate 32-bit integer instructions; otherwise the
 // same arithmetic is carried out in 64 bits.
+// int8 shortcut codes are passed in a register (sk8): the caller fetches them for all of a thread's chunks before
+// the first is processed, so their latency is paid once and not per chunk.  (Wide shortcut values -- one layer per
+// stage -- are read here: holding 16 dwords per chunk ahead of time would cost the kernel its occupancy.)
 template <bool FAST>
 __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const EpiDev &ep, int32_t *acc_out,
-                                           int gamma, int bpost, int bnext, uint32_t &range_bad)
+                                           int gamma, int bpost, int bnext, uint32_t &range_bad, const v4i &sk8)
 {
     if (acc_out) {
 #pragma unroll
@@ -107,7 +110,7 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
         if (ep.skip_wide) {
 #pragma unroll
             for (int k4 = 0; k4 < 4; ++k4) {
-                v4i w = ((const v4i *)((const int32_t *)ep.skip + off))[k4];
+                const v4i w = ((const v4i *)((const int32_t *)ep.skip + off))[k4];
                 sk[4 * k4] = w[0]; sk[4 * k4 + 1] = w[1]; sk[4 * k4 + 2] = w[2]; sk[4 * k4 + 3] = w[3];
             }
             if (FAST) {
@@ -117,9 +120,8 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
                 for (int k = 0; k < 16; ++k) range_bad |= (uint32_t)(sk[k] ^ __builtin_amdgcn_sbfe(sk[k], 0, 23));
             }
         } else {
-            v4i w = *(const v4i *)((const int8_t *)ep.skip + off);
 #pragma unroll
-            for (int k = 0; k < 16; ++k) sk[k] = byte_at(w, k);
+            for (int k = 0; k < 16; ++k) sk[k] = byte_at(sk8, k);
         }
     } else {
 #pragma unroll
@@ -132,7 +134,7 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
     for (int k = 0; k < 16; ++k) {
         int yc;
         if (FAST) {
-            const int z = gamma * t[k] + ((sk[k] << 7) + b128);
+            const int z = __mul24(gamma, t[k]) + ((sk[k] << 7) + b128);      // both factors are below 2^23 here: full-rate multiply
             mask |= ((uint32_t)(-z) >> 31) << k;                 // z > 0  (z != INT_MIN here)
             yc = rne_shift7(z);
             yc = yc < 0 ? 0 : (yc > CODE_MAX ? CODE_MAX : yc);   // = clamp(R(max(z,0)/128)): R is monotone, R(0) = 0
@@ -505,6 +507,33 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
     }
     int mx = 0;
     uint32_t range_bad = 0;
+    // Side inputs of the epilogue (shortcut values; incoming error and mask words for the ReLU backward step) for
+    // ALL chunks this thread will process, requested before the first chunk is staged: the registers of the main
+    // loop's load ring are free by now, and the memory latency is paid once instead of once per chunk.
+    constexpr int NPASS = 32 / ROWS_PER_PASS;
+    v4i pre8[TM][NPASS];
+    uint32_t premk[TM][NPASS];
+    if (EPI == EPI_FWD || EPI == EPI_RELU_BWD) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int ps = 0; ps < NPASS; ++ps) {
+                const int m = m0 + wm * WTM + i * 32 + ps * ROWS_PER_PASS + prow;
+                const int ch = n0 + wn * WTN + grp * 16;
+                pre8[i][ps] = v4i{0, 0, 0, 0};
+                premk[i][ps] = 0xffffu;
+                if (m < p.M && ch < p.NOUT) {
+                    const size_t off = (size_t)m * p.NOUT + ch;
+                    if (EPI == EPI_FWD) {
+                        if (p.ep.skip && p.ep.relu && !p.ep.skip_wide)
+                            pre8[i][ps] = *(const v4i *)((const int8_t *)p.ep.skip + off);
+                    } else {
+                        pre8[i][ps] = *(const v4i *)(p.rb_e0 + off);
+                        if (p.rb_mask16) premk[i][ps] = (uint32_t)p.rb_mask16[off >> 4];
+                    }
+                }
+            }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -529,12 +558,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
             if (m < p.M && ch < p.NOUT) {
                 const size_t off = (size_t)m * p.NOUT + ch;
                 if (EPI == EPI_FWD) {
-                    if (fast) epilogue16<true>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad);
-                    else epilogue16<false>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad);
+                    if (fast) epilogue16<true>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad, pre8[i][ps]);
+                    else epilogue16<false>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad, pre8[i][ps]);
                 } else if (EPI == EPI_RELU_BWD) {
                     // Eq.3 e1 = e0 * relu'(x4); Eq.4 sums for g_b2 and g_gamma with x2 = R(acc/128) recomputed
-                    const v4i ev = *(const v4i *)(p.rb_e0 + off);
-                    const uint32_t mk = p.rb_mask16 ? (uint32_t)p.rb_mask16[off >> 4] : 0xffffu;
+                    const v4i ev = pre8[i][ps];
+                    const uint32_t mk = premk[i][ps];
                     v4i o = {0, 0, 0, 0};
                     int ls = 0, lst = 0;
                     // |x2| <= 127^2 * (reduction length) / 128 and |e| <= 127: for reductions of up to 8192
@@ -547,7 +576,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
                         ls += e;
                         const int ae = e < 0 ? -e : e;
                         mx = ae > mx ? ae : mx;
-                        if (narrow) lst += e * rne_shift7(v[k]);
+                        if (narrow) lst += __mul24(e, rne_shift7(v[k]));
                         else rb_st += (long long)e * (long long)rne_shift7(v[k]);
                     }
                     sq_sum += ls;
@@ -711,7 +740,9 @@ __global__ void requant_fwd_kernel(const int32_t *acc, size_t n16, EpiDev ep)
             v[4 * k4] = w[0]; v[4 * k4 + 1] = w[1]; v[4 * k4 + 2] = w[2]; v[4 * k4 + 3] = w[3];
         }
         uint32_t unused = 0;
-        epilogue16<false>(v, i * 16, ep, nullptr, gamma, bpost, bnext, unused);
+        v4i sk8 = {0, 0, 0, 0};
+        if (ep.skip && ep.relu && !ep.skip_wide) sk8 = *(const v4i *)((const int8_t *)ep.skip + i * 16);
+        epilogue16<false>(v, i * 16, ep, nullptr, gamma, bpost, bnext, unused, sk8);
     }
 }
 
@@ -746,6 +777,11 @@ struct D16Finish {
     int8_t *e1;
     int64_t *sum_e1;
     int32_t *absmax_e1;
+    // block-input merge statistics: max|e4 * 2^(E4-Em) + other * 2^(Eo-Em)|, Em = min(E4, Eo)
+    const int8_t *mg_other;
+    const int32_t *mg_exp_other;
+    int32_t *mg_absmax;
+    uint32_t *status;
 };
 
 template <bool RELU>
@@ -754,7 +790,13 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
     const uint32_t Mx = (uint32_t)*p.absmax;
     const int r = Mx ? sq_exponent_u32(Mx) : 7;
     const int sh = r - 7;
-    if (blockIdx.x == 0 && threadIdx.x == 0) *p.exp_out = *p.exp_in + p.exp_in_off + (Mx ? sh : 0);
+    const int E4 = *p.exp_in + p.exp_in_off + (Mx ? sh : 0);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *p.exp_out = E4;
+    int mg_sa = 0, mg_sb = 0, mg_mx = 0;
+    if (p.mg_other) {
+        int Em;
+        merge_shifts(E4, *p.mg_exp_other, mg_sa, mg_sb, Em, p.status);
+    }
     const uint32_t c16 = (uint32_t)p.C >> 4;
     const uint32_t total = (uint32_t)p.M * c16;            // the host checked that this fits 32 bits
     // (pixel, channel group) of this lane's element, advanced by the grid stride without a division per element
@@ -790,11 +832,18 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
         uint32_t o4[4] = {0, 0, 0, 0}, o1[4] = {0, 0, 0, 0};
         uint32_t mk = 0xffffu;
         if (RELU && p.mask16) mk = (uint32_t)p.mask16[off >> 4];
+        v4i ov = {0, 0, 0, 0};
+        if (!RELU && p.mg_other) ov = *(const v4i *)(p.mg_other + off);
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             const int cd = clamp_i(code[k], -CODE_MAX, CODE_MAX);
             o4[k >> 2] |= ((uint32_t)cd & 0xffu) << (8 * (k & 3));
             s4 += cd;
+            if (!RELU) {
+                int mv = (cd << mg_sa) + (byte_at(ov, k) << mg_sb);
+                mv = mv < 0 ? -mv : mv;
+                mg_mx = mv > mg_mx ? mv : mg_mx;
+            }
             if (RELU) {
                 const int e = ((mk >> k) & 1u) ? cd : 0;
                 o1[k >> 2] |= ((uint32_t)e & 0xffu) << (8 * (k & 3));
@@ -811,6 +860,7 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
     }
     s4w += s4; s1w += s1;
     if (p.sum_e4) block_atomic_add_i64(s4w, p.sum_e4);
+    if (!RELU && p.mg_other) block_atomic_max_i32(mg_mx, p.mg_absmax);
     if (RELU) {
         if (p.sum_e1) block_atomic_add_i64(s1w, p.sum_e1);
         if (p.absmax_e1) block_atomic_max_i32(mx1, p.absmax_e1);
@@ -1084,9 +1134,15 @@ static int bwd_data_params(const eoq_conv_desc *d, const int8_t *e, const int8_t
 
 extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *e, const int8_t *w, int8_t *e4,
                                     int32_t *absmax_slot, const int32_t *exp_in, int32_t exp_in_off, int32_t *exp_out,
-                                    int64_t *sum_out, const uint32_t *mask_bits, int8_t *e1, int64_t *sum_e1,
-                                    int32_t *absmax_e1, void *ws, size_t ws_bytes)
+                                    int64_t *sum_out, const eoq_bwd_fuse *fuse, void *ws, size_t ws_bytes)
 {
+    const uint32_t *mask_bits = fuse ? fuse->mask_bits : nullptr;
+    int8_t *e1 = fuse ? fuse->e1 : nullptr;
+    int64_t *sum_e1 = fuse ? fuse->sum_e1 : nullptr;
+    int32_t *absmax_e1 = fuse ? fuse->absmax_e1 : nullptr;
+    const int8_t *mg_other = fuse ? fuse->merge_other : nullptr;
+    if (mg_other && (!e4 || e1 || !fuse->merge_exp_other || !fuse->merge_absmax || ((uintptr_t)mg_other & 15)))
+        return EOQ_ERR_ARG;
     if (!c || !e || !w || (!e4 && !e1) || !absmax_slot || !exp_in || !exp_out) return EOQ_ERR_ARG;
     if (!desc_ok(d)) return EOQ_ERR_SHAPE;
     if (d->K % 16 || d->C % 16 || d->R * d->S > 64) return EOQ_ERR_SHAPE;
@@ -1117,6 +1173,10 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
     f.absmax = absmax_slot; f.exp_in = exp_in; f.exp_in_off = exp_in_off; f.exp_out = exp_out;
     f.e4 = e4; f.sum_e4 = sum_out;
     f.mask16 = (const uint16_t *)mask_bits; f.e1 = e1; f.sum_e1 = sum_e1; f.absmax_e1 = absmax_e1;
+    f.mg_other = mg_other;
+    f.mg_exp_other = mg_other ? fuse->merge_exp_other : nullptr;
+    f.mg_absmax = mg_other ? fuse->merge_absmax : nullptr;
+    f.status = c->d_status;
     if (M * (d->C / 16) > 0x7fffffffu) return EOQ_ERR_SHAPE;
     // few, large blocks: each ends with atomics on the same two or three slots
     size_t fb = (M * (d->C / 16) + 1023) / 1024;

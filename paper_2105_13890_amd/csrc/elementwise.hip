@@ -169,18 +169,6 @@ __global__ void relu_bwd_kernel(const int8_t *e0, const uint16_t *mask16, const 
 // ------------------------------------------------------------------------------------------
 // merge: abs-max of a*2^(Ea-Em) + b*2^(Eb-Em)
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ void merge_shifts(int Ea, int Eb, int &sa, int &sb, int &Em, uint32_t *status)
-{
-    Em = Ea < Eb ? Ea : Eb;
-    sa = Ea - Em;
-    sb = Eb - Em;
-    if (sa > 24 || sb > 24) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, (uint32_t)EOQ_FLAG_EXP_GAP);
-        sa = sa > 24 ? 24 : sa;
-        sb = sb > 24 ? 24 : sb;
-    }
-}
-
 __global__ void merge_absmax_kernel(const int8_t *a, const int32_t *exp_a, const int8_t *b, const int32_t *exp_b,
                                     size_t n, int32_t *absmax, uint32_t *status)
 {

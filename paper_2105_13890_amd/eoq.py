@@ -27,6 +27,11 @@ EXPORTS = [
 ]
 
 
+class BwdFuse(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("mask_bits", "e1", "sum_e1", "absmax_e1", "merge_other", "merge_exp_other",
+                                          "merge_absmax")]
+
+
 class ConvDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("N", "H", "W", "C", "K", "R", "S", "stride", "pad")]
 
@@ -75,7 +80,7 @@ def _load():
     lib.eoq_pre_bias.argtypes = [vp, vp, sz, vp, vp]
     lib.eoq_conv_fwd.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, C.POINTER(Epilogue), vp, sz]
     lib.eoq_conv_bwd_data.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, sz]
-    lib.eoq_conv_bwd_data_sq.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz]
+    lib.eoq_conv_bwd_data_sq.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, i32, vp, vp, C.POINTER(BwdFuse), vp, sz]
     lib.eoq_conv_bwd_weight.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, sz]
     lib.eoq_relu_bwd.argtypes = [vp, vp, vp, vp, sz, vp, vp, vp, vp]
     lib.eoq_relu_bwd_recompute.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, vp, vp]
@@ -172,10 +177,16 @@ class Context:
                                       _ptr(ws), _nbytes(ws)), "eoq_conv_bwd_data")
 
     def conv_bwd_data_sq(self, desc, e, w, e4, absmax_slot, exp_in, exp_in_off, exp_out, sum_out, ws,
-                         mask=None, e1=None, sum_e1=None, absmax_e1=None):
+                         mask=None, e1=None, sum_e1=None, absmax_e1=None, merge_other=None, merge_exp_other=None,
+                         merge_absmax=None):
+        fuse = None
+        if e1 is not None or merge_other is not None:
+            fuse = BwdFuse(_ptr(mask), _ptr(e1), _ptr(sum_e1), _ptr(absmax_e1), _ptr(merge_other),
+                           _ptr(merge_exp_other), _ptr(merge_absmax))
         _check(_lib.eoq_conv_bwd_data_sq(self._h, C.byref(desc), _ptr(e), _ptr(w), _ptr(e4), _ptr(absmax_slot),
-                                         _ptr(exp_in), exp_in_off, _ptr(exp_out), _ptr(sum_out), _ptr(mask), _ptr(e1),
-                                         _ptr(sum_e1), _ptr(absmax_e1), _ptr(ws), _nbytes(ws)), "eoq_conv_bwd_data_sq")
+                                         _ptr(exp_in), exp_in_off, _ptr(exp_out), _ptr(sum_out),
+                                         C.byref(fuse) if fuse is not None else None, _ptr(ws), _nbytes(ws)),
+               "eoq_conv_bwd_data_sq")
 
     def conv_bwd_weight(self, desc, e, u, g_acc, absmax_slot, ws):
         _check(_lib.eoq_conv_bwd_weight(self._h, C.byref(desc), _ptr(e), _ptr(u), _ptr(g_acc), _ptr(absmax_slot),

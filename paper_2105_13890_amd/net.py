@@ -418,11 +418,14 @@ class FixupNet:
             self._rec(u.name + ".gw", g.view(u.w.shape))
         return g
 
-    def _unit_bwd(self, u: Unit, e0, bufs, need_dx=True, relu_done=False, fuse_below: Unit | None = None):
+    def _unit_bwd(self, u: Unit, e0, bufs, need_dx=True, relu_done=False, fuse_below: Unit | None = None,
+                  merge=None):
         """Eq.3 / Eq.4 for one layer; e0 is overwritten by e1.  Returns (buffer with the error for the layer
         below or None, e1).  relu_done: e0 already is e1 (the ReLU backward step was fused into the call that
         produced it).  fuse_below: the layer whose output is this layer's input -- its ReLU backward step and
-        sums are applied by this layer's backward-data call, which then returns e1 of that layer instead of e4."""
+        sums are applied by this layer's backward-data call, which then returns e1 of that layer instead of e4.
+        merge = (other error buffer, its exponent slot, abs-max slot): this layer's e4 is one of the two errors
+        that meet at the block input; the statistics of their sum are taken by the same call."""
         c = self.ctx
         n_out = int(np.prod(u.out_shape))
         e1 = e0
@@ -460,9 +463,13 @@ class FixupNet:
                 if self.tracing:
                     self._rec(u.name + ".e4", e4_dbg)
             else:
+                mg = {}
+                if merge is not None:
+                    mg = dict(merge_other=merge[0][:n_in], merge_exp_other=self.s32(merge[1]),
+                              merge_absmax=self.s32(merge[2]))
                 self._call("conv_bwd_data", u.name, self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
                            e4[:n_in], self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
-                           self.s64(u.name + ".S_e4"), self.ws)
+                           self.s64(u.name + ".S_e4"), self.ws, **mg)
                 if self.tracing:
                     self._rec(u.name + ".e4", e4[:n_in].view(u.in_shape))
         # W <- Q_w(W - Q_u(lr g)) (Eq.13) once every reader of the old weights has run
@@ -483,25 +490,28 @@ class FixupNet:
         """e: buffer holding the error at the last block's output (exponent slot self.E_top)."""
         c = self.ctx
         for b in reversed(self.blocks):
+            assert len(b.units) >= 2
             last = b.units[-1]
             # e now holds e1 of the last layer = shortcut error; its backward-data call already applies the ReLU
             # backward step of the layer below it, and so on down the branch
             e4, e_sk = self._unit_bwd(last, e, bufs, fuse_below=b.units[-2] if len(b.units) > 1 else None)
             E_sk = last.E0
             cur = e4
+            M_in = b.name + ".M_in"
             for idx in range(len(b.units) - 2, -1, -1):
+                # the first layer's e4 meets the shortcut error at the block input (identity shortcut: e_sk itself)
+                mg = (e_sk, E_sk, M_in) if (idx == 0 and not b.ds) else None
                 nxt, _ = self._unit_bwd(b.units[idx], cur, bufs, relu_done=True,
-                                        fuse_below=b.units[idx - 1] if idx > 0 else None)
+                                        fuse_below=b.units[idx - 1] if idx > 0 else None, merge=mg)
                 bufs.append(cur)
                 cur = nxt
             first = b.units[0]
             n_in = int(np.prod(first.in_shape))
             if b.ds:
-                e4d, _ = self._unit_bwd(b.ds, e_sk, bufs)
+                e4d, _ = self._unit_bwd(b.ds, e_sk, bufs, merge=(cur, first.E4, M_in))
                 other, E_other = e4d, b.ds.E4
             else:
                 other, E_other = e_sk, E_sk
-            c.merge_absmax(cur[:n_in], self.s32(first.E4), other[:n_in], self.s32(E_other), self.s32(b.name + ".M_in"))
             out = cur
             c.requant_epilogue(eoq.RQ_SQ_MERGE, n_in, src_a=cur[:n_in], src_b=other[:n_in], exp_in=self.s32(first.E4),
                                exp_b=self.s32(E_other), absmax=self.s32(b.name + ".M_in"), out=out[:n_in],

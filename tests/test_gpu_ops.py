@@ -196,8 +196,17 @@ def _bwd_data_sq_case(ctx, d, e, w, with_mask):
         ctx.conv_bwd_data_sq(desc_of(d), dev(e), dev(w), e4, sl[0:1], sl[1:2], -7, sl[2:3], sums[0:1],
                              ws_for(d, eoq.OP_CONV_BWD_DATA), mask=mask, e1=e1, sum_e1=sums[1:2], absmax_e1=sl[3:4])
     else:
+        # with the statistics of the block-input merge against another error tensor on a coarser grid
+        other = si.uniform_int8(6, "other", ishape)
+        mg = dev(np.array([-17, 0], dtype=np.int32))
+        other_d = dev(other)
         ctx.conv_bwd_data_sq(desc_of(d), dev(e), dev(w), e4, sl[0:1], sl[1:2], -7, sl[2:3], sums[0:1],
-                             ws_for(d, eoq.OP_CONV_BWD_DATA))
+                             ws_for(d, eoq.OP_CONV_BWD_DATA), merge_other=other_d, merge_exp_other=mg[0:1],
+                             merge_absmax=mg[1:2])
+        e4c, E4c = oo.sq_acc(want, -13 - 7)
+        Em = min(E4c, -17)
+        merged = e4c.astype(np.int64) * (1 << (E4c - Em)) + other.astype(np.int64) * (1 << (-17 - Em))
+        assert int(host(mg)[1]) == int(np.abs(merged).max())
     e4o, E4o = oo.sq_acc(want, -13 - 7)
     assert np.array_equal(host(e4), e4o) and int(host(sl)[2]) == E4o
     assert int(host(sl)[0]) == int(np.abs(want).max())
