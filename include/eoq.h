@@ -150,6 +150,9 @@ int eoq_conv_bwd_data(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, 
  *  - the statistics of the block-input merge: with merge_other non-NULL (int8 codes of the other error, same
  *    shape, exponent *merge_exp_other), *merge_absmax max= max|e4 * 2^(E4-Em) + other * 2^(Eo-Em)|,
  *    Em = min(E4, Eo), what eoq_merge_absmax computes; needs e4 and excludes e1.
+ *  - w_transposed non-NULL: the filters in C x R x S x K order, as written by eoq_transpose_filters from the same
+ *    w; the call then skips its own transposition (a caller that updates w once per step transposes it once,
+ *    off the critical path).
  * Requires 127^2 * R*S*K < 2^30. */
 typedef struct eoq_bwd_fuse {
     const uint32_t *mask_bits;
@@ -159,10 +162,14 @@ typedef struct eoq_bwd_fuse {
     const int8_t *merge_other;
     const int32_t *merge_exp_other;
     int32_t *merge_absmax;
+    const int8_t *w_transposed;
 } eoq_bwd_fuse;
 int eoq_conv_bwd_data_sq(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, const int8_t *w, int8_t *e4,
                          int32_t *absmax_slot, const int32_t *exp_in, int32_t exp_in_off, int32_t *exp_out,
                          int64_t *sum_out, const eoq_bwd_fuse *fuse, void *ws, size_t ws_bytes);
+
+/* Filters K x R x S x C -> C x R x S x K, the operand order of the backward-data gather (Eq.3 line e4). */
+int eoq_transpose_filters(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *w, int8_t *wt);
 
 /* ---- weight-gradient convolution: Eq.4 line g_w before Q_g ------------------------------------
  * g_acc[k,r,s,c] = sum_{n,p,q} e[n,p,q,k] * u[n, p*stride+r-pad, q*stride+s-pad, c], the exact integer

@@ -130,17 +130,29 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
     uint32_t yw[4] = {0, 0, 0, 0}, uw[4] = {0, 0, 0, 0};
     uint32_t mask = 0;
     const int b128 = bpost << 7;
+    // channels are walked from 15 down to 0 so that the mask can be built by shifting one sign bit in per element
+    // (alignbit(mask, -z, 31) = mask << 1 | [z > 0]; z != INT_MIN on the 32-bit path)
 #pragma unroll
-    for (int k = 0; k < 16; ++k) {
+    for (int kk = 0; kk < 16; ++kk) {
+        const int k = 15 - kk;
         int yc;
         if (FAST) {
-            const int z = __mul24(gamma, t[k]) + ((sk[k] << 7) + b128);      // both factors are below 2^23 here: full-rate multiply
-            mask |= ((uint32_t)(-z) >> 31) << k;                 // z > 0  (z != INT_MIN here)
-            yc = rne_shift7(z);
-            yc = yc < 0 ? 0 : (yc > CODE_MAX ? CODE_MAX : yc);   // = clamp(R(max(z,0)/128)): R is monotone, R(0) = 0
+            if (gamma == 128) {
+                // multiplier exactly one (every layer without a multiplier, and a block's last layer until its
+                // multiplier moves): z = 128 * (t + b + skip) is a multiple of 128, so Q_a2 rounds nothing and
+                // y = clamp(t + b + skip, 0, 127), [z > 0] = [t + b + skip > 0]
+                const int w = t[k] + sk[k] + bpost;
+                mask = __builtin_amdgcn_alignbit(mask, (uint32_t)(-w), 31);
+                yc = w < 0 ? 0 : (w > CODE_MAX ? CODE_MAX : w);
+            } else {
+                const int z = __mul24(gamma, t[k]) + ((sk[k] << 7) + b128);      // both factors are below 2^23 here
+                mask = __builtin_amdgcn_alignbit(mask, (uint32_t)(-z), 31);
+                yc = rne_shift7(z);
+                yc = yc < 0 ? 0 : (yc > CODE_MAX ? CODE_MAX : yc);   // = clamp(R(max(z,0)/128)): R is monotone, R(0) = 0
+            }
         } else {
             const int64_t z = (int64_t)gamma * (int64_t)t[k] + 128 * ((int64_t)bpost + (int64_t)sk[k]);
-            mask |= (z > 0 ? 1u : 0u) << k;
+            mask = (mask << 1) | (z > 0 ? 1u : 0u);
             const int64_t yy = rne_shift64(z > 0 ? z : 0, 7);
             yc = (int)(yy > CODE_MAX ? CODE_MAX : yy);
         }
@@ -1132,6 +1144,16 @@ static int bwd_data_params(const eoq_conv_desc *d, const int8_t *e, const int8_t
     return EOQ_OK;
 }
 
+extern "C" int eoq_transpose_filters(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *w, int8_t *wt)
+{
+    if (!c || !w || !wt || (((uintptr_t)w | (uintptr_t)wt) & 15)) return EOQ_ERR_ARG;
+    if (!desc_ok(d)) return EOQ_ERR_SHAPE;
+    hipLaunchKernelGGL(transpose_filters_kernel, dim3(grid_for((size_t)d->K * d->R * d->S * d->C)), dim3(256), 0,
+                       c->stream, w, d->K, d->R * d->S, d->C, wt);
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}
+
 extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *e, const int8_t *w, int8_t *e4,
                                     int32_t *absmax_slot, const int32_t *exp_in, int32_t exp_in_off, int32_t *exp_out,
                                     int64_t *sum_out, const eoq_bwd_fuse *fuse, void *ws, size_t ws_bytes)
@@ -1150,12 +1172,16 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
     if (((uintptr_t)e | (uintptr_t)w | (uintptr_t)e4 | (uintptr_t)e1) & 15 || ((uintptr_t)mask_bits & 3)) return EOQ_ERR_ARG;
     if (!ws || ws_bytes < eoq_workspace_bytes(d, EOQ_OP_CONV_BWD_DATA) || ((uintptr_t)ws & 15)) return EOQ_ERR_WORKSPACE;
     const size_t M = (size_t)d->N * d->H * d->W;
-    int8_t *wt = (int8_t *)ws;
-    int16_t *d16 = (int16_t *)(wt + round_up((size_t)d->K * d->R * d->S * d->C, 256));
+    const int8_t *wt = fuse ? fuse->w_transposed : nullptr;
+    if ((uintptr_t)wt & 15) return EOQ_ERR_ARG;
+    int16_t *d16 = (int16_t *)((int8_t *)ws + round_up((size_t)d->K * d->R * d->S * d->C, 256));
     int32_t *tile_shift = (int32_t *)((int8_t *)d16 + round_up(2 * M * d->C, 256));
-    hipLaunchKernelGGL(transpose_filters_kernel, dim3(grid_for((size_t)d->K * d->R * d->S * d->C)), dim3(256), 0,
-                       c->stream, w, d->K, d->R * d->S, d->C, wt);
-    EOQ_LAUNCH_CHECK();
+    if (!wt) {
+        hipLaunchKernelGGL(transpose_filters_kernel, dim3(grid_for((size_t)d->K * d->R * d->S * d->C)), dim3(256), 0,
+                           c->stream, w, d->K, d->R * d->S, d->C, (int8_t *)ws);
+        EOQ_LAUNCH_CHECK();
+        wt = (const int8_t *)ws;
+    }
     IgemmParams p{};
     p.status = c->d_status;
     if (int rc = bwd_data_params(d, e, wt, p)) return rc;

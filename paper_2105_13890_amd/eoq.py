@@ -20,7 +20,7 @@ RQ_FWD, RQ_SQ_ACC, RQ_SQ_GAMMA, RQ_SQ_MERGE = 0, 1, 2, 3
 
 EXPORTS = [
     "eoq_create", "eoq_destroy", "eoq_strerror", "eoq_status", "eoq_workspace_bytes", "eoq_fill_zero",
-    "eoq_quantize", "eoq_pre_bias", "eoq_conv_fwd", "eoq_conv_bwd_data", "eoq_conv_bwd_data_sq", "eoq_conv_bwd_weight",
+    "eoq_quantize", "eoq_pre_bias", "eoq_conv_fwd", "eoq_conv_bwd_data", "eoq_conv_bwd_data_sq", "eoq_transpose_filters", "eoq_conv_bwd_weight",
     "eoq_relu_bwd", "eoq_relu_bwd_recompute", "eoq_merge_absmax", "eoq_requant_epilogue", "eoq_update_int8", "eoq_update_scalars",
     "eoq_maxpool_fwd", "eoq_maxpool_bwd", "eoq_maxpool_bwd_sq", "eoq_gap_sum", "eoq_broadcast_hw", "eoq_head_workspace_bytes",
     "eoq_head_fwd_bwd",
@@ -29,7 +29,7 @@ EXPORTS = [
 
 class BwdFuse(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("mask_bits", "e1", "sum_e1", "absmax_e1", "merge_other", "merge_exp_other",
-                                          "merge_absmax")]
+                                          "merge_absmax", "w_transposed")]
 
 
 class ConvDesc(C.Structure):
@@ -80,6 +80,7 @@ def _load():
     lib.eoq_pre_bias.argtypes = [vp, vp, sz, vp, vp]
     lib.eoq_conv_fwd.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, C.POINTER(Epilogue), vp, sz]
     lib.eoq_conv_bwd_data.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, sz]
+    lib.eoq_transpose_filters.argtypes = [vp, C.POINTER(ConvDesc), vp, vp]
     lib.eoq_conv_bwd_data_sq.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, i32, vp, vp, C.POINTER(BwdFuse), vp, sz]
     lib.eoq_conv_bwd_weight.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, sz]
     lib.eoq_relu_bwd.argtypes = [vp, vp, vp, vp, sz, vp, vp, vp, vp]
@@ -176,13 +177,16 @@ class Context:
         _check(_lib.eoq_conv_bwd_data(self._h, C.byref(desc), _ptr(e), _ptr(w), _ptr(d_acc), _ptr(absmax_slot),
                                       _ptr(ws), _nbytes(ws)), "eoq_conv_bwd_data")
 
+    def transpose_filters(self, desc, w, wt):
+        _check(_lib.eoq_transpose_filters(self._h, C.byref(desc), _ptr(w), _ptr(wt)), "eoq_transpose_filters")
+
     def conv_bwd_data_sq(self, desc, e, w, e4, absmax_slot, exp_in, exp_in_off, exp_out, sum_out, ws,
                          mask=None, e1=None, sum_e1=None, absmax_e1=None, merge_other=None, merge_exp_other=None,
-                         merge_absmax=None):
+                         merge_absmax=None, w_transposed=None):
         fuse = None
-        if e1 is not None or merge_other is not None:
+        if e1 is not None or merge_other is not None or w_transposed is not None:
             fuse = BwdFuse(_ptr(mask), _ptr(e1), _ptr(sum_e1), _ptr(absmax_e1), _ptr(merge_other),
-                           _ptr(merge_exp_other), _ptr(merge_absmax))
+                           _ptr(merge_exp_other), _ptr(merge_absmax), _ptr(w_transposed))
         _check(_lib.eoq_conv_bwd_data_sq(self._h, C.byref(desc), _ptr(e), _ptr(w), _ptr(e4), _ptr(absmax_slot),
                                          _ptr(exp_in), exp_in_off, _ptr(exp_out), _ptr(sum_out),
                                          C.byref(fuse) if fuse is not None else None, _ptr(ws), _nbytes(ws)),

@@ -40,6 +40,7 @@ class Unit:
     b_post: str | None
     relu: bool = True
     w: torch.Tensor = None            # int8 KRSC
+    wt: torch.Tensor = None           # the same filters as CRSK (operand of the backward-data convolution)
     u: torch.Tensor = None            # int8 biased input x1 (what the convolution reads)
     mask: torch.Tensor = None         # ReLU bits
     t: torch.Tensor = None            # wide Q_a1 output (multiplier layers, shortcut convolutions)
@@ -158,6 +159,9 @@ class FixupNet:
             wf = torch.from_numpy((z * std).astype(np.float32)).to(self.dev)
             u.w = torch.empty((d.K, d.R, d.S, d.C), dtype=torch.int8, device=self.dev)
             self.ctx.quantize(wf, eoq.CQ, 0, u.w)                  # Q_w = CQ (Eq.8)
+            if d.C % 16 == 0 and d.K % 16 == 0:
+                u.wt = torch.empty_like(u.w)                       # refreshed after every update, off the critical path
+                self.ctx.transpose_filters(d, u.w, u.wt)
         if self.classes:
             z = si.standard_normal(seed, "fc.w", (self.classes, ch))
             self.Wfc = torch.from_numpy(z * math.sqrt(2.0 / ch)).to(self.dev)
@@ -458,7 +462,7 @@ class FixupNet:
                 f = fuse_below
                 self._call("conv_bwd_data", u.name, self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
                            e4_dbg, self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
-                           self.s64(u.name + ".S_e4"), self.ws, mask=f.mask, e1=e4[:n_in],
+                           self.s64(u.name + ".S_e4"), self.ws, w_transposed=u.wt, mask=f.mask, e1=e4[:n_in],
                            sum_e1=self.s64(f.name + ".S_e1"), absmax_e1=self.s32(f.name + ".M_e1"))
                 if self.tracing:
                     self._rec(u.name + ".e4", e4_dbg)
@@ -469,7 +473,7 @@ class FixupNet:
                               merge_absmax=self.s32(merge[2]))
                 self._call("conv_bwd_data", u.name, self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
                            e4[:n_in], self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
-                           self.s64(u.name + ".S_e4"), self.ws, **mg)
+                           self.s64(u.name + ".S_e4"), self.ws, w_transposed=u.wt, **mg)
                 if self.tracing:
                     self._rec(u.name + ".e4", e4[:n_in].view(u.in_shape))
         # W <- Q_w(W - Q_u(lr g)) (Eq.13) once every reader of the old weights has run
@@ -478,10 +482,14 @@ class FixupNet:
                 u.ev_dx.record(self.main)
                 self.side.wait_event(u.ev_dx)
             self.ctx_w.update_int8(u.w, g, self.s32(u.name + ".Eg"), self.s32(u.name + ".gmax"), self.lr)
+            if u.wt is not None:
+                self.ctx_w.transpose_filters(u.desc, u.w, u.wt)
             u.ev_done.record(self.side)
             self._pending[e3.data_ptr()] = u.ev_done       # e3 may not be overwritten before dW has read it
         else:
             c.update_int8(u.w, g, self.s32(u.name + ".Eg"), self.s32(u.name + ".gmax"), self.lr)
+            if u.wt is not None:
+                c.transpose_filters(u.desc, u.w, u.wt)
         if u.gamma:
             bufs.append(e3)
         return e4, e1
