@@ -15,7 +15,7 @@ struct eoq_ctx {
 };
 
 constexpr int EOQ_SCRATCH_SLOTS = 64;
-constexpr int EOQ_PARTIAL_SLOTS = 2 * 32768;
+constexpr int EOQ_PARTIAL_SLOTS = 1 << 20;      // 8 MB: per-wave pairs of the largest benchmark layer
 constexpr int CODE_MAX = 127;
 
 #define EOQ_HIP(expr)                                  \

@@ -643,15 +643,18 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
     if (EPI == EPI_SQ && p.sq_sum_out) block_atomic_add_i64(sq_sum, p.sq_sum_out);
     if (EPI == EPI_RELU_BWD) {
         if (p.rb_part) {
-            // thousands of workgroups adding to two slots would queue up behind each other: each stores its own
-            // pair, a one-block kernel adds them up afterwards
-            const int64_t a = block_sum_i64(sq_sum), b = block_sum_i64(rb_st);
-            if (tid == 0) { p.rb_part[2 * bid] = a; p.rb_part[2 * bid + 1] = b; }
+            // thousands of workgroups adding to two slots would queue up behind each other: each wave stores its
+            // own pair (no barrier, no shared memory), a one-block kernel adds them up afterwards
+            const int64_t a = wave_sum_i64(sq_sum), b = wave_sum_i64(rb_st);
+            if (lane == 0) { p.rb_part[2 * (4 * bid + wave)] = a; p.rb_part[2 * (4 * bid + wave) + 1] = b; }
         } else {
             if (p.rb_sum_e1) block_atomic_add_i64(sq_sum, p.rb_sum_e1);
             if (p.rb_sum_e1t) block_atomic_add_i64(rb_st, p.rb_sum_e1t);
         }
-        if (p.rb_absmax) block_atomic_max_i32(mx, p.rb_absmax);
+        if (p.rb_absmax) {
+            const int wm_ = wave_max_i32(mx);
+            if (lane == 0) slot_atomic_max_i32(p.rb_absmax, wm_);
+        }
     }
 }
 
@@ -758,11 +761,14 @@ __global__ void requant_fwd_kernel(const int32_t *acc, size_t n16, EpiDev ep)
     }
 }
 
-// adds up per-workgroup pairs of partial sums (one block)
+// adds up the per-wave pairs of partial sums (a handful of blocks: two atomics each)
 __global__ __launch_bounds__(1024) void pair_reduce_kernel(const int64_t *part, int n, int64_t *sum0, int64_t *sum1)
 {
     int64_t a = 0, b = 0;
-    for (int i = threadIdx.x; i < n; i += blockDim.x) { a += part[2 * i]; b += part[2 * i + 1]; }
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+        a += part[2 * i];
+        b += part[2 * i + 1];
+    }
     a = block_sum_i64(a);
     b = block_sum_i64(b);
     if (threadIdx.x == 0) {
@@ -1118,12 +1124,15 @@ extern "C" int eoq_relu_bwd_recompute(eoq_ctx *c, const eoq_conv_desc *d, const 
     p.rb_sum_e1 = sum_e1; p.rb_sum_e1t = sum_e1t; p.rb_absmax = absmax_e1;
     // every tile shape the dispatcher may choose is at least 64 x 32
     const long max_tiles = (long)((p.M + 63) / 64) * ((p.NOUT + 31) / 32);
-    if ((sum_e1 || sum_e1t) && 2 * max_tiles <= EOQ_PARTIAL_SLOTS) p.rb_part = c->d_partials;
+    if ((sum_e1 || sum_e1t) && 8 * max_tiles <= EOQ_PARTIAL_SLOTS) p.rb_part = c->d_partials;
     int bm = 0, bn = 0;
     if (int rc = dispatch_igemm<MODE_FWD, EPI_RELU_BWD>(c, p, &bm, &bn)) return rc;
     if (p.rb_part) {
         const int tiles = ((p.M + bm - 1) / bm) * ((p.NOUT + bn - 1) / bn);
-        hipLaunchKernelGGL(pair_reduce_kernel, dim3(1), dim3(1024), 0, c->stream, c->d_partials, tiles, sum_e1, sum_e1t);
+        int rblocks = (4 * tiles + 1023) / 1024;
+        if (rblocks > 32) rblocks = 32;
+        hipLaunchKernelGGL(pair_reduce_kernel, dim3(rblocks), dim3(1024), 0, c->stream, c->d_partials, 4 * tiles, sum_e1,
+                           sum_e1t);
         EOQ_LAUNCH_CHECK();
     }
     return EOQ_OK;
