@@ -44,12 +44,6 @@ struct IgemmParams {
     int32_t *absmax;
     uint32_t *status;  // device status word of the context
     EpiDev ep;
-    // EPI_SQ: scale-quantised int8 output (Q_e fused into the second evaluation of the convolution)
-    int8_t *sq_out;
-    const int32_t *sq_exp_in;
-    int32_t sq_exp_off;
-    int32_t *sq_exp_out;
-    int64_t *sq_sum_out;
     // EPI_D16: 16-bit block-scaled output of the backward-data convolution (one shift per workgroup tile)
     int16_t *d16;
     int32_t *tile_shift;
@@ -63,7 +57,7 @@ struct IgemmParams {
 };
 
 enum { MODE_FWD = 0, MODE_BWD_DATA = 1 };
-enum { EPI_FWD = 0, EPI_ACC = 1, EPI_ABSMAX = 2, EPI_SQ = 3, EPI_RELU_BWD = 4, EPI_D16 = 5 };
+enum { EPI_FWD = 0, EPI_ACC = 1, EPI_RELU_BWD = 4, EPI_D16 = 5 };
 
 __device__ __forceinline__ void set_byte(v4i &v, int i, int code)
 {
@@ -446,23 +440,6 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
     __syncthreads();
 
     // ---- epilogue ----
-    if (EPI == EPI_ABSMAX) {
-        // first evaluation of a two-pass scale quantisation: only max|acc| is needed, straight from the
-        // accumulator registers (rows / columns outside the problem accumulated zeros)
-        int mx0 = 0;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int jn = 0; jn < TN; ++jn)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int v = acc[i][jn][e];
-                    const int av = v < 0 ? -v : v;
-                    mx0 = av > mx0 ? av : mx0;
-                }
-        block_atomic_max_i32(mx0, p.absmax);
-        return;
-    }
     // Block-scaled 16-bit output (the scale quantiser of Eq.11 needs max|d| of the WHOLE tensor before any element
     // can be coded, so the exact 32-bit sums would have to be stored or recomputed).  Instead each workgroup keeps,
     // relative to the largest magnitude of ITS tile, the top 14 bits of every sum plus a sticky bit (any dropped
@@ -498,13 +475,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
         }
     }
     // per wave, 32 rows at a time through LDS
-    int sq_r = 7;
     long long sq_sum = 0, rb_st = 0;
-    if (EPI == EPI_SQ) {
-        const uint32_t M = (uint32_t)*p.absmax;
-        sq_r = M ? sq_exponent_u32(M) : 7;
-        if (blockIdx.x == 0 && tid == 0) *p.sq_exp_out = *p.sq_exp_in + p.sq_exp_off + sq_r - 7;
-    }
     int32_t *stg = (int32_t *)lds + wave * 32 * EPI_LD;
     constexpr int GROUPS = WTN / 16;              // 16-channel groups per row of the wave tile
     constexpr int ROWS_PER_PASS = 64 / GROUPS;
@@ -607,21 +578,6 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
                     v4i *dst = (v4i *)(p.d16 + off);
                     dst[0] = v4i{(int)w8[0], (int)w8[1], (int)w8[2], (int)w8[3]};
                     dst[1] = v4i{(int)w8[4], (int)w8[5], (int)w8[6], (int)w8[7]};
-                } else if (EPI == EPI_SQ) {
-                    // Q_e (Eq.11): clamp(R(v * 2^(7-r))); |v| < 2^30 here, so 32-bit arithmetic is exact
-                    const int sh = sq_r - 7;
-                    v4i o = {0, 0, 0, 0};
-                    int ls = 0;
-#pragma unroll
-                    for (int k = 0; k < 16; ++k) {
-                        int cde = sh <= 0 ? (v[k] << (-sh))
-                                          : ((v[k] + ((1 << (sh - 1)) - 1) + ((v[k] >> sh) & 1)) >> sh);
-                        cde = clamp_i(cde, -CODE_MAX, CODE_MAX);
-                        ls += cde;
-                        set_byte(o, k, cde);
-                    }
-                    sq_sum += ls;
-                    *(v4i *)(p.sq_out + off) = o;
                 } else {
 #pragma unroll
                     for (int k4 = 0; k4 < 4; ++k4) {
@@ -640,7 +596,6 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
     }
     if (EPI == EPI_FWD && range_bad) atomicOr(p.status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);
     if (EPI == EPI_ACC && p.absmax) block_atomic_max_i32(mx, p.absmax);
-    if (EPI == EPI_SQ && p.sq_sum_out) block_atomic_add_i64(sq_sum, p.sq_sum_out);
     if (EPI == EPI_RELU_BWD) {
         if (p.rb_part) {
             // thousands of workgroups adding to two slots would queue up behind each other: each wave stores its
