@@ -125,34 +125,43 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
     uint32_t mask = 0;
     const int b128 = bpost << 7;
     // channels are walked from 15 down to 0 so that the mask can be built by shifting one sign bit in per element
-    // (alignbit(mask, -z, 31) = mask << 1 | [z > 0]; z != INT_MIN on the 32-bit path)
-#pragma unroll
-    for (int kk = 0; kk < 16; ++kk) {
-        const int k = 15 - kk;
-        int yc;
-        if (FAST) {
-            if (gamma == 128) {
-                // multiplier exactly one (every layer without a multiplier, and a block's last layer until its
-                // multiplier moves): z = 128 * (t + b + skip) is a multiple of 128, so Q_a2 rounds nothing and
-                // y = clamp(t + b + skip, 0, 127), [z > 0] = [t + b + skip > 0]
-                const int w = t[k] + sk[k] + bpost;
-                mask = __builtin_amdgcn_alignbit(mask, (uint32_t)(-w), 31);
-                yc = w < 0 ? 0 : (w > CODE_MAX ? CODE_MAX : w);
-            } else {
-                const int z = __mul24(gamma, t[k]) + ((sk[k] << 7) + b128);      // both factors are below 2^23 here
-                mask = __builtin_amdgcn_alignbit(mask, (uint32_t)(-z), 31);
-                yc = rne_shift7(z);
-                yc = yc < 0 ? 0 : (yc > CODE_MAX ? CODE_MAX : yc);   // = clamp(R(max(z,0)/128)): R is monotone, R(0) = 0
-            }
-        } else {
-            const int64_t z = (int64_t)gamma * (int64_t)t[k] + 128 * ((int64_t)bpost + (int64_t)sk[k]);
-            mask = (mask << 1) | (z > 0 ? 1u : 0u);
-            const int64_t yy = rne_shift64(z > 0 ? z : 0, 7);
-            yc = (int)(yy > CODE_MAX ? CODE_MAX : yy);
-        }
+    // (alignbit(mask, -z, 31) = mask << 1 | [z > 0]; z != INT_MIN on the 32-bit path).  The three variants are
+    // three separate loops: a uniform test inside the loop is not hoisted by the compiler and turns into a branch
+    // per element.
+    auto put = [&](int k, int yc) {
         const int uc = clamp_i(yc + bnext, -CODE_MAX, CODE_MAX);
         yw[k >> 2] |= (uint32_t)yc << (8 * (k & 3));
         uw[k >> 2] |= ((uint32_t)uc & 0xffu) << (8 * (k & 3));
+    };
+    if (FAST && gamma == 128) {
+        // multiplier exactly one (every layer without a multiplier, and a block's last layer until its multiplier
+        // moves): z = 128 * (t + b + skip) is a multiple of 128, so Q_a2 rounds nothing and
+        // y = clamp(t + b + skip, 0, 127), [z > 0] = [t + b + skip > 0]
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const int k = 15 - kk;
+            const int w = t[k] + sk[k] + bpost;
+            mask = __builtin_amdgcn_alignbit(mask, (uint32_t)(-w), 31);
+            put(k, w < 0 ? 0 : (w > CODE_MAX ? CODE_MAX : w));
+        }
+    } else if (FAST) {
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const int k = 15 - kk;
+            const int z = __mul24(gamma, t[k]) + ((sk[k] << 7) + b128);      // both factors are below 2^23 here
+            mask = __builtin_amdgcn_alignbit(mask, (uint32_t)(-z), 31);
+            const int yc = rne_shift7(z);
+            put(k, yc < 0 ? 0 : (yc > CODE_MAX ? CODE_MAX : yc));   // = clamp(R(max(z,0)/128)): R is monotone, R(0) = 0
+        }
+    } else {
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const int k = 15 - kk;
+            const int64_t z = (int64_t)gamma * (int64_t)t[k] + 128 * ((int64_t)bpost + (int64_t)sk[k]);
+            mask = (mask << 1) | (z > 0 ? 1u : 0u);
+            const int64_t yy = rne_shift64(z > 0 ? z : 0, 7);
+            put(k, (int)(yy > CODE_MAX ? CODE_MAX : yy));
+        }
     }
     if (ep.y) *(v4i *)(ep.y + off) = v4i{(int)yw[0], (int)yw[1], (int)yw[2], (int)yw[3]};
     if (ep.u_next) *(v4i *)(ep.u_next + off) = v4i{(int)uw[0], (int)uw[1], (int)uw[2], (int)uw[3]};
