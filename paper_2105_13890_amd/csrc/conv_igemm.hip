@@ -764,6 +764,9 @@ struct D16Finish {
     const int32_t *mg_exp_other;
     int32_t *mg_absmax;
     uint32_t *status;
+    // strided 1x1 filter: the sums exist only for the input pixels the filter touched (every sub-th row and column),
+    // stored compactly as N x P x Q rows; all other input pixels receive no error
+    int sub, H, W, P, Q;
 };
 
 template <bool RELU>
@@ -791,10 +794,26 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
     int since = 0;
     for (; i < total; i += step) {
         const int c = (int)cg << 4;
-        const int s = p.tile_shift[(m >> p.bm_shift) * p.tiles_n + (c >> p.bn_shift)];
-        const int T = sh - s + 1;                          // rounding position inside the stored 16-bit value
         const size_t off = (size_t)m * p.C + c;
-        const v4i lo = ((const v4i *)(p.d16 + off))[0], hi = ((const v4i *)(p.d16 + off))[1];
+        uint32_t mrow = m;                                 // row of the stored sums
+        bool have = true;
+        if (p.sub) {
+            const uint32_t hw = (uint32_t)(p.H * p.W);
+            const uint32_t n = m / hw, rem = m - n * hw;
+            const uint32_t h = rem / (uint32_t)p.W, x = rem - h * (uint32_t)p.W;
+            const uint32_t hp = h / (uint32_t)p.sub, xq = x / (uint32_t)p.sub;
+            have = hp * p.sub == h && xq * p.sub == x;
+            mrow = (n * p.P + hp) * p.Q + xq;
+        }
+        int s = 0;
+        v4i lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
+        if (have) {
+            s = p.tile_shift[(mrow >> p.bm_shift) * p.tiles_n + (c >> p.bn_shift)];
+            const size_t src = (size_t)mrow * p.C + c;
+            lo = ((const v4i *)(p.d16 + src))[0];
+            hi = ((const v4i *)(p.d16 + src))[1];
+        }
+        const int T = sh - s + 1;                          // rounding position inside the stored 16-bit value
         int v[16];
 #pragma unroll
         for (int k = 0; k < 16; k += 2) {
@@ -1164,7 +1183,17 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
     }
     IgemmParams p{};
     p.status = c->d_status;
-    if (int rc = bwd_data_params(d, e, wt, p)) return rc;
+    // A strided 1x1 filter touches only every stride-th input row and column: the sums are formed for those pixels
+    // alone (a stride-1 problem on the P x Q grid of the error) and the streaming kernel writes zeros elsewhere --
+    // 1/stride^2 of the multiply-adds of the general gather, which would spend the rest on structural zeros.
+    const bool sub = d->R == 1 && d->S == 1 && d->pad == 0 && d->stride > 1;
+    eoq_conv_desc dsub = *d;
+    if (sub) {
+        dsub.H = conv_out_dim(d->H, 0, 1, d->stride);
+        dsub.W = conv_out_dim(d->W, 0, 1, d->stride);
+        dsub.stride = 1;
+    }
+    if (int rc = bwd_data_params(sub ? &dsub : d, e, wt, p)) return rc;
     p.absmax = absmax_slot;
     p.d16 = d16;
     p.tile_shift = tile_shift;
@@ -1183,6 +1212,7 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
     f.mg_exp_other = mg_other ? fuse->merge_exp_other : nullptr;
     f.mg_absmax = mg_other ? fuse->merge_absmax : nullptr;
     f.status = c->d_status;
+    if (sub) { f.sub = d->stride; f.H = d->H; f.W = d->W; f.P = dsub.H; f.Q = dsub.W; }
     if (M * (d->C / 16) > 0x7fffffffu) return EOQ_ERR_SHAPE;
     // few, large blocks: each ends with atomics on the same two or three slots
     size_t fb = (M * (d->C / 16) + 1023) / 1024;

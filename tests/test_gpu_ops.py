@@ -218,7 +218,11 @@ def _bwd_data_sq_case(ctx, d, e, w, with_mask):
         assert int(host(sl)[3]) == int(np.abs(e1o.astype(np.int64)).max())
 
 
-@pytest.mark.parametrize("d", CONV_SHAPES[:8], ids=IDS[:8])
+SQ_SHAPES = CONV_SHAPES[:8] + [ConvShape(2, 17, 13, 32, 64, 1, 1, 2, 0),     # strided 1x1, odd extents
+                               ConvShape(1, 10, 10, 16, 48, 1, 1, 3, 0)]     # stride 3
+
+
+@pytest.mark.parametrize("d", SQ_SHAPES, ids=[f"{d.N}x{d.H}x{d.W}x{d.C}-k{d.K}r{d.R}s{d.stride}" for d in SQ_SHAPES])
 def test_conv_bwd_data_sq(ctx, d):
     """One evaluation of the convolution, 16-bit block-scaled intermediate: the codes must equal Q_e of the exact
     sums whatever the spread of magnitudes between tiles -- uniform errors, errors that are tiny in half of the
