@@ -336,14 +336,14 @@ class FixupNet:
         return 2.0 * d.N * d.P * d.Q * d.K * d.C * d.R * d.S       # algorithmic ops (multiply-add = 2)
 
     # ------------------------------------------------------------------------------------------ forward
-    def _unit_fwd(self, u: Unit, skip=None, y=None, u_next=None, b_next=None):
-        c = self.ctx
+    def _unit_fwd(self, u: Unit, skip=None, y=None, u_next=None, b_next=None, side=False):
+        c, ws, st = (self.ctx_w, self.ws_w, self.side) if side else (self.ctx, self.ws, self.main)
         if not u.relu:
             ep = c.epilogue(relu=0, t_wide=u.t)
         else:
             ep = c.epilogue(gamma=self.sc(u.gamma), b_post=self.sc(u.b_post), skip=skip, relu=1,
                             b_next_pre=self.sc(b_next), y=y, u_next=u_next, mask=u.mask, t_wide=u.t)
-        self._call("conv_fwd", u.name, self._conv_work(u), c.conv_fwd, u.desc, u.u, u.w, ep=ep, ws=self.ws)
+        self._call("conv_fwd", u.name, self._conv_work(u), c.conv_fwd, u.desc, u.u, u.w, ep=ep, ws=ws, stream=st)
         if self.tracing:
             self._rec(u.name + ".u", u.u)
             if u.t is not None:
@@ -357,13 +357,22 @@ class FixupNet:
         for bi, b in enumerate(self.blocks):
             nxt = self.blocks[bi + 1] if bi + 1 < len(self.blocks) else None
             if b.ds:
-                self._unit_fwd(b.ds)
+                # the shortcut convolution only meets the branch at the block's last layer: it runs beside the
+                # branch on the side stream (it is bound by its wide stores, the branch's first layers are not)
+                if self.overlap:
+                    b.ds.ev_e3.record(self.main)
+                    self.side.wait_event(b.ds.ev_e3)
+                self._unit_fwd(b.ds, side=self.overlap)
+                if self.overlap:
+                    b.ds.ev_dx.record(self.side)
             for i, u in enumerate(b.units):
                 last = i == len(b.units) - 1
                 if not last:
                     n_u = b.units[i + 1]
                     self._unit_fwd(u, u_next=n_u.u, b_next=n_u.b_pre, y=self._dbg_y(u))
                 else:
+                    if b.ds and self.overlap:
+                        self.main.wait_event(b.ds.ev_dx)
                     skip = b.ds.t if b.ds else b.a_in
                     if nxt is not None:
                         self._unit_fwd(u, skip=skip, y=nxt.a_in if nxt.a_in is not None else self._dbg_y(u),
