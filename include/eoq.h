@@ -188,7 +188,8 @@ int eoq_relu_bwd(eoq_ctx *ctx, const int8_t *e0, const uint32_t *mask_bits, cons
 /* Same as eoq_relu_bwd with t_wide = R(conv(u, w) / 128) recomputed on the fly instead of read from
  * memory (the wide Q_a1 output of a multiplier layer then never has to be stored by the forward pass):
  * one more evaluation of the forward convolution (desc, u, w as in eoq_conv_fwd, C % 16 == 0) whose
- * epilogue does the masking and the three reductions.  e1 may alias e0. */
+ * epilogue does the masking and the three reductions.  e1 may alias e0; e1 may be NULL when only the sums
+ * are wanted (e0 then already is e1 and mask_bits is NULL: the multiplier's gradient, off the critical path). */
 int eoq_relu_bwd_recompute(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *u, const int8_t *w,
                            const int8_t *e0, const uint32_t *mask_bits, int8_t *e1, int64_t *sum_e1,
                            int64_t *sum_e1t, int32_t *absmax_e1);
@@ -208,7 +209,10 @@ int eoq_merge_absmax(eoq_ctx *ctx, const int8_t *a, const int32_t *exp_a, const 
  * For the SQ modes, with M = *absmax: r = R(log2 M) (integer test, no tie possible),
  * out = clamp(R(v * 2^(7-r)), -127, 127), *exp_out = E + r - 7; M = 0 gives zeros and *exp_out = E.
  * Optional extras: *sum_out += sum of the output codes (bias gradient of Eq.4);
- * *max_code_out = max|out| (lets eoq_update_int8 skip its own abs-max pass). */
+ * *max_code_out = max|out| (lets eoq_update_int8 skip its own abs-max pass).
+ * EOQ_RQ_SQ_MERGE can apply, in the same pass, the ReLU backward step of the layer that receives the merged
+ * error (Eq.3 line e1): with mask_bits (that layer's forward mask) the output is the code where the bit is set
+ * and 0 elsewhere, sum_out sums these masked codes, and *absmax_out max= max|out| (for Q_e of e1 * gamma). */
 enum eoq_rq_mode { EOQ_RQ_FWD = 0, EOQ_RQ_SQ_ACC = 1, EOQ_RQ_SQ_GAMMA = 2, EOQ_RQ_SQ_MERGE = 3 };
 typedef struct eoq_requant_args {
     int32_t mode;
@@ -227,6 +231,8 @@ typedef struct eoq_requant_args {
     int32_t *exp_out;
     int64_t *sum_out;          /* may be NULL */
     int32_t *max_code_out;     /* may be NULL */
+    const uint32_t *mask_bits; /* SQ_MERGE only, may be NULL: see above (n % 16 == 0) */
+    int32_t *absmax_out;       /* SQ_MERGE only, may be NULL */
 } eoq_requant_args;
 int eoq_requant_epilogue(eoq_ctx *ctx, const eoq_requant_args *args);
 

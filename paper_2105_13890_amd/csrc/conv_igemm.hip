@@ -573,7 +573,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
                     }
                     sq_sum += ls;
                     rb_st += lst;
-                    *(v4i *)(p.rb_e1 + off) = o;
+                    if (p.rb_e1) *(v4i *)(p.rb_e1 + off) = o;
                 } else if (EPI == EPI_D16) {
                     const int smask = (1 << d16_s) - 1;
                     uint32_t w8[8];
@@ -1094,7 +1094,7 @@ extern "C" int eoq_relu_bwd_recompute(eoq_ctx *c, const eoq_conv_desc *d, const 
                                       const int8_t *e0, const uint32_t *mask_bits, int8_t *e1, int64_t *sum_e1,
                                       int64_t *sum_e1t, int32_t *absmax_e1)
 {
-    if (!c || !u || !w || !e0 || !e1) return EOQ_ERR_ARG;
+    if (!c || !u || !w || !e0 || (!e1 && !sum_e1 && !sum_e1t && !absmax_e1)) return EOQ_ERR_ARG;
     if (!desc_ok(d)) return EOQ_ERR_SHAPE;
     if (d->K % 16 || d->C % 16 || d->R * d->S > 64) return EOQ_ERR_SHAPE;
     if (((uintptr_t)u | (uintptr_t)w | (uintptr_t)e0 | (uintptr_t)e1) & 15 || ((uintptr_t)mask_bits & 3)) return EOQ_ERR_ARG;

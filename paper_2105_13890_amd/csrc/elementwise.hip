@@ -210,6 +210,8 @@ struct SqArgs {
     int64_t *sum_out;
     int32_t *max_code_out;
     uint32_t *status;
+    const uint16_t *mask16;      // SQ_MERGE: ReLU mask applied to the output (16 bits per 16 elements)
+    int32_t *absmax_out;         // SQ_MERGE with mask: max|out|
 };
 
 template <int MODE>
@@ -237,6 +239,7 @@ __global__ void sq_pass_kernel(SqArgs p)
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     int64_t s = 0;
+    int mxo = 0;
     for (; i < nv; i += stride) {
         v4i o = {0, 0, 0, 0};
         int ls = 0;
@@ -260,11 +263,15 @@ __global__ void sq_pass_kernel(SqArgs p)
             }
         } else {
             v4i a = ((const v4i *)p.src_a)[i], b = ((const v4i *)p.src_b)[i];
+            const uint32_t mk = p.mask16 ? (uint32_t)p.mask16[i] : 0xffffu;
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
                 int c = sq_code((int64_t)((byte_at(a, k) << sa) + (byte_at(b, k) << sb)), r);
+                c = ((mk >> k) & 1u) ? c : 0;
                 set_byte(o, k, c);
                 ls += c;
+                const int ac = c < 0 ? -c : c;
+                mxo = ac > mxo ? ac : mxo;
             }
         }
         s += ls;
@@ -281,6 +288,7 @@ __global__ void sq_pass_kernel(SqArgs p)
         s += c;
     }
     if (p.sum_out) block_atomic_add_i64(s, p.sum_out);
+    if (MODE == EOQ_RQ_SQ_MERGE && p.absmax_out) block_atomic_max_i32(mxo, p.absmax_out);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -467,6 +475,16 @@ extern "C" int eoq_requant_epilogue(eoq_ctx *c, const eoq_requant_args *a)
     p.acc = a->acc; p.src_a = a->src_a; p.src_b = a->src_b; p.exp_b = a->exp_b; p.gamma = a->gamma;
     p.absmax = a->absmax; p.exp_in = a->exp_in; p.exp_in_off = a->exp_in_off; p.n = a->n; p.out = a->out;
     p.exp_out = a->exp_out; p.sum_out = a->sum_out; p.max_code_out = a->max_code_out; p.status = c->d_status;
+    p.mask16 = nullptr; p.absmax_out = nullptr;
+    if (a->mode == EOQ_RQ_SQ_MERGE) {
+        // the mask is addressed in 16-element words: a ragged tail would need its own path
+        if ((a->mask_bits || a->absmax_out) && (a->n & 15)) return EOQ_ERR_SHAPE;
+        if ((uintptr_t)a->mask_bits & 3) return EOQ_ERR_ARG;
+        p.mask16 = (const uint16_t *)a->mask_bits;
+        p.absmax_out = a->absmax_out;
+    } else if (a->mask_bits || a->absmax_out) {
+        return EOQ_ERR_ARG;
+    }
     const dim3 grid(ew_blocks(a->n / 16)), block(EW_THREADS);
     switch (a->mode) {
     case EOQ_RQ_SQ_ACC:

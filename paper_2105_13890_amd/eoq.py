@@ -54,7 +54,8 @@ class RequantArgs(C.Structure):
     _fields_ = [("mode", C.c_int32), ("K", C.c_int32), ("n", C.c_size_t), ("acc", C.c_void_p), ("ep", C.c_void_p),
                 ("src_a", C.c_void_p), ("src_b", C.c_void_p), ("exp_b", C.c_void_p), ("gamma", C.c_void_p),
                 ("absmax", C.c_void_p), ("exp_in", C.c_void_p), ("exp_in_off", C.c_int32), ("out", C.c_void_p),
-                ("exp_out", C.c_void_p), ("sum_out", C.c_void_p), ("max_code_out", C.c_void_p)]
+                ("exp_out", C.c_void_p), ("sum_out", C.c_void_p), ("max_code_out", C.c_void_p),
+                ("mask_bits", C.c_void_p), ("absmax_out", C.c_void_p)]
 
 
 class ScalarGrad(C.Structure):
@@ -210,10 +211,10 @@ class Context:
 
     def requant_epilogue(self, mode, n, *, K=0, acc=None, ep=None, src_a=None, src_b=None, exp_b=None, gamma=None,
                          absmax=None, exp_in=None, exp_in_off=0, out=None, exp_out=None, sum_out=None,
-                         max_code_out=None):
+                         max_code_out=None, mask=None, absmax_out=None):
         a = RequantArgs(mode, K, n, _ptr(acc), C.addressof(ep) if ep is not None else None, _ptr(src_a), _ptr(src_b),
                         _ptr(exp_b), _ptr(gamma), _ptr(absmax), _ptr(exp_in), exp_in_off, _ptr(out), _ptr(exp_out),
-                        _ptr(sum_out), _ptr(max_code_out))
+                        _ptr(sum_out), _ptr(max_code_out), _ptr(mask), _ptr(absmax_out))
         _check(_lib.eoq_requant_epilogue(self._h, C.byref(a)), "eoq_requant_epilogue")
 
     def update_int8(self, w, g, g_exp_slot, g_max_code, lr_slot):

@@ -202,7 +202,7 @@ class FixupNet:
         self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=self.dev)
         self.ws_w = torch.empty((ws_bytes,), dtype=torch.uint8, device=self.dev)     # the side stream's own scratch
         for u in all_units:
-            u.ev_e3, u.ev_dx, u.ev_done = (torch.cuda.Event() for _ in range(3))
+            u.ev_e3, u.ev_dx, u.ev_done, u.ev_g, u.ev_gdone = (torch.cuda.Event() for _ in range(5))
         # ---- slots -------------------------------------------------------------------------------
         self.sl = _Slots()
         self._plan_slots()
@@ -431,6 +431,21 @@ class FixupNet:
             self._rec(u.name + ".gw", g.view(u.w.shape))
         return g
 
+    def _gamma_sum(self, u: Unit, e1):
+        """Sum of e1 * x2 for the multiplier's gradient (Eq.4), with x2 recomputed from (u, w) instead of having
+        been stored by the forward pass.  Nothing on the error chain waits for it -- only the scalar update at the
+        end of the step does -- so the convolution runs on the side stream."""
+        n_out = int(np.prod(u.out_shape))
+        c, st = (self.ctx_w, self.side) if self.overlap else (self.ctx, self.main)
+        if self.overlap:
+            u.ev_g.record(self.main)
+            self.side.wait_event(u.ev_g)
+        self._call("relu_bwd_recompute", u.name, self._conv_work(u), c.relu_bwd_recompute, u.desc, u.u, u.w,
+                   e1[:n_out], None, None, None, self.s64(u.name + ".S_e1t"), None, stream=st)
+        if self.overlap:
+            u.ev_gdone.record(self.side)
+            self._pending[e1.data_ptr()] = u.ev_gdone
+
     def _unit_bwd(self, u: Unit, e0, bufs, need_dx=True, relu_done=False, fuse_below: Unit | None = None,
                   merge=None):
         """Eq.3 / Eq.4 for one layer; e0 is overwritten by e1.  Returns (buffer with the error for the layer
@@ -442,15 +457,11 @@ class FixupNet:
         c = self.ctx
         n_out = int(np.prod(u.out_shape))
         e1 = e0
-        if relu_done:
-            pass
-        elif u.relu and u.gamma:
-            self._call("relu_bwd_recompute", u.name, self._conv_work(u), c.relu_bwd_recompute, u.desc, u.u, u.w,
-                       e0[:n_out], u.mask, e1[:n_out], self.s64(u.name + ".S_e1"), self.s64(u.name + ".S_e1t"),
-                       self.s32(u.name + ".M_e1"))
-        elif u.relu:
+        if u.relu and not relu_done:
             c.relu_bwd(e0[:n_out], u.mask, None, e1[:n_out], self.s64(u.name + ".S_e1"), None,
                        self.s32(u.name + ".M_e1"))
+        if u.relu and u.gamma:
+            self._gamma_sum(u, e1)
         if u.gamma:
             e3 = self._acquire(bufs)
             c.requant_epilogue(eoq.RQ_SQ_GAMMA, n_out, src_a=e1[:n_out], gamma=self.sc(u.gamma),
@@ -506,12 +517,15 @@ class FixupNet:
     def _backward_blocks(self, e, bufs):
         """e: buffer holding the error at the last block's output (exponent slot self.E_top)."""
         c = self.ctx
-        for b in reversed(self.blocks):
+        masked = False                     # the error handed down already went through the receiving layer's ReLU
+        for bi in range(len(self.blocks) - 1, -1, -1):
+            b = self.blocks[bi]
             assert len(b.units) >= 2
             last = b.units[-1]
             # e now holds e1 of the last layer = shortcut error; its backward-data call already applies the ReLU
             # backward step of the layer below it, and so on down the branch
-            e4, e_sk = self._unit_bwd(last, e, bufs, fuse_below=b.units[-2] if len(b.units) > 1 else None)
+            e4, e_sk = self._unit_bwd(last, e, bufs, relu_done=masked,
+                                      fuse_below=b.units[-2] if len(b.units) > 1 else None)
             E_sk = last.E0
             cur = e4
             M_in = b.name + ".M_in"
@@ -530,9 +544,16 @@ class FixupNet:
             else:
                 other, E_other = e_sk, E_sk
             out = cur
+            # Q_e of the merged error; when a block lies below, the same pass applies the ReLU backward step of
+            # that block's last layer (its mask, its bias-gradient sum, the abs-max for Q_e(e1 * gamma))
+            low = self.blocks[bi - 1].units[-1] if bi > 0 and not self.tracing else None
+            extra = {}
+            if low is not None:
+                extra = dict(mask=low.mask, sum_out=self.s64(low.name + ".S_e1"), absmax_out=self.s32(low.name + ".M_e1"))
             c.requant_epilogue(eoq.RQ_SQ_MERGE, n_in, src_a=cur[:n_in], src_b=other[:n_in], exp_in=self.s32(first.E4),
                                exp_b=self.s32(E_other), absmax=self.s32(b.name + ".M_in"), out=out[:n_in],
-                               exp_out=self.s32(b.name + ".E_in"))
+                               exp_out=self.s32(b.name + ".E_in"), **extra)
+            masked = low is not None
             if b.ds:
                 bufs.append(e4d)
             bufs.append(e_sk)

@@ -164,6 +164,10 @@ def test_relu_bwd_recompute(ctx, d):
     assert np.array_equal(host(e1), e1o)
     assert int(host(sums)[0]) == int(e1o.astype(np.int64).sum())
     assert int(host(sums)[1]) == int((e1o.astype(np.int64) * t).sum())
+    # sums only: the input already is e1, nothing is stored
+    only = zeros((1,), torch.int64)
+    ctx.relu_bwd_recompute(desc_of(d), dev(u), dev(w), dev(e1o), None, None, None, only[0:1], None)
+    assert int(host(only)[0]) == int((e1o.astype(np.int64) * t).sum())
     assert int(host(slots)[0]) == int(np.abs(e1o.astype(np.int64)).max())
 
 
@@ -285,7 +289,7 @@ def test_relu_bwd_and_sq_passes(ctx, n):
                np.frombuffer(np.packbits(maskb, bitorder="little").tobytes() + b"\0\0", dtype=np.int32))
     e1 = zeros((n,), torch.int8)
     sums = zeros((4,), torch.int64)
-    slots = zeros((8,), torch.int32)
+    slots = zeros((10,), torch.int32)
     ctx.relu_bwd(dev(e0), mask, dev(t), e1, sums[0:1], sums[1:2], slots[0:1])
     e1o = (e0.astype(np.int64) * maskb).astype(np.int8)
     assert np.array_equal(host(e1), e1o)
@@ -320,6 +324,20 @@ def test_relu_bwd_and_sq_passes(ctx, n):
                              absmax=slots[6:7], out=out, exp_out=slots[7:8])
         em, Em = oo.merge_errors(ea, Ea, eb, Eb)
         assert np.array_equal(host(out), em) and int(host(slots)[7]) == Em
+        if n % 16 == 0:
+            # the same pass with the ReLU backward step of the receiving layer: masked codes, their sum, their abs-max
+            mb = (si.words(6, "mask2", n) & np.uint64(1)).astype(bool)
+            pk = np.packbits(mb, bitorder="little")
+            mk = dev(np.frombuffer(pk.tobytes() + b"\0" * (-len(pk) % 4), dtype=np.int32))
+            st = zeros((1,), torch.int64)
+            slots[8] = 0
+            ctx.requant_epilogue(eoq.RQ_SQ_MERGE, n, src_a=dev(ea), src_b=dev(eb), exp_in=ex[0:1], exp_b=ex[1:2],
+                                 absmax=slots[6:7], out=out, exp_out=slots[7:8], mask=mk, sum_out=st,
+                                 absmax_out=slots[8:9])
+            e1m = (em.astype(np.int64) * mb).astype(np.int8)
+            assert np.array_equal(host(out), e1m) and int(host(slots)[7]) == Em
+            assert int(host(st)[0]) == int(e1m.astype(np.int64).sum())
+            assert int(host(slots)[8]) == int(np.abs(e1m.astype(np.int64)).max())
     # all-zero tensors keep their exponent
     slots[3] = 0
     ctx.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=zeros((n,), torch.int32), absmax=slots[3:4], exp_in=slots[1:2],
