@@ -7,8 +7,10 @@
 // The reduction is walked in 16-byte pieces ("k-chunks": 16 consecutive input channels of one filter
 // tap), four per LDS stage.  One MFMA v_mfma_i32_32x32x32_i8 consumes two k-chunks: lanes 0-31 supply
 // the first, lanes 32-63 the second, identically for both operands, so any (tap, channel) order is
-// legal as long as A and B agree.  A workgroup is 4 waves; each wave owns a (BM/WGM) x (BN/WGN) block
-// of 32x32 MFMA tiles.  Global -> register -> LDS software pipeline with two LDS buffers, one
+// legal as long as A and B agree.  A workgroup is 4 or 8 waves (WGM x WGN); each wave owns a (BM/WGM) x (BN/WGN)
+// block of 32x32 MFMA tiles.  With 8 waves every SIMD hosts two of them, and the two run the phases of an
+// iteration in opposite order (one multiplies while the other moves data through LDS): four waves in lockstep
+// leave the matrix pipes idle while they all read LDS and the LDS idle while they all multiply.  Global -> register -> LDS software pipeline with two LDS buffers, one
 // barrier per stage; LDS rows are 64 bytes with the 16-byte chunk index XOR-swizzled by (row/4)%4 so
 // that both the 16-byte writes and the MFMA operand reads spread over all banks.
 //
@@ -179,15 +181,16 @@ __device__ __forceinline__ bool epilogue_fits32(const EpiDev &ep, int gamma, int
 }
 
 template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
-__global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
+__global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams p)
 {
-    static_assert(WGM * WGN == 4, "4 waves");
+    constexpr int NW = WGM * WGN, NT = NW * 64;
+    static_assert(NW == 4 || NW == 8, "4 or 8 waves");
     static_assert(BK == 64 || BK == 128, "stage depth in bytes");
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     static_assert(TM >= 1 && TN >= 1, "tile");
     constexpr int CH = BK / 16;                 // k-chunks per LDS row
-    constexpr int RPP = 256 / CH;               // rows loaded per pass of the 256 threads
+    constexpr int RPP = NT / CH;                // rows loaded per pass of the workgroup's threads
     constexpr int RP = 16 / CH;                 // rows per 256 bytes of LDS (swizzle period)
     constexpr int A_ROWS = (BM + RPP - 1) / RPP, B_ROWS = (BN + RPP - 1) / RPP;
     constexpr int STAGE_BYTES = (BM + BN) * BK;
@@ -411,19 +414,36 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
     // loads go first, so that their latency runs under this stage's MFMAs; the LDS writes sit between the two
     // halves of the MFMAs, so that a wave that has to wait for its global data has already queued matrix work
     // and the writes have landed by the time the last MFMA is issued and the barrier is reached.
+    // With 8 waves, the waves of the second half of the workgroup (the second wave of every SIMD) run an
+    // iteration in the opposite order -- all MFMAs first, then the data movement -- so that on every SIMD one wave
+    // multiplies while the other uses LDS and the memory pipeline.  Within an iteration the order is free: the
+    // MFMAs use fragments read one iteration ago, the LDS reads use the buffer written one iteration ago, and the
+    // LDS writes go to the buffer whose fragments every wave read before the last barrier.
+    const bool mfma_first = NW == 8 && wave >= NW / 2;                              // wave-uniform
     for (; st + D <= nstages; st += D) {           // full groups: straight-line code, one exit
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);        // stage st+d+1
-            __builtin_amdgcn_sched_barrier(0);
-            load_stage(ra[d], rb[d]);                                               // stage st+d+D
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_half(0, fa[d & 1], fb[d & 1]);                                     // stage st+d
-            __builtin_amdgcn_sched_barrier(0);
-            store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);                     // stage st+d+2
-            __builtin_amdgcn_sched_barrier(0);
+            if (mfma_first) {
 #pragma unroll
-            for (int j = 1; j < CH / 2; ++j) mfma_half(j, fa[d & 1], fb[d & 1]);
+                for (int j = 0; j < CH / 2; ++j) mfma_half(j, fa[d & 1], fb[d & 1]);    // stage st+d
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);        // stage st+d+1
+                __builtin_amdgcn_sched_barrier(0);
+                load_stage(ra[d], rb[d]);                                               // stage st+d+D
+                __builtin_amdgcn_sched_barrier(0);
+                store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);                     // stage st+d+2
+            } else {
+                read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);        // stage st+d+1
+                __builtin_amdgcn_sched_barrier(0);
+                load_stage(ra[d], rb[d]);                                               // stage st+d+D
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_half(0, fa[d & 1], fb[d & 1]);                                     // stage st+d
+                __builtin_amdgcn_sched_barrier(0);
+                store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);                     // stage st+d+2
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 1; j < CH / 2; ++j) mfma_half(j, fa[d & 1], fb[d & 1]);
+            }
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
             cur = STAGE_BYTES - cur;
@@ -474,7 +494,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
         __syncthreads();
         int tmax = red[0];
 #pragma unroll
-        for (int w = 1; w < 4; ++w) tmax = red[w] > tmax ? red[w] : tmax;
+        for (int w = 1; w < NW; ++w) tmax = red[w] > tmax ? red[w] : tmax;
         __syncthreads();                             // before the staging below overwrites red[]
         const int ploc = tmax ? 31 - __clz(tmax) : 0;
         d16_s = ploc > 13 ? ploc - 13 : 0;
@@ -610,7 +630,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(IgemmParams p)
             // thousands of workgroups adding to two slots would queue up behind each other: each wave stores its
             // own pair (no barrier, no shared memory), a one-block kernel adds them up afterwards
             const int64_t a = wave_sum_i64(sq_sum), b = wave_sum_i64(rb_st);
-            if (lane == 0) { p.rb_part[2 * (4 * bid + wave)] = a; p.rb_part[2 * (4 * bid + wave) + 1] = b; }
+            if (lane == 0) { p.rb_part[2 * (NW * bid + wave)] = a; p.rb_part[2 * (NW * bid + wave) + 1] = b; }
         } else {
             if (p.rb_sum_e1) block_atomic_add_i64(sq_sum, p.rb_sum_e1);
             if (p.rb_sum_e1t) block_atomic_add_i64(rb_st, p.rb_sum_e1t);
@@ -879,7 +899,8 @@ inline unsigned grid_for(size_t total)
 template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
 int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
 {
-    constexpr int main_bytes = 2 * (BM + BN) * BK, epi_bytes = 4 * 32 * (BN / WGN + 4) * 4;
+    constexpr int NW = WGM * WGN;
+    constexpr int main_bytes = 2 * (BM + BN) * BK, epi_bytes = NW * 32 * (BN / WGN + 4) * 4;
     constexpr int lds_bytes = main_bytes > epi_bytes ? main_bytes : epi_bytes;
     static bool attr_done = false;
     auto kern = igemm_kernel<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>;
@@ -889,7 +910,7 @@ int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
         attr_done = true;
     }
     const long tiles = (long)((p.M + BM - 1) / BM) * ((p.NOUT + BN - 1) / BN);
-    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(256), lds_bytes, c->stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(NW * 64), lds_bytes, c->stream, p);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }
@@ -917,9 +938,14 @@ int launch_igemm(eoq_ctx *c, const IgemmParams &p)
 }
 
 template <int MODE, int EPI>
-int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in, int *bm_out = nullptr, int *bn_out = nullptr)
+int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in, int *bm_out = nullptr, int *bn_out = nullptr,
+                   int *nw_out = nullptr)
 {
-    auto chosen = [&](int bm, int bn) { if (bm_out) *bm_out = bm; if (bn_out) *bn_out = bn; };
+    auto chosen = [&](int bm, int bn, int nw = 4) {
+        if (bm_out) *bm_out = bm;
+        if (bn_out) *bn_out = bn;
+        if (nw_out) *nw_out = nw;
+    };
     IgemmParams p = p_in;
     if (!p.xstep) p.xstep = p.C;
     p.gemm = (p.R == 1 && p.S == 1 && p.stride == 1 && p.pad == 0 && !p.no_pad && p.P == p.H && p.Q == p.W) ? 1 : 0;
@@ -928,10 +954,11 @@ int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in, int *bm_out = nullptr, i
     switch (forced_tile()) {
     case 128128064: chosen(128, 128); return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
     case 128128065: chosen(128, 128); return launch_igemm<128, 128, 4, 1, 64, MODE, EPI>(c, p);   // waves stacked in M
+    case 256128064: chosen(256, 128, 8); return launch_igemm<256, 128, 4, 2, 64, MODE, EPI>(c, p);   // 8 waves
+    case 128128068: chosen(128, 128, 8); return launch_igemm<128, 128, 2, 4, 64, MODE, EPI>(c, p);
+    case 128064068: chosen(128, 64, 8); return launch_igemm<128, 64, 4, 2, 64, MODE, EPI>(c, p);
     case 128064064: chosen(128, 64); return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
     case 128032064: chosen(128, 32); return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p);
-    case 64064064: chosen(64, 64); return launch_igemm<64, 64, 2, 2, 64, MODE, EPI>(c, p);
-    case 64128064: chosen(64, 128); return launch_igemm<64, 128, 2, 2, 64, MODE, EPI>(c, p);
     default: break;
     }
     // Measured on MI355X: throughput is nearly flat in the tile shape and in the prefetch depth (4, 6, 8 stages),
@@ -1115,13 +1142,13 @@ extern "C" int eoq_relu_bwd_recompute(eoq_ctx *c, const eoq_conv_desc *d, const 
     // every tile shape the dispatcher may choose is at least 64 x 32
     const long max_tiles = (long)((p.M + 63) / 64) * ((p.NOUT + 31) / 32);
     if ((sum_e1 || sum_e1t) && 8 * max_tiles <= EOQ_PARTIAL_SLOTS) p.rb_part = c->d_partials;
-    int bm = 0, bn = 0;
-    if (int rc = dispatch_igemm<MODE_FWD, EPI_RELU_BWD>(c, p, &bm, &bn)) return rc;
+    int bm = 0, bn = 0, nw = 4;
+    if (int rc = dispatch_igemm<MODE_FWD, EPI_RELU_BWD>(c, p, &bm, &bn, &nw)) return rc;
     if (p.rb_part) {
         const int tiles = ((p.M + bm - 1) / bm) * ((p.NOUT + bn - 1) / bn);
-        int rblocks = (4 * tiles + 1023) / 1024;
+        int rblocks = (nw * tiles + 1023) / 1024;
         if (rblocks > 32) rblocks = 32;
-        hipLaunchKernelGGL(pair_reduce_kernel, dim3(rblocks), dim3(1024), 0, c->stream, c->d_partials, 4 * tiles, sum_e1,
+        hipLaunchKernelGGL(pair_reduce_kernel, dim3(rblocks), dim3(1024), 0, c->stream, c->d_partials, nw * tiles, sum_e1,
                            sum_e1t);
         EOQ_LAUNCH_CHECK();
     }
@@ -1201,7 +1228,7 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
     if (int rc = dispatch_igemm<MODE_BWD_DATA, EPI_D16>(c, p, &bm, &bn)) return rc;
     D16Finish f{};
     f.d16 = d16; f.tile_shift = tile_shift;
-    f.bm_shift = bm == 64 ? 6 : 7;
+    f.bm_shift = bm == 64 ? 6 : (bm == 128 ? 7 : 8);
     f.bn_shift = bn == 32 ? 5 : (bn == 64 ? 6 : 7);
     f.tiles_n = (d->C + bn - 1) / bn;
     f.M = M; f.C = d->C;
