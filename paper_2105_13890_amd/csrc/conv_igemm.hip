@@ -388,6 +388,78 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams p)
                 acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[j][i], fb[j][jn], acc[i][jn], 0, 0, 0);
     };
 
+    const int nstages = (p.nk16 + CH - 1) / CH;
+    if constexpr (BK == 128) {
+        // 128-byte stages: every row of a stage is one full 128-byte cache line per global load instruction (8
+        // lanes per row).  With 64-byte stages and rows longer than 64 bytes each instruction takes half of
+        // 16 different lines and the other halves are fetched again one stage later -- measured on this chip,
+        // half-line gathers move 30 B/clk/CU out of L2 against 50 B/clk/CU for whole lines.
+        // A stage is 4 MFMA reduction steps; fragments are pipelined by HALF stages (two steps) so that their
+        // register cost stays that of the 64-byte kernel: P holds the first half of the stage about to be
+        // multiplied (read at the end of the previous iteration), Q its second half (read at the start of this
+        // one).  Global registers: a ring of two stages.  One barrier per stage:
+        //     read Q(st) | MFMA P | MFMA Q | barrier | read P(st+1) | LDS <- stage st+2 | request stage st+4
+        // Entering iteration st: LDS[cur] = stage st, LDS[other] = st+1, ring[st & 1] = st+2, ring[~st & 1] = st+3.
+        // After the barrier every wave has read both halves of stage st, so its buffer takes stage st+2; stage
+        // st+1 was written before the previous barrier.  All steps are unconditional (see the 64-byte loop).
+        constexpr int HJ = CH / 4;                   // MFMA reduction steps per half stage
+        static_assert(HJ == 2, "two steps per half stage");
+        v4i ra2[2][A_ROWS], rb2[2][B_ROWS];
+        v4i pa[HJ][TM], pb[HJ][TN], qa[HJ][TM], qb[HJ][TN];
+        auto read_half = [&](int buf, int h, v4i (&fa)[HJ][TM], v4i (&fb)[HJ][TN]) {
+            const int8_t *base = lds + buf;
+#pragma unroll
+            for (int j = 0; j < HJ; ++j) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fa[j][i] = *(const v4i *)(base + rd_a[h * HJ + j] + i * 32 * BK);
+#pragma unroll
+                for (int i = 0; i < TN; ++i) fb[j][i] = *(const v4i *)(base + rd_b[h * HJ + j] + i * 32 * BK);
+            }
+        };
+        auto mfma2 = [&](const v4i (&fa)[HJ][TM], const v4i (&fb)[HJ][TN]) {
+#pragma unroll
+            for (int j = 0; j < HJ; ++j)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int jn = 0; jn < TN; ++jn)
+                        acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[j][i], fb[j][jn], acc[i][jn], 0, 0, 0);
+        };
+        load_stage(ra2[0], rb2[0]);                                  // stage 0
+        load_stage(ra2[1], rb2[1]);                                  // stage 1
+        store_stage(0, ra2[0], rb2[0]);
+        load_stage(ra2[0], rb2[0]);                                  // stage 2
+        store_stage(STAGE_BYTES, ra2[1], rb2[1]);
+        load_stage(ra2[1], rb2[1]);                                  // stage 3
+        __syncthreads();
+        read_half(0, 0, pa, pb);
+        int cur = 0, st = 0;
+        for (; st + 2 <= nstages; st += 2) {
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {
+                read_half(cur, 1, qa, qb);                           // second half of stage st+d
+                __builtin_amdgcn_sched_barrier(0);
+                mfma2(pa, pb);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma2(qa, qb);
+                __builtin_amdgcn_sched_barrier(0);
+                __syncthreads();
+                read_half(STAGE_BYTES - cur, 0, pa, pb);             // first half of stage st+d+1
+                __builtin_amdgcn_sched_barrier(0);
+                store_stage(cur, ra2[d], rb2[d]);                    // stage st+d+2
+                __builtin_amdgcn_sched_barrier(0);
+                load_stage(ra2[d], rb2[d]);                          // stage st+d+4
+                __builtin_amdgcn_sched_barrier(0);
+                cur = STAGE_BYTES - cur;
+            }
+        }
+        if (st < nstages) {                                          // odd number of stages: the last one
+            read_half(cur, 1, qa, qb);
+            mfma2(pa, pb);
+            mfma2(qa, qb);
+        }
+        __syncthreads();
+    } else {
     // Software pipeline over the reduction, unrolled D (= 4) times so that the register rings are indexed
     // statically.  Entering iteration st: fragments of stage st are in registers, LDS buffer (st+1)%2 holds
     // stage st+1, global registers hold stages st+2 .. st+D-1.  The iteration reads the fragments of st+1,
@@ -398,7 +470,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams p)
     // The number of loads in flight at each wait is therefore a compile-time constant, and the compiler can
     // wait for exactly the oldest stage (a conditional load anywhere in the loop would force it to wait for
     // everything, i.e. to expose the full memory latency in every iteration).
-    const int nstages = (p.nk16 + CH - 1) / CH;
     v4i ra[D][A_ROWS], rb[D][B_ROWS];
     v4i fa[2][CH / 2][TM], fb[2][CH / 2][TN];
 #pragma unroll
@@ -467,6 +538,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams p)
         }
     }
     __syncthreads();
+
+    }
 
     // ---- epilogue ----
     // Block-scaled 16-bit output (the scale quantiser of Eq.11 needs max|d| of the WHOLE tensor before any element
@@ -954,6 +1027,8 @@ int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in, int *bm_out = nullptr, i
     switch (forced_tile()) {
     case 128128064: chosen(128, 128); return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
     case 128128065: chosen(128, 128); return launch_igemm<128, 128, 4, 1, 64, MODE, EPI>(c, p);   // waves stacked in M
+    case 128128128: if (p.c16 % 8 == 0) { chosen(128, 128); return launch_igemm_u<128, 128, 2, 2, 128, 4, true, MODE, EPI>(c, p); } break;
+    case 128064128: if (p.c16 % 8 == 0) { chosen(128, 64); return launch_igemm_u<128, 64, 2, 2, 128, 4, true, MODE, EPI>(c, p); } break;
     case 256128064: chosen(256, 128, 8); return launch_igemm<256, 128, 4, 2, 64, MODE, EPI>(c, p);   // 8 waves
     case 128128068: chosen(128, 128, 8); return launch_igemm<128, 128, 2, 4, 64, MODE, EPI>(c, p);
     case 128064068: chosen(128, 64, 8); return launch_igemm<128, 64, 4, 2, 64, MODE, EPI>(c, p);
