@@ -32,6 +32,14 @@ struct EpiDev {
     int32_t *t_wide;
 };
 
+// One parity class of a stride-2 backward-data gather (up to four per launch): its own output grid, taps, filters
+struct IgemmCls {
+    int P, Q, R, S, pad, pad_w_delta, M, nk16;
+    int rm_Hc, rm_Wc, rm_h0, rm_w0;
+    int tile_base;                 // first workgroup tile of the class (= its first tile_shift entry)
+    int b_off;                     // byte offset of the class's packed filters
+};
+
 struct IgemmParams {
     const int8_t *A;   // input N x H x W x C
     const int8_t *B;   // filters NOUT x (R*S*C)
@@ -46,9 +54,16 @@ struct IgemmParams {
     int32_t *absmax;
     uint32_t *status;  // device status word of the context
     EpiDev ep;
+    int pad_w_delta;   // column padding minus row padding (0 except for the parity classes of a stride-2 gather)
+    int ncls;          // > 0: the launch covers ncls independent problems that differ in the fields of IgemmCls
+    IgemmCls cls[4];
     // EPI_D16: 16-bit block-scaled output of the backward-data convolution (one shift per workgroup tile)
     int16_t *d16;
     int32_t *tile_shift;
+    int ts_base;       // first entry of this launch in tile_shift
+    // EPI_D16 row remap (parity classes): GEMM row (n, gh, gw) of a rm_Hc x rm_Wc grid is input pixel
+    // (n, 2*gh + rm_h0, 2*gw + rm_w0) of the rm_H x rm_W image
+    int rm_on, rm_Hc, rm_Wc, rm_H, rm_W, rm_h0, rm_w0;
     // EPI_RELU_BWD: ReLU backward with the Q_a1 output recomputed instead of read back
     const int8_t *rb_e0;
     const uint16_t *rb_mask16;
@@ -181,8 +196,9 @@ __device__ __forceinline__ bool epilogue_fits32(const EpiDev &ep, int gamma, int
 }
 
 template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
-__global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams p)
+__global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
 {
+    IgemmParams p = pin;           // uniform; patched below when the launch covers several classes
     constexpr int NW = WGM * WGN, NT = NW * 64;
     static_assert(NW == 4 || NW == 8, "4 or 8 waves");
     static_assert(BK == 64 || BK == 128, "stage depth in bytes");
@@ -208,6 +224,18 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams p)
     {
         const int nb = gridDim.x, per = nb / 8;
         if (bid < per * 8) bid = (bid % 8) * per + bid / 8;
+    }
+    if (EPI == EPI_D16 && p.ncls) {
+        int cl = 0;
+#pragma unroll
+        for (int i = 1; i < 4; ++i)
+            if (i < p.ncls && bid >= p.cls[i].tile_base) cl = i;
+        const IgemmCls &q = pin.cls[cl];
+        p.P = q.P; p.Q = q.Q; p.R = q.R; p.S = q.S; p.pad = q.pad; p.pad_w_delta = q.pad_w_delta; p.M = q.M;
+        p.nk16 = q.nk16; p.rm_Hc = q.rm_Hc; p.rm_Wc = q.rm_Wc; p.rm_h0 = q.rm_h0; p.rm_w0 = q.rm_w0;
+        p.B = pin.B + q.b_off;
+        p.ts_base = q.tile_base;
+        bid -= q.tile_base;
     }
     const int tile_m = bid / tiles_n, tile_n = bid % tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -251,7 +279,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams p)
                 for (int ss = 0; ss < p.S; ++ss, ++tap)
                     if ((unsigned)(hb + rr) < (unsigned)p.H && (unsigned)(wb + ss) < (unsigned)p.W) mask |= 1ull << tap;
         } else {
-            const int hp = ho + p.pad, wp = wo + p.pad;
+            const int hp = ho + p.pad, wp = wo + p.pad + p.pad_w_delta;
             hb = hp / p.stride; wb = wp / p.stride;
             const int hm = hp - hb * p.stride, wm_ = wp - wb * p.stride;
             int tap = 0;
@@ -573,7 +601,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams p)
         d16_s = ploc > 13 ? ploc - 13 : 0;
         if (tid == 0) {
             slot_atomic_max_i32(p.absmax, tmax);
-            p.tile_shift[bid] = d16_s;
+            p.tile_shift[p.ts_base + bid] = d16_s;
         }
     }
     // per wave, 32 rows at a time through LDS
@@ -641,7 +669,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams p)
                 v[4 * k4] = w[0]; v[4 * k4 + 1] = w[1]; v[4 * k4 + 2] = w[2]; v[4 * k4 + 3] = w[3];
             }
             if (m < p.M && ch < p.NOUT) {
-                const size_t off = (size_t)m * p.NOUT + ch;
+                size_t off = (size_t)m * p.NOUT + ch;
+                if (EPI == EPI_D16 && p.rm_on) {
+                    const int hw = p.rm_Hc * p.rm_Wc;
+                    const int n = m / hw, r = m - n * hw;
+                    const int gh = r / p.rm_Wc, gw = r - gh * p.rm_Wc;
+                    off = ((size_t)(n * p.rm_H + 2 * gh + p.rm_h0) * p.rm_W + 2 * gw + p.rm_w0) * p.NOUT + ch;
+                }
                 if (EPI == EPI_FWD) {
                     if (fast) epilogue16<true>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad, pre8[i][ps]);
                     else epilogue16<false>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad, pre8[i][ps]);
@@ -725,6 +759,25 @@ __global__ void transpose_filters_kernel(const int8_t *w, int K, int RS, int C, 
         size_t t = i / K;
         int rs = (int)(t % RS), c = (int)(t / RS);
         wt[i] = w[((size_t)k * RS + rs) * C + c];
+    }
+}
+
+// Filters of the four parity classes of a stride-2 backward-data gather: class (a, b) takes the taps r = a, a+2, ..
+// and s = b, b+2, .. of the K x R x S x C filters, stored as C x Ra x Sa x K (the operand order of the gather) at
+// byte offset base[2a+b].
+struct ClsPack { int base[4], Ra[2], Sa[2]; };
+__global__ void pack_class_filters_kernel(const int8_t *w, int K, int R, int S, int C, ClsPack cp, int8_t *wc)
+{
+    const size_t total = (size_t)K * R * S * C;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int k = (int)(i % K);             // walk the OUTPUT order of the largest class so that writes coalesce
+        size_t t = i / K;
+        const int s = (int)(t % S); t /= S;
+        const int r = (int)(t % R);
+        const int c = (int)(t / R);
+        const int a = r & 1, b = s & 1, r2 = r >> 1, s2 = s >> 1;
+        wc[cp.base[2 * a + b] + (((size_t)c * cp.Ra[a] + r2) * cp.Sa[b] + s2) * K + k] =
+            w[(((size_t)k * R + r) * S + s) * C + c];
     }
 }
 
@@ -860,6 +913,11 @@ struct D16Finish {
     // strided 1x1 filter: the sums exist only for the input pixels the filter touched (every sub-th row and column),
     // stored compactly as N x P x Q rows; all other input pixels receive no error
     int sub, H, W, P, Q;
+    // stride-2 filters larger than 1x1: four launches, one per parity class (a, b) of (h + pad, w + pad); the sums sit
+    // at their final positions, only the tile of an element (for its shift) depends on the class
+    int cls_on, cls_pad;
+    int cls_hh0[2], cls_ww0[2], cls_Hc[2], cls_Wc[2];
+    int cls_base[4], cls_bm_shift[4], cls_bn_shift[4], cls_tiles_n[4];
 };
 
 template <bool RELU>
@@ -900,7 +958,18 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
         }
         int s = 0;
         v4i lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
-        if (have) {
+        if (p.cls_on) {
+            const uint32_t hw = (uint32_t)(p.H * p.W);
+            const uint32_t n = m / hw, rem = m - n * hw;
+            const uint32_t h = rem / (uint32_t)p.W, x = rem - h * (uint32_t)p.W;
+            const int a = (int)((h + p.cls_pad) & 1u), b = (int)((x + p.cls_pad) & 1u), cl = a * 2 + b;
+            const int gh = (int)((h + p.cls_pad - a) >> 1) - p.cls_hh0[a], gw = (int)((x + p.cls_pad - b) >> 1) - p.cls_ww0[b];
+            const uint32_t mc = (n * p.cls_Hc[a] + gh) * p.cls_Wc[b] + gw;
+            s = p.tile_shift[p.cls_base[cl] + (mc >> p.cls_bm_shift[cl]) * p.cls_tiles_n[cl] + (c >> p.cls_bn_shift[cl])];
+            const size_t src = (size_t)m * p.C + c;
+            lo = ((const v4i *)(p.d16 + src))[0];
+            hi = ((const v4i *)(p.d16 + src))[1];
+        } else if (have) {
             s = p.tile_shift[(mrow >> p.bm_shift) * p.tiles_n + (c >> p.bn_shift)];
             const size_t src = (size_t)mrow * p.C + c;
             lo = ((const v4i *)(p.d16 + src))[0];
@@ -982,7 +1051,18 @@ int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
             return EOQ_ERR_HIP;
         attr_done = true;
     }
-    const long tiles = (long)((p.M + BM - 1) / BM) * ((p.NOUT + BN - 1) / BN);
+    long tiles = (long)((p.M + BM - 1) / BM) * ((p.NOUT + BN - 1) / BN);
+    if (p.ncls) {
+        IgemmParams q = p;
+        tiles = 0;
+        for (int i = 0; i < p.ncls; ++i) {
+            q.cls[i].tile_base = (int)tiles;
+            tiles += (long)((p.cls[i].M + BM - 1) / BM) * ((p.NOUT + BN - 1) / BN);
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(NW * 64), lds_bytes, c->stream, q);
+        EOQ_LAUNCH_CHECK();
+        return EOQ_OK;
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(NW * 64), lds_bytes, c->stream, p);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
@@ -1021,7 +1101,9 @@ int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in, int *bm_out = nullptr, i
     };
     IgemmParams p = p_in;
     if (!p.xstep) p.xstep = p.C;
-    p.gemm = (p.R == 1 && p.S == 1 && p.stride == 1 && p.pad == 0 && !p.no_pad && p.P == p.H && p.Q == p.W) ? 1 : 0;
+    p.gemm = (p.R == 1 && p.S == 1 && p.stride == 1 && p.pad == 0 && p.pad_w_delta == 0 && !p.no_pad && p.P == p.H &&
+              p.Q == p.W) ? 1 : 0;
+    if (p.ncls) p.gemm = 0;            // the classes differ in their grids and taps
     const int nout = p.NOUT;
     auto wgs = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((nout + bn - 1) / bn); };
     switch (forced_tile()) {
@@ -1277,7 +1359,8 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
     if ((uintptr_t)wt & 15) return EOQ_ERR_ARG;
     int16_t *d16 = (int16_t *)((int8_t *)ws + round_up((size_t)d->K * d->R * d->S * d->C, 256));
     int32_t *tile_shift = (int32_t *)((int8_t *)d16 + round_up(2 * M * d->C, 256));
-    if (!wt) {
+    const bool cls = d->stride == 2 && d->R >= 2 && d->S >= 2;      // see below
+    if (!wt && !cls) {
         hipLaunchKernelGGL(transpose_filters_kernel, dim3(grid_for((size_t)d->K * d->R * d->S * d->C)), dim3(256), 0,
                            c->stream, w, d->K, d->R * d->S, d->C, (int8_t *)ws);
         EOQ_LAUNCH_CHECK();
@@ -1295,13 +1378,71 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
         dsub.W = conv_out_dim(d->W, 0, 1, d->stride);
         dsub.stride = 1;
     }
+    // Stride 2 with a filter larger than 1x1: an input pixel only sees the taps whose parity matches its own, a
+    // quarter of them on average.  The four parity classes (a, b) of (h + pad, w + pad) are four stride-1 gathers over
+    // the error, each with its own taps (r = a, a+2, ..; s = b, b+2, ..) packed as a small filter -- no multiply-add
+    // is spent on a structural zero.
+    D16Finish f{};
+    int bm = 0, bn = 0;
+    if (cls) {
+        const int P = conv_out_dim(d->H, d->pad, d->R, 2), Q = conv_out_dim(d->W, d->pad, d->S, 2);
+        if ((size_t)d->N * d->H * d->W > 0x7fffffffu || (size_t)d->N * P * Q * d->K > 0x7fffffffu) return EOQ_ERR_SHAPE;
+        int8_t *wc = (int8_t *)ws;                     // the four packed filters share the transposed-filter region
+        f.cls_on = 1; f.cls_pad = d->pad; f.H = d->H; f.W = d->W;
+        ClsPack cp{};
+        for (int a = 0; a < 2; ++a) {
+            f.cls_hh0[a] = f.cls_ww0[a] = d->pad > a ? (d->pad - a + 1) >> 1 : 0;
+            const int first = 2 * f.cls_hh0[a] + a - d->pad;           // first row / column of this parity
+            f.cls_Hc[a] = first < d->H ? (d->H - 1 - first) / 2 + 1 : 0;
+            f.cls_Wc[a] = first < d->W ? (d->W - 1 - first) / 2 + 1 : 0;
+            cp.Ra[a] = (d->R - a + 1) / 2;
+            cp.Sa[a] = (d->S - a + 1) / 2;
+        }
+        p.A = e; p.B = wc;
+        p.N = d->N; p.H = P; p.W = Q; p.C = d->K; p.NOUT = d->C;
+        p.stride = 1; p.c16 = p.C / 16; p.xstep = p.C;
+        p.absmax = absmax_slot; p.d16 = d16; p.tile_shift = tile_shift; p.rm_on = 1; p.rm_H = d->H; p.rm_W = d->W;
+        int cls_of[4] = {0, 0, 0, 0}, off = 0;
+        for (int a = 0; a < 2; ++a)
+            for (int b = 0; b < 2; ++b) {
+                cp.base[2 * a + b] = off;
+                const int Hc = f.cls_Hc[a], Wc = f.cls_Wc[b];
+                if (Hc && Wc) {
+                    IgemmCls &q = p.cls[p.ncls];
+                    q.P = Hc; q.Q = Wc; q.R = cp.Ra[a]; q.S = cp.Sa[b];
+                    q.pad = f.cls_hh0[a]; q.pad_w_delta = f.cls_ww0[b] - f.cls_hh0[a];
+                    q.M = d->N * Hc * Wc; q.nk16 = q.R * q.S * p.c16;
+                    q.rm_Hc = Hc; q.rm_Wc = Wc;
+                    q.rm_h0 = 2 * f.cls_hh0[a] + a - d->pad; q.rm_w0 = 2 * f.cls_ww0[b] + b - d->pad;
+                    q.b_off = off;
+                    cls_of[p.ncls++] = 2 * a + b;
+                    p.M += q.M;                        // the tile heuristic sees the whole launch
+                }
+                off += d->C * cp.Ra[a] * cp.Sa[b] * d->K;
+            }
+        hipLaunchKernelGGL(pack_class_filters_kernel, dim3(grid_for((size_t)d->K * d->R * d->S * d->C)), dim3(256), 0,
+                           c->stream, w, d->K, d->R, d->S, d->C, cp, wc);
+        EOQ_LAUNCH_CHECK();
+        // fields the kernel takes from the class table still need sane values for the dispatcher
+        p.P = d->H; p.Q = d->W; p.R = cp.Ra[0]; p.S = cp.Sa[0]; p.nk16 = p.R * p.S * p.c16;
+        if (int rc = dispatch_igemm<MODE_BWD_DATA, EPI_D16>(c, p, &bm, &bn)) return rc;
+        const int tiles_n = (d->C + bn - 1) / bn;
+        int base = 0;
+        for (int i = 0; i < p.ncls; ++i) {
+            const int cl = cls_of[i];
+            f.cls_base[cl] = base;
+            f.cls_bm_shift[cl] = bm == 64 ? 6 : (bm == 128 ? 7 : 8);
+            f.cls_bn_shift[cl] = bn == 32 ? 5 : (bn == 64 ? 6 : 7);
+            f.cls_tiles_n[cl] = tiles_n;
+            base += ((p.cls[i].M + bm - 1) / bm) * tiles_n;
+        }
+    } else {
     if (int rc = bwd_data_params(sub ? &dsub : d, e, wt, p)) return rc;
     p.absmax = absmax_slot;
     p.d16 = d16;
     p.tile_shift = tile_shift;
-    int bm = 0, bn = 0;
     if (int rc = dispatch_igemm<MODE_BWD_DATA, EPI_D16>(c, p, &bm, &bn)) return rc;
-    D16Finish f{};
+    }
     f.d16 = d16; f.tile_shift = tile_shift;
     f.bm_shift = bm == 64 ? 6 : (bm == 128 ? 7 : 8);
     f.bn_shift = bn == 32 ? 5 : (bn == 64 ? 6 : 7);

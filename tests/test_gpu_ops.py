@@ -223,7 +223,10 @@ def _bwd_data_sq_case(ctx, d, e, w, with_mask):
 
 
 SQ_SHAPES = CONV_SHAPES[:8] + [ConvShape(2, 17, 13, 32, 64, 1, 1, 2, 0),     # strided 1x1, odd extents
-                               ConvShape(1, 10, 10, 16, 48, 1, 1, 3, 0)]     # stride 3
+                               ConvShape(1, 10, 10, 16, 48, 1, 1, 3, 0),     # stride 3
+                               ConvShape(2, 28, 28, 64, 128, 3, 3, 2, 1),    # stride-2 3x3: four parity classes
+                               ConvShape(2, 12, 9, 32, 32, 5, 5, 2, 2),      # 5x5 stride 2, pad 2
+                               ConvShape(1, 11, 14, 16, 16, 2, 2, 2, 0)]     # 2x2 stride 2, no padding
 
 
 @pytest.mark.parametrize("d", SQ_SHAPES, ids=[f"{d.N}x{d.H}x{d.W}x{d.C}-k{d.K}r{d.R}s{d.stride}" for d in SQ_SHAPES])
