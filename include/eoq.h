@@ -244,6 +244,20 @@ int eoq_requant_epilogue(eoq_ctx *ctx, const eoq_requant_args *args);
 int eoq_update_int8(eoq_ctx *ctx, int8_t *w, size_t n, const int8_t *g, const int32_t *g_exp_slot,
                     const int32_t *g_max_code, const int32_t *lr_slot);
 
+/* ---- Q_g, Q_u and the update of one layer's filters in one pass (Eq.12, Eq.13, Eq.8) -------------
+ * Same result as eoq_requant_epilogue(EOQ_RQ_SQ_ACC) on the weight-gradient sums, eoq_update_int8 with the
+ * codes it wrote and (wt non-NULL) eoq_transpose_filters of the updated filters, without writing the gradient
+ * codes and reading them back:  with M = *absmax_slot (max|acc|, as left by eoq_conv_bwd_weight),
+ * r = R(log2 M), g = clamp(R(acc * 2^(7-r))), Eg = *exp_in + exp_in_off + r - 7, then the update of
+ * eoq_update_int8 with (g, Eg, max|g|) and the learning rate in lr_slot.  acc and w are device arrays of
+ * desc->K * R * S * C elements in K x R x S x C order, 16-byte aligned; w is updated in place.
+ * wt (may be NULL; needs K % 16 == 0 and C % 16 == 0): receives the updated filters in C x R x S x K order.
+ * g_out (may be NULL) receives the gradient codes; *exp_out = Eg and *max_code_out = max|g| when non-NULL.
+ * M = 0 leaves w unchanged (wt is still written), g = 0, Eg = *exp_in + exp_in_off. */
+int eoq_grad_update(eoq_ctx *ctx, const eoq_conv_desc *desc, const int32_t *acc, const int32_t *absmax_slot,
+                    const int32_t *exp_in, int32_t exp_in_off, const int32_t *lr_slot, int8_t *w, int8_t *wt,
+                    int8_t *g_out, int32_t *exp_out, int32_t *max_code_out);
+
 /* ---- scalar parameters (bias, multiplier: Eq.10, Eq.4 lines g_b1, g_b2, g_gamma, Eq.13) -----------
  * The gradient of a scalar is the sum over all elements, then Q_g of that one-element tensor, then
  * the update above without the clamp.  Each descriptor names up to two terms S * 2^(E + off):

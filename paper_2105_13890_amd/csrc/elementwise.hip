@@ -39,6 +39,7 @@ __device__ __forceinline__ void set_byte(v4i &v, int i, int code)
 // ------------------------------------------------------------------------------------------
 __global__ void absmax_f32_kernel(const float *x, size_t n, uint32_t *slot_bits, uint32_t *status)
 {
+    __shared__ uint32_t red[16];
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     uint32_t m = 0;
@@ -47,9 +48,12 @@ __global__ void absmax_f32_kernel(const float *x, size_t n, uint32_t *slot_bits,
         m = b > m ? b : m;
     }
     m = wave_max_u32(m);
-    if ((threadIdx.x & 63) == 0) {
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (unsigned w = 1; w < (blockDim.x + 63) / 64; ++w) m = red[w] > m ? red[w] : m;
         if (m >= 0x7f800000u) atomicOr(status, (uint32_t)EOQ_FLAG_NONFINITE);
-        if (m) atomicMax(slot_bits, m);
+        if (m > *(volatile uint32_t *)slot_bits) atomicMax(slot_bits, m);      // one same-address atomic per block at most
     }
 }
 
@@ -363,6 +367,109 @@ __global__ void update_int8_kernel(int8_t *w, size_t n, const int8_t *g, const i
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Q_g, Q_u and the update of one filter bank in one pass (Eq.12, Eq.13), with the transposed copy
+// ------------------------------------------------------------------------------------------
+struct GradUpdate {
+    const int32_t *acc, *absmax, *exp_in, *lr;
+    int32_t exp_in_off;
+    int8_t *w, *wt, *g_out;
+    int32_t *exp_out, *max_code_out;
+    uint32_t *status;
+    int K, RS, C;
+    size_t n;
+};
+
+struct GradRule {
+    int r;            // Q_g shift exponent
+    bool live;        // a non-zero gradient exists
+    UpdateRule u;
+};
+
+__device__ __forceinline__ GradRule make_grad_rule(const GradUpdate &p, bool writer)
+{
+    GradRule gr;
+    const uint64_t M = (uint64_t)(uint32_t)*p.absmax;
+    const int E = *p.exp_in + p.exp_in_off;
+    gr.r = M ? sq_exponent_u64(M) : 7;
+    const int Eg = M ? E + gr.r - 7 : E;
+    const int gmax = M ? sq_code((int64_t)M, gr.r) : 0;
+    if (writer) {
+        if (p.exp_out) *p.exp_out = Eg;
+        if (p.max_code_out) *p.max_code_out = gmax;
+    }
+    gr.live = make_update_rule(gmax, Eg, p.lr, gr.u, p.status);
+    return gr;
+}
+
+// 16 consecutive elements: codes of the gradient, new weights
+__device__ __forceinline__ void grad_update16(const GradRule &gr, const v4i a[4], v4i wv, v4i &gv, v4i &ov)
+{
+    gv = v4i{0, 0, 0, 0};
+    ov = wv;
+    if (!gr.live) return;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const int g = sq_code((int64_t)a[k >> 2][k & 3], gr.r);
+        set_byte(gv, k, g);
+        set_byte(ov, k, clamp_i(byte_at(wv, k) - gr.u.delta(g), -CODE_MAX, CODE_MAX));
+    }
+}
+
+// any element count, no transposed copy
+__global__ void grad_update_flat_kernel(GradUpdate p)
+{
+    const GradRule gr = make_grad_rule(p, blockIdx.x == 0 && threadIdx.x == 0);
+    const size_t nv = p.n / 16;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv; i += (size_t)gridDim.x * blockDim.x) {
+        v4i a[4], gv, ov;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) a[k] = ((const v4i *)p.acc)[i * 4 + k];
+        grad_update16(gr, a, ((const v4i *)p.w)[i], gv, ov);
+        ((v4i *)p.w)[i] = ov;
+        if (p.g_out) ((v4i *)p.g_out)[i] = gv;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (p.n & 15)) {
+        const size_t t = nv * 16 + threadIdx.x;
+        const int g = gr.live ? sq_code((int64_t)p.acc[t], gr.r) : 0;
+        if (gr.live) p.w[t] = (int8_t)clamp_i((int)p.w[t] - gr.u.delta(g), -CODE_MAX, CODE_MAX);
+        if (p.g_out) p.g_out[t] = (int8_t)g;
+    }
+}
+
+// K x RS x C filters with K, C multiples of 16: one workgroup per 64 (k) x 64 (c) tile of one tap; the new weights
+// also go out in C x RS x K order through a transposing LDS tile
+constexpr int GU_LD = 80;
+__global__ void __launch_bounds__(256) grad_update_tiled_kernel(GradUpdate p)
+{
+    __shared__ __align__(16) int8_t tile[64 * GU_LD];
+    const GradRule gr = make_grad_rule(p, blockIdx.x == 0 && threadIdx.x == 0);
+    const int tiles_c = (p.C + 63) / 64;
+    int b = blockIdx.x;
+    const int tc = b % tiles_c; b /= tiles_c;
+    const int rs = b % p.RS;
+    const int tk = b / p.RS;
+    const int t = threadIdx.x;
+    const int kl = t >> 2, cl = (t & 3) * 16;
+    const int k = tk * 64 + kl, c = tc * 64 + cl;
+    if (k < p.K && c < p.C) {
+        const size_t i = (((size_t)k * p.RS + rs) * p.C + c) / 16;
+        v4i a[4], gv, ov;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) a[q] = ((const v4i *)p.acc)[i * 4 + q];
+        grad_update16(gr, a, ((const v4i *)p.w)[i], gv, ov);
+        ((v4i *)p.w)[i] = ov;
+        if (p.g_out) ((v4i *)p.g_out)[i] = gv;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) tile[(cl + q) * GU_LD + kl] = (int8_t)byte_at(ov, q);
+    }
+    __syncthreads();
+    const int cr = t >> 2, ks = (t & 3) * 16;
+    const int c2 = tc * 64 + cr, k2 = tk * 64 + ks;
+    if (c2 < p.C && k2 < p.K)
+        *(v4i *)(p.wt + ((size_t)c2 * p.RS + rs) * p.K + k2) = *(const v4i *)(tile + cr * GU_LD + ks);
+}
+
 __global__ void update_scalars_kernel(int32_t *scalars, const eoq_scalar_grad *descs, int count, const int64_t *sums,
                                       const int32_t *exps, const int32_t *lr_slot, int32_t *g_code_out,
                                       int32_t *g_exp_out, uint32_t *status)
@@ -519,6 +626,30 @@ extern "C" int eoq_update_int8(eoq_ctx *c, int8_t *w, size_t n, const int8_t *g,
     }
     hipLaunchKernelGGL(update_int8_kernel, grid, block, 0, c->stream, w, n, g, g_exp_slot, g_max_code, lr_slot,
                        c->d_status);
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}
+
+extern "C" int eoq_grad_update(eoq_ctx *c, const eoq_conv_desc *d, const int32_t *acc, const int32_t *absmax_slot,
+                               const int32_t *exp_in, int32_t exp_in_off, const int32_t *lr_slot, int8_t *w, int8_t *wt,
+                               int8_t *g_out, int32_t *exp_out, int32_t *max_code_out)
+{
+    if (!c || !d || !acc || !absmax_slot || !exp_in || !lr_slot || !w) return EOQ_ERR_ARG;
+    if (d->K <= 0 || d->R <= 0 || d->S <= 0 || d->C <= 0) return EOQ_ERR_SHAPE;
+    if (!aligned16(acc) || !aligned16(w) || !aligned16(wt) || !aligned16(g_out)) return EOQ_ERR_ARG;
+    GradUpdate p{};
+    p.acc = acc; p.absmax = absmax_slot; p.exp_in = exp_in; p.lr = lr_slot; p.exp_in_off = exp_in_off;
+    p.w = w; p.wt = wt; p.g_out = g_out; p.exp_out = exp_out; p.max_code_out = max_code_out; p.status = c->d_status;
+    p.K = d->K; p.RS = d->R * d->S; p.C = d->C;
+    p.n = (size_t)d->K * p.RS * d->C;
+    if (wt) {
+        if (d->K % 16 || d->C % 16) return EOQ_ERR_SHAPE;
+        const size_t tiles = (size_t)((d->K + 63) / 64) * p.RS * ((d->C + 63) / 64);
+        if (tiles > 0x7fffffffu) return EOQ_ERR_SHAPE;
+        hipLaunchKernelGGL(grad_update_tiled_kernel, dim3((unsigned)tiles), dim3(256), 0, c->stream, p);
+    } else {
+        hipLaunchKernelGGL(grad_update_flat_kernel, dim3(ew_blocks(p.n / 16 + 1)), dim3(EW_THREADS), 0, c->stream, p);
+    }
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }

@@ -21,7 +21,7 @@ RQ_FWD, RQ_SQ_ACC, RQ_SQ_GAMMA, RQ_SQ_MERGE = 0, 1, 2, 3
 EXPORTS = [
     "eoq_create", "eoq_destroy", "eoq_strerror", "eoq_status", "eoq_workspace_bytes", "eoq_fill_zero",
     "eoq_quantize", "eoq_pre_bias", "eoq_conv_fwd", "eoq_conv_bwd_data", "eoq_conv_bwd_data_sq", "eoq_transpose_filters", "eoq_conv_bwd_weight",
-    "eoq_relu_bwd", "eoq_relu_bwd_recompute", "eoq_merge_absmax", "eoq_requant_epilogue", "eoq_update_int8", "eoq_update_scalars",
+    "eoq_relu_bwd", "eoq_relu_bwd_recompute", "eoq_merge_absmax", "eoq_requant_epilogue", "eoq_update_int8", "eoq_grad_update", "eoq_update_scalars",
     "eoq_maxpool_fwd", "eoq_maxpool_bwd", "eoq_maxpool_bwd_sq", "eoq_gap_sum", "eoq_broadcast_hw", "eoq_head_workspace_bytes",
     "eoq_head_fwd_bwd",
 ]
@@ -89,6 +89,7 @@ def _load():
     lib.eoq_merge_absmax.argtypes = [vp, vp, vp, vp, vp, sz, vp]
     lib.eoq_requant_epilogue.argtypes = [vp, C.POINTER(RequantArgs)]
     lib.eoq_update_int8.argtypes = [vp, vp, sz, vp, vp, vp, vp]
+    lib.eoq_grad_update.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.eoq_update_scalars.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.eoq_maxpool_fwd.argtypes = [vp, vp] + [i32] * 8 + [vp, vp, vp, vp]
     lib.eoq_maxpool_bwd.argtypes = [vp, vp, vp] + [i32] * 8 + [vp, vp]
@@ -220,6 +221,12 @@ class Context:
     def update_int8(self, w, g, g_exp_slot, g_max_code, lr_slot):
         _check(_lib.eoq_update_int8(self._h, _ptr(w), w.numel(), _ptr(g), _ptr(g_exp_slot), _ptr(g_max_code),
                                     _ptr(lr_slot)), "eoq_update_int8")
+
+    def grad_update(self, desc, acc, absmax_slot, exp_in, exp_in_off, lr_slot, w, wt=None, g_out=None, exp_out=None,
+                    max_code_out=None):
+        _check(_lib.eoq_grad_update(self._h, C.byref(desc), _ptr(acc), _ptr(absmax_slot), _ptr(exp_in), exp_in_off,
+                                    _ptr(lr_slot), _ptr(w), _ptr(wt), _ptr(g_out), _ptr(exp_out), _ptr(max_code_out)),
+               "eoq_grad_update")
 
     def update_scalars(self, scalars, descs, count, sums, exps, lr_slot, g_code_out=None, g_exp_out=None):
         _check(_lib.eoq_update_scalars(self._h, _ptr(scalars), _ptr(descs), count, _ptr(sums), _ptr(exps),

@@ -91,6 +91,7 @@ class FixupNet:
         self.side = torch.cuda.Stream()            # default priority
         self.ctx_w = eoq.Context(self.side)        # parameter chain: dW, Q_g, update
         self._pending: dict[int, torch.cuda.Event] = {}     # error buffer -> last read of it on the side stream
+        self._last_gdone = None                 # event after the latest multiplier-gradient sum of this step
         self.trace: dict[str, object] = {}
         self.prof = None                   # list of (kind, unit, work, start event, end event) while profiling
         bt = cfg["block"]
@@ -413,23 +414,34 @@ class FixupNet:
 
     # ------------------------------------------------------------------------------------------ backward
     def _grad(self, u: Unit, e3):
-        """g_w = Q_g(e3 * x1) (Eq.4, Eq.12), on the side stream once e3 exists."""
+        """Weight-gradient sums e3 * x1 (Eq.4) on the side stream once e3 exists.  Returns the int32 sums; Q_g (Eq.12)
+        and the update follow in _apply_update once the layer's backward-data call has read the old weights."""
         c, ws, st = (self.ctx_w, self.ws_w, self.side) if self.overlap else (self.ctx, self.ws, self.main)
         if self.overlap:
             u.ev_e3.record(self.main)
             self.side.wait_event(u.ev_e3)
-        n = u.w.numel()
-        G = self.gacc[:n]
+        G = self.gacc[:u.w.numel()]
         self._call("conv_bwd_weight", u.name, self._conv_work(u), c.conv_bwd_weight, u.desc, e3, u.u, G,
                    self.s32(u.name + ".M_G"), ws, stream=st)
+        return G
+
+    def _apply_update(self, u: Unit, G):
+        """g_w = Q_g(G) (Eq.12), W <- Q_w(W - Q_u(lr g_w)) (Eq.13), and the transposed copy the next backward-data
+        call multiplies with: one fused call; three separate ones when tracing, which records the gradient codes."""
+        c = self.ctx_w if self.overlap else self.ctx
+        M_G, Eg, gmax = self.s32(u.name + ".M_G"), self.s32(u.name + ".Eg"), self.s32(u.name + ".gmax")
+        if not self.tracing:
+            c.grad_update(u.desc, G, M_G, self.s32(u.E3), -7, self.lr, u.w, wt=u.wt, exp_out=Eg, max_code_out=gmax)
+            return
+        n = u.w.numel()
         g = self.gq[:n]
-        c.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=G, absmax=self.s32(u.name + ".M_G"), exp_in=self.s32(u.E3),
-                           exp_in_off=-7, out=g, exp_out=self.s32(u.name + ".Eg"),
-                           max_code_out=self.s32(u.name + ".gmax"))
-        if self.tracing:
-            self._rec(u.name + ".G", G.view(u.w.shape))
-            self._rec(u.name + ".gw", g.view(u.w.shape))
-        return g
+        c.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=G, absmax=M_G, exp_in=self.s32(u.E3), exp_in_off=-7, out=g,
+                           exp_out=Eg, max_code_out=gmax)
+        self._rec(u.name + ".G", G.view(u.w.shape))
+        self._rec(u.name + ".gw", g.view(u.w.shape))
+        c.update_int8(u.w, g, Eg, gmax, self.lr)
+        if u.wt is not None:
+            c.transpose_filters(u.desc, u.w, u.wt)
 
     def _gamma_sum(self, u: Unit, e1):
         """Sum of e1 * x2 for the multiplier's gradient (Eq.4), with x2 recomputed from (u, w) instead of having
@@ -445,6 +457,7 @@ class FixupNet:
         if self.overlap:
             u.ev_gdone.record(self.side)
             self._pending[e1.data_ptr()] = u.ev_gdone
+            self._last_gdone = u.ev_gdone
 
     def _unit_bwd(self, u: Unit, e0, bufs, need_dx=True, relu_done=False, fuse_below: Unit | None = None,
                   merge=None):
@@ -496,20 +509,14 @@ class FixupNet:
                            self.s64(u.name + ".S_e4"), self.ws, w_transposed=u.wt, **mg)
                 if self.tracing:
                     self._rec(u.name + ".e4", e4[:n_in].view(u.in_shape))
-        # W <- Q_w(W - Q_u(lr g)) (Eq.13) once every reader of the old weights has run
+        # the update, once every reader of the old weights has run
+        if self.overlap and need_dx:
+            u.ev_dx.record(self.main)
+            self.side.wait_event(u.ev_dx)
+        self._apply_update(u, g)
         if self.overlap:
-            if need_dx:
-                u.ev_dx.record(self.main)
-                self.side.wait_event(u.ev_dx)
-            self.ctx_w.update_int8(u.w, g, self.s32(u.name + ".Eg"), self.s32(u.name + ".gmax"), self.lr)
-            if u.wt is not None:
-                self.ctx_w.transpose_filters(u.desc, u.w, u.wt)
             u.ev_done.record(self.side)
             self._pending[e3.data_ptr()] = u.ev_done       # e3 may not be overwritten before dW has read it
-        else:
-            c.update_int8(u.w, g, self.s32(u.name + ".Eg"), self.s32(u.name + ".gmax"), self.lr)
-            if u.wt is not None:
-                c.transpose_filters(u.desc, u.w, u.wt)
         if u.gamma:
             bufs.append(e3)
         return e4, e1
@@ -579,6 +586,8 @@ class FixupNet:
         bufs.append(e)
 
     def _update_scalars(self):
+        if self.overlap and self._last_gdone is not None:
+            self.main.wait_event(self._last_gdone)       # the multiplier-gradient sums come from the side stream
         self.ctx.update_scalars(self.scal, self.sgrad_tab, len(self.sgrad_entries), self.sums64, self.slots32, self.lr,
                                 self.g_code, self.g_exp)
 
@@ -587,6 +596,7 @@ class FixupNet:
         if self.overlap:
             self.main.wait_stream(self.side)
         self._pending.clear()
+        self._last_gdone = None
 
     # ------------------------------------------------------------------------------------------ whole steps
     def _zero_stats(self):

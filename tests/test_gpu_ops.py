@@ -378,6 +378,34 @@ def test_update_int8_and_scalars(ctx):
             assert int(host(sd)[param]) == oo.update_scalar(int(scal[param]), gco, geo, m, j), (i, m, j)
 
 
+@pytest.mark.parametrize("K,R,S,Cc,with_t", [(64, 1, 1, 64, True), (48, 3, 3, 80, True), (128, 1, 1, 512, True),
+                                             (208, 3, 3, 16, True), (64, 7, 7, 3, False), (16, 3, 3, 16, False)])
+def test_grad_update(ctx, K, R, S, Cc, with_t):
+    """Q_g + Q_u + update (+ transposed copy) in one call against the oracle's three steps (Eq.12, Eq.13, Eq.8)."""
+    from paper_2105_13890_amd import eoq
+    n = K * R * S * Cc
+    d = eoq.ConvDesc(1, 8, 8, Cc, K, R, S, 1, 0)
+    cases = [(-12, 1, -3, 9173), (-9, 3, 2, 1), (-20, 1, 4, 300), (-14, 25, -6, 70000), (-10, 1, 0, 0)]
+    for trial, (E, m, j, mul) in enumerate(cases):
+        W = si.uniform_int8(trial, "W", (n,))
+        acc = si.uniform_int8(trial, "acc", (n,)).astype(np.int32) * mul + (si.uniform_int8(trial, "acc2", (n,)) if mul else 0)
+        go, Eg = oo.sq_acc(acc, E - 7)
+        Wo = oo.update_weights(W, go, Eg, m, j) if acc.any() else W
+        Wd, wt, gd = dev(W), (zeros((n,), torch.int8) if with_t else None), zeros((n,), torch.int8)
+        sl = dev(np.array([int(np.abs(acc.astype(np.int64)).max()), E, m, j, 0, 0], dtype=np.int32))
+        ctx.grad_update(d, dev(acc), sl[0:1], sl[1:2], -7, sl[2:4], Wd, wt=wt, g_out=gd, exp_out=sl[4:5],
+                        max_code_out=sl[5:6])
+        assert np.array_equal(host(gd), go), trial
+        assert np.array_equal(host(Wd), Wo), trial
+        assert int(host(sl)[4]) == Eg and int(host(sl)[5]) == int(np.abs(go.astype(np.int64)).max()), trial
+        if with_t:
+            assert np.array_equal(host(wt).reshape(Cc, R, S, K), Wo.reshape(K, R, S, Cc).transpose(3, 1, 2, 0)), trial
+        # without the optional outputs
+        Wd2 = dev(W)
+        ctx.grad_update(d, dev(acc), sl[0:1], sl[1:2], -7, sl[2:4], Wd2, wt=wt)
+        assert np.array_equal(host(Wd2), Wo), trial
+
+
 def test_pool_gap_broadcast(ctx):
     N, H, W, Cc = 3, 13, 15, 32
     a = si.uniform_int8(7, "a", (N, H, W, Cc), -6, 6)
