@@ -79,7 +79,7 @@ class _Slots:
 
 
 class FixupNet:
-    N_EBUF = 8     # rotating error buffers: enough that the main stream rarely waits for the side stream's reads
+    N_EBUF = 6     # rotating error buffers (at least 5: e1, e3, e4 of a layer, the shortcut error, the other merge input)
 
     def __init__(self, cfg: dict, batch: int, seed: int = 0, trace: bool = False, overlap: bool = True):
         assert torch.cuda.is_available(), "libeoq needs the GPU; there is no CPU path"
@@ -90,8 +90,11 @@ class FixupNet:
         self.main = torch.cuda.current_stream()
         self.side = torch.cuda.Stream()            # default priority
         self.ctx_w = eoq.Context(self.side)        # parameter chain: dW, Q_g, update
-        self._pending: dict[int, torch.cuda.Event] = {}     # error buffer -> last read of it on the side stream
+        self._pending: dict[int, int] = {}      # error buffer -> index (in _side_ev) of the side stream's last read of it
+        self._side_ev: list = []                # this step's events on the side stream, in the order they were recorded
+        self._synced = -1                       # the main stream has waited for _side_ev[: _synced + 1]
         self._last_gdone = None                 # event after the latest multiplier-gradient sum of this step
+        self._deferred = None                   # (layer, weight-gradient sums) whose update has not been enqueued yet
         self.trace: dict[str, object] = {}
         self.prof = None                   # list of (kind, unit, work, start event, end event) while profiling
         bt = cfg["block"]
@@ -193,6 +196,9 @@ class FixupNet:
         self.y_out = i8(self.blocks[-1].units[-1].out_shape)
         max_act = max(max(int(np.prod(u.out_shape)), int(np.prod(u.in_shape))) for u in all_units)
         max_w = max(u.w.numel() for u in all_units)
+        # few rotating error buffers: a buffer that was written a moment ago is still in the memory-side cache when
+        # the next kernel reads it (one buffer per acquisition, which would spare the main stream every wait for
+        # the side stream's reads, measured 10 % slower)
         self.ebuf = [i8((max_act,)) for _ in range(self.N_EBUF)]
         self.gacc = i32((max_w,))
         self.gq = i8((max_w,))
@@ -203,7 +209,7 @@ class FixupNet:
         self.ws = torch.empty((ws_bytes,), dtype=torch.uint8, device=self.dev)
         self.ws_w = torch.empty((ws_bytes,), dtype=torch.uint8, device=self.dev)     # the side stream's own scratch
         for u in all_units:
-            u.ev_e3, u.ev_dx, u.ev_done, u.ev_g, u.ev_gdone = (torch.cuda.Event() for _ in range(5))
+            u.ev_e3, u.ev_dx, u.ev_done = (torch.cuda.Event() for _ in range(3))
         # ---- slots -------------------------------------------------------------------------------
         self.sl = _Slots()
         self._plan_slots()
@@ -321,11 +327,14 @@ class FixupNet:
             self.trace[name] = t.detach().clone()
 
     def _acquire(self, bufs):
-        """Next free error buffer; if the side stream still reads its previous content, the main stream waits."""
+        """Next free error buffer; if the side stream may still read its previous content, the main stream waits for
+        that read (waiting for a later event of the side stream instead, to cover the buffers acquired next with
+        one wait, stalls the main stream whenever the side stream runs a layer or two behind: measured slower)."""
         b = bufs.popleft()
-        ev = self._pending.pop(b.data_ptr(), None)
-        if ev is not None:
-            self.main.wait_event(ev)
+        k = self._pending.pop(b.data_ptr(), -1)
+        if k > self._synced:
+            self.main.wait_event(self._side_ev[k])
+            self._synced = k
         return b
 
     def set_lr(self, m: int, j: int):
@@ -413,17 +422,48 @@ class FixupNet:
         self._rec("gap.sum", self.gap)
 
     # ------------------------------------------------------------------------------------------ backward
-    def _grad(self, u: Unit, e3):
-        """Weight-gradient sums e3 * x1 (Eq.4) on the side stream once e3 exists.  Returns the int32 sums; Q_g (Eq.12)
-        and the update follow in _apply_update once the layer's backward-data call has read the old weights."""
-        c, ws, st = (self.ctx_w, self.ws_w, self.side) if self.overlap else (self.ctx, self.ws, self.main)
-        if self.overlap:
-            u.ev_e3.record(self.main)
-            self.side.wait_event(u.ev_e3)
+    def _grad(self, u: Unit, e3, e3_buf, gamma_e1=None):
+        """Weight-gradient sums e3 * x1 (Eq.4) on the side stream once e3 exists; Q_g (Eq.12) and the update follow in
+        _apply_update.  A wait for an event of another stream costs the waiting stream several microseconds even
+        when the event has long happened, so the side stream waits ONCE per layer, here, and everything else it
+        needs is ordered through that wait: the main stream produced e3 after the backward-data call of the layer
+        above, so that layer's update (deferred until now) may overwrite its weights; e1 exists before e3, so the
+        multiplier-gradient sum of this layer (gamma_e1: its e1 buffer) is enqueued here too."""
+        if not self.overlap:
+            if gamma_e1 is not None:
+                self._gamma_sum(u, gamma_e1, self.ctx, self.main)
+            G = self.gacc[:u.w.numel()]
+            self._call("conv_bwd_weight", u.name, self._conv_work(u), self.ctx.conv_bwd_weight, u.desc, e3, u.u, G,
+                       self.s32(u.name + ".M_G"), self.ws, stream=self.main)
+            return G
+        u.ev_e3.record(self.main)
+        self.side.wait_event(u.ev_e3)
+        self._flush_update()
+        if gamma_e1 is not None:
+            self._gamma_sum(u, gamma_e1, self.ctx_w, self.side)
         G = self.gacc[:u.w.numel()]
-        self._call("conv_bwd_weight", u.name, self._conv_work(u), c.conv_bwd_weight, u.desc, e3, u.u, G,
-                   self.s32(u.name + ".M_G"), ws, stream=st)
+        self._call("conv_bwd_weight", u.name, self._conv_work(u), self.ctx_w.conv_bwd_weight, u.desc, e3, u.u, G,
+                   self.s32(u.name + ".M_G"), self.ws_w, stream=self.side)
+        u.ev_done.record(self.side)
+        self._side_ev.append(u.ev_done)
+        k = len(self._side_ev) - 1
+        self._pending[e3_buf.data_ptr()] = k               # neither e3 nor e1 is overwritten before the side stream
+        if gamma_e1 is not None:                           # has read it
+            self._pending[gamma_e1.data_ptr()] = k
+            self._last_gdone = k
         return G
+
+    def _flush_update(self, final=False):
+        """Apply the deferred update.  final: no later layer orders it behind the backward-data call that read the
+        old weights, so the side stream waits for the main stream as it stands."""
+        if self._deferred is None:
+            return
+        u, G = self._deferred
+        self._deferred = None
+        if final and self.overlap:
+            u.ev_dx.record(self.main)
+            self.side.wait_event(u.ev_dx)
+        self._apply_update(u, G)
 
     def _apply_update(self, u: Unit, G):
         """g_w = Q_g(G) (Eq.12), W <- Q_w(W - Q_u(lr g_w)) (Eq.13), and the transposed copy the next backward-data
@@ -443,21 +483,13 @@ class FixupNet:
         if u.wt is not None:
             c.transpose_filters(u.desc, u.w, u.wt)
 
-    def _gamma_sum(self, u: Unit, e1):
+    def _gamma_sum(self, u: Unit, e1, c, st):
         """Sum of e1 * x2 for the multiplier's gradient (Eq.4), with x2 recomputed from (u, w) instead of having
         been stored by the forward pass.  Nothing on the error chain waits for it -- only the scalar update at the
         end of the step does -- so the convolution runs on the side stream."""
         n_out = int(np.prod(u.out_shape))
-        c, st = (self.ctx_w, self.side) if self.overlap else (self.ctx, self.main)
-        if self.overlap:
-            u.ev_g.record(self.main)
-            self.side.wait_event(u.ev_g)
         self._call("relu_bwd_recompute", u.name, self._conv_work(u), c.relu_bwd_recompute, u.desc, u.u, u.w,
                    e1[:n_out], None, None, None, self.s64(u.name + ".S_e1t"), None, stream=st)
-        if self.overlap:
-            u.ev_gdone.record(self.side)
-            self._pending[e1.data_ptr()] = u.ev_gdone
-            self._last_gdone = u.ev_gdone
 
     def _unit_bwd(self, u: Unit, e0, bufs, need_dx=True, relu_done=False, fuse_below: Unit | None = None,
                   merge=None):
@@ -473,8 +505,6 @@ class FixupNet:
         if u.relu and not relu_done:
             c.relu_bwd(e0[:n_out], u.mask, None, e1[:n_out], self.s64(u.name + ".S_e1"), None,
                        self.s32(u.name + ".M_e1"))
-        if u.relu and u.gamma:
-            self._gamma_sum(u, e1)
         if u.gamma:
             e3 = self._acquire(bufs)
             c.requant_epilogue(eoq.RQ_SQ_GAMMA, n_out, src_a=e1[:n_out], gamma=self.sc(u.gamma),
@@ -484,7 +514,7 @@ class FixupNet:
             e3 = e1
         if self.tracing:
             self._rec(u.name + ".e3", e3[:n_out].view(u.out_shape))
-        g = self._grad(u, e3[:n_out])
+        g = self._grad(u, e3[:n_out], e3, gamma_e1=e1 if (u.relu and u.gamma) else None)
         e4 = None
         if need_dx:
             n_in = int(np.prod(u.in_shape))
@@ -509,14 +539,11 @@ class FixupNet:
                            self.s64(u.name + ".S_e4"), self.ws, w_transposed=u.wt, **mg)
                 if self.tracing:
                     self._rec(u.name + ".e4", e4[:n_in].view(u.in_shape))
-        # the update, once every reader of the old weights has run
+        # the update, once every reader of the old weights has run: behind the next layer's wait on the side stream
         if self.overlap and need_dx:
-            u.ev_dx.record(self.main)
-            self.side.wait_event(u.ev_dx)
-        self._apply_update(u, g)
-        if self.overlap:
-            u.ev_done.record(self.side)
-            self._pending[e3.data_ptr()] = u.ev_done       # e3 may not be overwritten before dW has read it
+            self._deferred = (u, g)
+        else:
+            self._apply_update(u, g)
         if u.gamma:
             bufs.append(e3)
         return e4, e1
@@ -586,16 +613,20 @@ class FixupNet:
         bufs.append(e)
 
     def _update_scalars(self):
-        if self.overlap and self._last_gdone is not None:
-            self.main.wait_event(self._last_gdone)       # the multiplier-gradient sums come from the side stream
+        if self.overlap and self._last_gdone is not None and self._last_gdone > self._synced:
+            self.main.wait_event(self._side_ev[self._last_gdone])       # the multiplier-gradient sums come from the side stream
+            self._synced = self._last_gdone
         self.ctx.update_scalars(self.scal, self.sgrad_tab, len(self.sgrad_entries), self.sums64, self.slots32, self.lr,
                                 self.g_code, self.g_exp)
 
     def _join(self):
         """End of a step: everything the side stream did is ordered before what the main stream does next."""
+        self._flush_update(final=True)
         if self.overlap:
             self.main.wait_stream(self.side)
         self._pending.clear()
+        self._side_ev.clear()
+        self._synced = -1
         self._last_gdone = None
 
     # ------------------------------------------------------------------------------------------ whole steps
