@@ -149,7 +149,9 @@ int eoq_conv_bwd_data(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, 
  *    and 0 elsewhere, *sum_e1 += sum(e1), *absmax_e1 max= max|e1| (each may be NULL); e4 may then be NULL;
  *  - the statistics of the block-input merge: with merge_other non-NULL (int8 codes of the other error, same
  *    shape, exponent *merge_exp_other), *merge_absmax max= max|e4 * 2^(E4-Em) + other * 2^(Eo-Em)|,
- *    Em = min(E4, Eo), what eoq_merge_absmax computes; needs e4 and excludes e1.
+ *    Em = min(E4, Eo), what eoq_merge_absmax computes; needs e4 and excludes e1.  With merge_mask_bits (one bit per
+ *    element, the forward mask of the layer that receives the merged error) *merge_absmax_masked max= the same
+ *    maximum over the elements whose bit is set: what EOQ_RQ_SQ_MERGE needs to write Q_e(e1 * gamma) in its own pass.
  *  - w_transposed non-NULL: the filters in C x R x S x K order, as written by eoq_transpose_filters from the same
  *    w; the call then skips its own transposition (a caller that updates w once per step transposes it once,
  *    off the critical path).
@@ -163,6 +165,8 @@ typedef struct eoq_bwd_fuse {
     const int32_t *merge_exp_other;
     int32_t *merge_absmax;
     const int8_t *w_transposed;
+    const uint32_t *merge_mask_bits;
+    int32_t *merge_absmax_masked;
 } eoq_bwd_fuse;
 int eoq_conv_bwd_data_sq(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, const int8_t *w, int8_t *e4,
                          int32_t *absmax_slot, const int32_t *exp_in, int32_t exp_in_off, int32_t *exp_out,
@@ -212,7 +216,11 @@ int eoq_merge_absmax(eoq_ctx *ctx, const int8_t *a, const int32_t *exp_a, const 
  * *max_code_out = max|out| (lets eoq_update_int8 skip its own abs-max pass).
  * EOQ_RQ_SQ_MERGE can apply, in the same pass, the ReLU backward step of the layer that receives the merged
  * error (Eq.3 line e1): with mask_bits (that layer's forward mask) the output is the code where the bit is set
- * and 0 elsewhere, sum_out sums these masked codes, and *absmax_out max= max|out| (for Q_e of e1 * gamma). */
+ * and 0 elsewhere, sum_out sums these masked codes, and *absmax_out max= max|out| (for Q_e of e1 * gamma).
+ * With out_b it also writes that next step itself: out_b = what EOQ_RQ_SQ_GAMMA gives for src_a = out, *gamma,
+ * *absmax = max|out|, *exp_in = the merge's *exp_out (Eq.3 line e3), and *exp_out_b = its exponent.  max|out| is
+ * not known before the pass, but the quantiser is monotone: it is the code of the largest merged value under the
+ * mask, *absmax_masked (from eoq_conv_bwd_data_sq's merge_absmax_masked; without mask_bits *absmax serves). */
 enum eoq_rq_mode { EOQ_RQ_FWD = 0, EOQ_RQ_SQ_ACC = 1, EOQ_RQ_SQ_GAMMA = 2, EOQ_RQ_SQ_MERGE = 3 };
 typedef struct eoq_requant_args {
     int32_t mode;
@@ -233,6 +241,9 @@ typedef struct eoq_requant_args {
     int32_t *max_code_out;     /* may be NULL */
     const uint32_t *mask_bits; /* SQ_MERGE only, may be NULL: see above (n % 16 == 0) */
     int32_t *absmax_out;       /* SQ_MERGE only, may be NULL */
+    int8_t *out_b;             /* SQ_MERGE only, may be NULL: second output, see above (n % 16 == 0) */
+    int32_t *exp_out_b;        /* with out_b */
+    const int32_t *absmax_masked; /* with out_b and mask_bits */
 } eoq_requant_args;
 int eoq_requant_epilogue(eoq_ctx *ctx, const eoq_requant_args *args);
 

@@ -909,6 +909,8 @@ struct D16Finish {
     const int8_t *mg_other;
     const int32_t *mg_exp_other;
     int32_t *mg_absmax;
+    const uint16_t *mg_mask16;       // with mg_absmax_m: the same maximum over the elements whose mask bit is set
+    int32_t *mg_absmax_m;
     uint32_t *status;
     // strided 1x1 filter: the sums exist only for the input pixels the filter touched (every sub-th row and column),
     // stored compactly as N x P x Q rows; all other input pixels receive no error
@@ -928,7 +930,7 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
     const int sh = r - 7;
     const int E4 = *p.exp_in + p.exp_in_off + (Mx ? sh : 0);
     if (blockIdx.x == 0 && threadIdx.x == 0) *p.exp_out = E4;
-    int mg_sa = 0, mg_sb = 0, mg_mx = 0;
+    int mg_sa = 0, mg_sb = 0, mg_mx = 0, mg_mxm = 0;
     if (p.mg_other) {
         int Em;
         merge_shifts(E4, *p.mg_exp_other, mg_sa, mg_sb, Em, p.status);
@@ -997,6 +999,7 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
         if (RELU && p.mask16) mk = (uint32_t)p.mask16[off >> 4];
         v4i ov = {0, 0, 0, 0};
         if (!RELU && p.mg_other) ov = *(const v4i *)(p.mg_other + off);
+        if (!RELU && p.mg_mask16) mk = (uint32_t)p.mg_mask16[off >> 4];
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             const int cd = clamp_i(code[k], -CODE_MAX, CODE_MAX);
@@ -1006,6 +1009,8 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
                 int mv = (cd << mg_sa) + (byte_at(ov, k) << mg_sb);
                 mv = mv < 0 ? -mv : mv;
                 mg_mx = mv > mg_mx ? mv : mg_mx;
+                const int mm = ((mk >> k) & 1u) ? mv : 0;
+                mg_mxm = mm > mg_mxm ? mm : mg_mxm;
             }
             if (RELU) {
                 const int e = ((mk >> k) & 1u) ? cd : 0;
@@ -1024,6 +1029,7 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
     s4w += s4; s1w += s1;
     if (p.sum_e4) block_atomic_add_i64(s4w, p.sum_e4);
     if (!RELU && p.mg_other) block_atomic_max_i32(mg_mx, p.mg_absmax);
+    if (!RELU && p.mg_mask16) block_atomic_max_i32(mg_mxm, p.mg_absmax_m);
     if (RELU) {
         if (p.sum_e1) block_atomic_add_i64(s1w, p.sum_e1);
         if (p.absmax_e1) block_atomic_max_i32(mx1, p.absmax_e1);
@@ -1348,6 +1354,9 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
     const int8_t *mg_other = fuse ? fuse->merge_other : nullptr;
     if (mg_other && (!e4 || e1 || !fuse->merge_exp_other || !fuse->merge_absmax || ((uintptr_t)mg_other & 15)))
         return EOQ_ERR_ARG;
+    const uint32_t *mg_mask = mg_other ? fuse->merge_mask_bits : nullptr;
+    if (fuse && !mg_other && (fuse->merge_mask_bits || fuse->merge_absmax_masked)) return EOQ_ERR_ARG;
+    if (mg_mask && (!fuse->merge_absmax_masked || ((uintptr_t)mg_mask & 3))) return EOQ_ERR_ARG;
     if (!c || !e || !w || (!e4 && !e1) || !absmax_slot || !exp_in || !exp_out) return EOQ_ERR_ARG;
     if (!desc_ok(d)) return EOQ_ERR_SHAPE;
     if (d->K % 16 || d->C % 16 || d->R * d->S > 64) return EOQ_ERR_SHAPE;
@@ -1454,6 +1463,8 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
     f.mg_other = mg_other;
     f.mg_exp_other = mg_other ? fuse->merge_exp_other : nullptr;
     f.mg_absmax = mg_other ? fuse->merge_absmax : nullptr;
+    f.mg_mask16 = (const uint16_t *)mg_mask;
+    f.mg_absmax_m = mg_mask ? fuse->merge_absmax_masked : nullptr;
     f.status = c->d_status;
     if (sub) { f.sub = d->stride; f.H = d->H; f.W = d->W; f.P = dsub.H; f.Q = dsub.W; }
     if (M * (d->C / 16) > 0x7fffffffu) return EOQ_ERR_SHAPE;

@@ -216,6 +216,9 @@ struct SqArgs {
     uint32_t *status;
     const uint16_t *mask16;      // SQ_MERGE: ReLU mask applied to the output (16 bits per 16 elements)
     int32_t *absmax_out;         // SQ_MERGE with mask: max|out|
+    int8_t *out_b;               // SQ_MERGE: second output Q_e(out * gamma)
+    int32_t *exp_out_b;
+    const int32_t *absmax_m;     // SQ_MERGE with out_b and a mask: max|v| over the elements whose mask bit is set
 };
 
 template <int MODE>
@@ -235,6 +238,17 @@ __global__ void sq_pass_kernel(SqArgs p)
         E = Em;
     }
     const int r = M ? sq_exponent_u64(M) : 7;
+    // second output of the merge pass: the scale quantiser is monotone, so the largest masked code is the code of
+    // the largest masked value, and the shift of Q_e(out * gamma) is known before any element has been coded
+    int r2 = 7;
+    if (MODE == EOQ_RQ_SQ_MERGE && p.out_b) {
+        g = *p.gamma;
+        const uint64_t Mm = p.absmax_m ? (uint64_t)(uint32_t)*p.absmax_m : M;
+        const uint64_t M2 = (Mm ? (uint64_t)sq_code((int64_t)Mm, r) : 0) * (uint64_t)(g < 0 ? -g : g);
+        r2 = M2 ? sq_exponent_u64(M2) : 7;
+        const int E2 = (M ? E + r - 7 : E) - 7;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *p.exp_out_b = M2 ? E2 + r2 - 7 : E2;
+    }
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         *p.exp_out = M ? E + r - 7 : E;
         if (p.max_code_out) *p.max_code_out = M ? sq_code((int64_t)M, r) : 0;
@@ -268,6 +282,7 @@ __global__ void sq_pass_kernel(SqArgs p)
         } else {
             v4i a = ((const v4i *)p.src_a)[i], b = ((const v4i *)p.src_b)[i];
             const uint32_t mk = p.mask16 ? (uint32_t)p.mask16[i] : 0xffffu;
+            v4i o2 = {0, 0, 0, 0};
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
                 int c = sq_code((int64_t)((byte_at(a, k) << sa) + (byte_at(b, k) << sb)), r);
@@ -276,7 +291,9 @@ __global__ void sq_pass_kernel(SqArgs p)
                 ls += c;
                 const int ac = c < 0 ? -c : c;
                 mxo = ac > mxo ? ac : mxo;
+                if (p.out_b) set_byte(o2, k, sq_code((int64_t)c * (int64_t)g, r2));
             }
+            if (p.out_b) ((v4i *)p.out_b)[i] = o2;
         }
         s += ls;
         ((v4i *)p.out)[i] = o;
@@ -582,14 +599,18 @@ extern "C" int eoq_requant_epilogue(eoq_ctx *c, const eoq_requant_args *a)
     p.acc = a->acc; p.src_a = a->src_a; p.src_b = a->src_b; p.exp_b = a->exp_b; p.gamma = a->gamma;
     p.absmax = a->absmax; p.exp_in = a->exp_in; p.exp_in_off = a->exp_in_off; p.n = a->n; p.out = a->out;
     p.exp_out = a->exp_out; p.sum_out = a->sum_out; p.max_code_out = a->max_code_out; p.status = c->d_status;
-    p.mask16 = nullptr; p.absmax_out = nullptr;
+    p.mask16 = nullptr; p.absmax_out = nullptr; p.out_b = nullptr; p.exp_out_b = nullptr; p.absmax_m = nullptr;
     if (a->mode == EOQ_RQ_SQ_MERGE) {
         // the mask is addressed in 16-element words: a ragged tail would need its own path
-        if ((a->mask_bits || a->absmax_out) && (a->n & 15)) return EOQ_ERR_SHAPE;
+        if ((a->mask_bits || a->absmax_out || a->out_b) && (a->n & 15)) return EOQ_ERR_SHAPE;
         if ((uintptr_t)a->mask_bits & 3) return EOQ_ERR_ARG;
         p.mask16 = (const uint16_t *)a->mask_bits;
         p.absmax_out = a->absmax_out;
-    } else if (a->mask_bits || a->absmax_out) {
+        if (a->out_b) {
+            if (!a->gamma || !a->exp_out_b || !aligned16(a->out_b) || (a->mask_bits && !a->absmax_masked)) return EOQ_ERR_ARG;
+            p.out_b = a->out_b; p.exp_out_b = a->exp_out_b; p.absmax_m = a->mask_bits ? a->absmax_masked : nullptr;
+        }
+    } else if (a->mask_bits || a->absmax_out || a->out_b) {
         return EOQ_ERR_ARG;
     }
     const dim3 grid(ew_blocks(a->n / 16)), block(EW_THREADS);

@@ -29,7 +29,7 @@ EXPORTS = [
 
 class BwdFuse(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("mask_bits", "e1", "sum_e1", "absmax_e1", "merge_other", "merge_exp_other",
-                                          "merge_absmax", "w_transposed")]
+                                          "merge_absmax", "w_transposed", "merge_mask_bits", "merge_absmax_masked")]
 
 
 class ConvDesc(C.Structure):
@@ -55,7 +55,8 @@ class RequantArgs(C.Structure):
                 ("src_a", C.c_void_p), ("src_b", C.c_void_p), ("exp_b", C.c_void_p), ("gamma", C.c_void_p),
                 ("absmax", C.c_void_p), ("exp_in", C.c_void_p), ("exp_in_off", C.c_int32), ("out", C.c_void_p),
                 ("exp_out", C.c_void_p), ("sum_out", C.c_void_p), ("max_code_out", C.c_void_p),
-                ("mask_bits", C.c_void_p), ("absmax_out", C.c_void_p)]
+                ("mask_bits", C.c_void_p), ("absmax_out", C.c_void_p), ("out_b", C.c_void_p),
+                ("exp_out_b", C.c_void_p), ("absmax_masked", C.c_void_p)]
 
 
 class ScalarGrad(C.Structure):
@@ -184,11 +185,12 @@ class Context:
 
     def conv_bwd_data_sq(self, desc, e, w, e4, absmax_slot, exp_in, exp_in_off, exp_out, sum_out, ws,
                          mask=None, e1=None, sum_e1=None, absmax_e1=None, merge_other=None, merge_exp_other=None,
-                         merge_absmax=None, w_transposed=None):
+                         merge_absmax=None, w_transposed=None, merge_mask=None, merge_absmax_masked=None):
         fuse = None
         if e1 is not None or merge_other is not None or w_transposed is not None:
             fuse = BwdFuse(_ptr(mask), _ptr(e1), _ptr(sum_e1), _ptr(absmax_e1), _ptr(merge_other),
-                           _ptr(merge_exp_other), _ptr(merge_absmax), _ptr(w_transposed))
+                           _ptr(merge_exp_other), _ptr(merge_absmax), _ptr(w_transposed), _ptr(merge_mask),
+                           _ptr(merge_absmax_masked))
         _check(_lib.eoq_conv_bwd_data_sq(self._h, C.byref(desc), _ptr(e), _ptr(w), _ptr(e4), _ptr(absmax_slot),
                                          _ptr(exp_in), exp_in_off, _ptr(exp_out), _ptr(sum_out),
                                          C.byref(fuse) if fuse is not None else None, _ptr(ws), _nbytes(ws)),
@@ -212,10 +214,12 @@ class Context:
 
     def requant_epilogue(self, mode, n, *, K=0, acc=None, ep=None, src_a=None, src_b=None, exp_b=None, gamma=None,
                          absmax=None, exp_in=None, exp_in_off=0, out=None, exp_out=None, sum_out=None,
-                         max_code_out=None, mask=None, absmax_out=None):
+                         max_code_out=None, mask=None, absmax_out=None, out_b=None, exp_out_b=None,
+                         absmax_masked=None):
         a = RequantArgs(mode, K, n, _ptr(acc), C.addressof(ep) if ep is not None else None, _ptr(src_a), _ptr(src_b),
                         _ptr(exp_b), _ptr(gamma), _ptr(absmax), _ptr(exp_in), exp_in_off, _ptr(out), _ptr(exp_out),
-                        _ptr(sum_out), _ptr(max_code_out), _ptr(mask), _ptr(absmax_out))
+                        _ptr(sum_out), _ptr(max_code_out), _ptr(mask), _ptr(absmax_out), _ptr(out_b), _ptr(exp_out_b),
+                        _ptr(absmax_masked))
         _check(_lib.eoq_requant_epilogue(self._h, C.byref(a)), "eoq_requant_epilogue")
 
     def update_int8(self, w, g, g_exp_slot, g_max_code, lr_slot):

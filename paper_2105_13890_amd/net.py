@@ -95,6 +95,7 @@ class FixupNet:
         self._synced = -1                       # the main stream has waited for _side_ev[: _synced + 1]
         self._last_gdone = None                 # event after the latest multiplier-gradient sum of this step
         self._deferred = None                   # (layer, weight-gradient sums) whose update has not been enqueued yet
+        self.ev_fwd = [torch.cuda.Event(), torch.cuda.Event()]      # fork / join of the two forward half-batch chains
         self.trace: dict[str, object] = {}
         self.prof = None                   # list of (kind, unit, work, start event, end event) while profiling
         bt = cfg["block"]
@@ -272,6 +273,7 @@ class FixupNet:
                 for nm in (d.E4, d.name + ".Eg", d.name + ".M_D", d.name + ".M_G", d.name + ".gmax"):
                     sl.i32(nm)
             sl.i32(b.name + ".M_in")
+            sl.i32(b.name + ".M_inm")
             e_name = b.name + ".E_in"
             sl.i32(e_name)
         if self.stem:
@@ -346,14 +348,27 @@ class FixupNet:
         return 2.0 * d.N * d.P * d.Q * d.K * d.C * d.R * d.S       # algorithmic ops (multiply-add = 2)
 
     # ------------------------------------------------------------------------------------------ forward
-    def _unit_fwd(self, u: Unit, skip=None, y=None, u_next=None, b_next=None, side=False):
+    def _unit_fwd(self, u: Unit, skip=None, y=None, u_next=None, b_next=None, side=False, half=None):
+        """One forward convolution with its fused epilogue (Eq.2).  half = 0 / 1: only that half of the batch (every
+        tensor is batch-major, so a half is a contiguous slice), on the main / side stream."""
+        side = side or half == 1
         c, ws, st = (self.ctx_w, self.ws_w, self.side) if side else (self.ctx, self.ws, self.main)
+        desc, sl = u.desc, (lambda t: t)
+        if half is not None:
+            d = u.desc
+            desc = eoq.ConvDesc(d.N // 2, d.H, d.W, d.C, d.K, d.R, d.S, d.stride, d.pad)
+
+            def sl(t):
+                if t is None:
+                    return None
+                n = t.numel() // 2
+                return t.view(-1)[half * n:(half + 1) * n]
         if not u.relu:
-            ep = c.epilogue(relu=0, t_wide=u.t)
+            ep = c.epilogue(relu=0, t_wide=sl(u.t))
         else:
-            ep = c.epilogue(gamma=self.sc(u.gamma), b_post=self.sc(u.b_post), skip=skip, relu=1,
-                            b_next_pre=self.sc(b_next), y=y, u_next=u_next, mask=u.mask, t_wide=u.t)
-        self._call("conv_fwd", u.name, self._conv_work(u), c.conv_fwd, u.desc, u.u, u.w, ep=ep, ws=ws, stream=st)
+            ep = c.epilogue(gamma=self.sc(u.gamma), b_post=self.sc(u.b_post), skip=sl(skip), relu=1,
+                            b_next_pre=self.sc(b_next), y=sl(y), u_next=sl(u_next), mask=sl(u.mask), t_wide=sl(u.t))
+        self._call("conv_fwd", u.name, self._conv_work(u), c.conv_fwd, desc, sl(u.u), u.w, ep=ep, ws=ws, stream=st)
         if self.tracing:
             self._rec(u.name + ".u", u.u)
             if u.t is not None:
@@ -363,32 +378,53 @@ class FixupNet:
                 if y is not None:
                     self._rec(u.name + ".y", y)
 
+    def _can_split_forward(self):
+        """Nothing in the forward pass of the blocks looks across images, so the two halves of the batch can run as
+        two independent chains.  Needs an even batch and mask words that do not straddle the halves."""
+        return (self.overlap and not self.tracing and self.N % 2 == 0 and
+                all(int(np.prod(u.out_shape)) % 64 == 0 for b in self.blocks for u in b.units))
+
     def _forward_blocks(self):
+        if self._can_split_forward():
+            # two half-batch chains, one per stream: a convolution of this size leaves the chip partly idle while it
+            # starts and drains, and a chain of dependent launches cannot hide that; two independent chains can
+            self.ev_fwd[0].record(self.main)
+            self.side.wait_event(self.ev_fwd[0])
+            for bi, b in enumerate(self.blocks):
+                nxt = self.blocks[bi + 1] if bi + 1 < len(self.blocks) else None
+                for half in (0, 1):
+                    self._forward_block(b, nxt, half)
+            self.ev_fwd[1].record(self.side)
+            self.main.wait_event(self.ev_fwd[1])
+            return
         for bi, b in enumerate(self.blocks):
-            nxt = self.blocks[bi + 1] if bi + 1 < len(self.blocks) else None
-            if b.ds:
-                # the shortcut convolution only meets the branch at the block's last layer: it runs beside the
-                # branch on the side stream (it is bound by its wide stores, the branch's first layers are not)
-                if self.overlap:
-                    b.ds.ev_e3.record(self.main)
-                    self.side.wait_event(b.ds.ev_e3)
-                self._unit_fwd(b.ds, side=self.overlap)
-                if self.overlap:
-                    b.ds.ev_dx.record(self.side)
-            for i, u in enumerate(b.units):
-                last = i == len(b.units) - 1
-                if not last:
-                    n_u = b.units[i + 1]
-                    self._unit_fwd(u, u_next=n_u.u, b_next=n_u.b_pre, y=self._dbg_y(u))
+            self._forward_block(b, self.blocks[bi + 1] if bi + 1 < len(self.blocks) else None, None)
+
+    def _forward_block(self, b, nxt, half):
+        fork = b.ds is not None and self.overlap and half is None
+        if b.ds:
+            # whole-batch chain: the shortcut convolution only meets the branch at the block's last layer, so it runs
+            # beside the branch on the side stream (it is bound by its wide stores, the branch's first layers are not)
+            if fork:
+                b.ds.ev_e3.record(self.main)
+                self.side.wait_event(b.ds.ev_e3)
+            self._unit_fwd(b.ds, side=fork, half=half)
+            if fork:
+                b.ds.ev_dx.record(self.side)
+        for i, u in enumerate(b.units):
+            last = i == len(b.units) - 1
+            if not last:
+                n_u = b.units[i + 1]
+                self._unit_fwd(u, u_next=n_u.u, b_next=n_u.b_pre, y=self._dbg_y(u), half=half)
+            else:
+                if fork:
+                    self.main.wait_event(b.ds.ev_dx)
+                skip = b.ds.t if b.ds else b.a_in
+                if nxt is not None:
+                    self._unit_fwd(u, skip=skip, y=nxt.a_in if nxt.a_in is not None else self._dbg_y(u),
+                                   u_next=nxt.units[0].u, b_next=nxt.units[0].b_pre, half=half)
                 else:
-                    if b.ds and self.overlap:
-                        self.main.wait_event(b.ds.ev_dx)
-                    skip = b.ds.t if b.ds else b.a_in
-                    if nxt is not None:
-                        self._unit_fwd(u, skip=skip, y=nxt.a_in if nxt.a_in is not None else self._dbg_y(u),
-                                       u_next=nxt.units[0].u, b_next=nxt.units[0].b_pre)
-                    else:
-                        self._unit_fwd(u, skip=skip, y=self.y_out)
+                    self._unit_fwd(u, skip=skip, y=self.y_out, half=half)
 
     def _dbg_y(self, u):
         """Unbiased int8 output of an inner layer: only materialised when tracing (tests compare it)."""
@@ -492,20 +528,24 @@ class FixupNet:
                    e1[:n_out], None, None, None, self.s64(u.name + ".S_e1t"), None, stream=st)
 
     def _unit_bwd(self, u: Unit, e0, bufs, need_dx=True, relu_done=False, fuse_below: Unit | None = None,
-                  merge=None):
+                  merge=None, e3_done=None):
         """Eq.3 / Eq.4 for one layer; e0 is overwritten by e1.  Returns (buffer with the error for the layer
         below or None, e1).  relu_done: e0 already is e1 (the ReLU backward step was fused into the call that
         produced it).  fuse_below: the layer whose output is this layer's input -- its ReLU backward step and
         sums are applied by this layer's backward-data call, which then returns e1 of that layer instead of e4.
         merge = (other error buffer, its exponent slot, abs-max slot): this layer's e4 is one of the two errors
-        that meet at the block input; the statistics of their sum are taken by the same call."""
+        that meet at the block input; the statistics of their sum are taken by the same call (a fourth and fifth
+        entry: the mask of the layer receiving the merged error and the slot for the maximum under that mask).
+        e3_done: buffer that already holds Q_e(e1 * gamma) (written by the merge pass that produced e1)."""
         c = self.ctx
         n_out = int(np.prod(u.out_shape))
         e1 = e0
         if u.relu and not relu_done:
             c.relu_bwd(e0[:n_out], u.mask, None, e1[:n_out], self.s64(u.name + ".S_e1"), None,
                        self.s32(u.name + ".M_e1"))
-        if u.gamma:
+        if u.gamma and e3_done is not None:
+            e3 = e3_done
+        elif u.gamma:
             e3 = self._acquire(bufs)
             c.requant_epilogue(eoq.RQ_SQ_GAMMA, n_out, src_a=e1[:n_out], gamma=self.sc(u.gamma),
                                absmax=self.s32(u.name + ".M_e1"), exp_in=self.s32(u.E0), out=e3[:n_out],
@@ -534,6 +574,8 @@ class FixupNet:
                 if merge is not None:
                     mg = dict(merge_other=merge[0][:n_in], merge_exp_other=self.s32(merge[1]),
                               merge_absmax=self.s32(merge[2]))
+                    if len(merge) > 3:
+                        mg.update(merge_mask=merge[3], merge_absmax_masked=self.s32(merge[4]))
                 self._call("conv_bwd_data", u.name, self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
                            e4[:n_in], self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
                            self.s64(u.name + ".S_e4"), self.ws, w_transposed=u.wt, **mg)
@@ -552,20 +594,25 @@ class FixupNet:
         """e: buffer holding the error at the last block's output (exponent slot self.E_top)."""
         c = self.ctx
         masked = False                     # the error handed down already went through the receiving layer's ReLU
+        e3_low = None                      # ... and Q_e(e1 * gamma) of that layer exists as well
         for bi in range(len(self.blocks) - 1, -1, -1):
             b = self.blocks[bi]
             assert len(b.units) >= 2
             last = b.units[-1]
+            # the layer that receives this block's merged input error: the last layer of the block below.  Its ReLU
+            # backward step (mask, bias-gradient sum) and its Q_e(e1 * gamma) ride on the merge pass
+            low = self.blocks[bi - 1].units[-1] if bi > 0 and not self.tracing else None
+            M_in, M_inm = b.name + ".M_in", b.name + ".M_inm"
+            mstat = (low.mask, M_inm) if low is not None else ()
             # e now holds e1 of the last layer = shortcut error; its backward-data call already applies the ReLU
             # backward step of the layer below it, and so on down the branch
             e4, e_sk = self._unit_bwd(last, e, bufs, relu_done=masked,
-                                      fuse_below=b.units[-2] if len(b.units) > 1 else None)
+                                      fuse_below=b.units[-2] if len(b.units) > 1 else None, e3_done=e3_low)
             E_sk = last.E0
             cur = e4
-            M_in = b.name + ".M_in"
             for idx in range(len(b.units) - 2, -1, -1):
                 # the first layer's e4 meets the shortcut error at the block input (identity shortcut: e_sk itself)
-                mg = (e_sk, E_sk, M_in) if (idx == 0 and not b.ds) else None
+                mg = (e_sk, E_sk, M_in) + mstat if (idx == 0 and not b.ds) else None
                 nxt, _ = self._unit_bwd(b.units[idx], cur, bufs, relu_done=True,
                                         fuse_below=b.units[idx - 1] if idx > 0 else None, merge=mg)
                 bufs.append(cur)
@@ -573,19 +620,19 @@ class FixupNet:
             first = b.units[0]
             n_in = int(np.prod(first.in_shape))
             if b.ds:
-                e4d, _ = self._unit_bwd(b.ds, e_sk, bufs, merge=(cur, first.E4, M_in))
+                e4d, _ = self._unit_bwd(b.ds, e_sk, bufs, merge=(cur, first.E4, M_in) + mstat)
                 other, E_other = e4d, b.ds.E4
             else:
                 other, E_other = e_sk, E_sk
             out = cur
-            # Q_e of the merged error; when a block lies below, the same pass applies the ReLU backward step of
-            # that block's last layer (its mask, its bias-gradient sum, the abs-max for Q_e(e1 * gamma))
-            low = self.blocks[bi - 1].units[-1] if bi > 0 and not self.tracing else None
             extra = {}
+            e3_low = None
             if low is not None:
-                extra = dict(mask=low.mask, sum_out=self.s64(low.name + ".S_e1"), absmax_out=self.s32(low.name + ".M_e1"))
+                e3_low = self._acquire(bufs)
+                extra = dict(mask=low.mask, sum_out=self.s64(low.name + ".S_e1"), gamma=self.sc(low.gamma),
+                             out_b=e3_low[:n_in], exp_out_b=self.s32(low.E3), absmax_masked=self.s32(M_inm))
             c.requant_epilogue(eoq.RQ_SQ_MERGE, n_in, src_a=cur[:n_in], src_b=other[:n_in], exp_in=self.s32(first.E4),
-                               exp_b=self.s32(E_other), absmax=self.s32(b.name + ".M_in"), out=out[:n_in],
+                               exp_b=self.s32(E_other), absmax=self.s32(M_in), out=out[:n_in],
                                exp_out=self.s32(b.name + ".E_in"), **extra)
             masked = low is not None
             if b.ds:

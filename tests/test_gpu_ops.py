@@ -202,15 +202,17 @@ def _bwd_data_sq_case(ctx, d, e, w, with_mask):
     else:
         # with the statistics of the block-input merge against another error tensor on a coarser grid
         other = si.uniform_int8(6, "other", ishape)
-        mg = dev(np.array([-17, 0], dtype=np.int32))
+        mg = dev(np.array([-17, 0, 0], dtype=np.int32))
         other_d = dev(other)
         ctx.conv_bwd_data_sq(desc_of(d), dev(e), dev(w), e4, sl[0:1], sl[1:2], -7, sl[2:3], sums[0:1],
                              ws_for(d, eoq.OP_CONV_BWD_DATA), merge_other=other_d, merge_exp_other=mg[0:1],
-                             merge_absmax=mg[1:2])
+                             merge_absmax=mg[1:2], merge_mask=mask, merge_absmax_masked=mg[2:3])
         e4c, E4c = oo.sq_acc(want, -13 - 7)
         Em = min(E4c, -17)
         merged = e4c.astype(np.int64) * (1 << (E4c - Em)) + other.astype(np.int64) * (1 << (-17 - Em))
         assert int(host(mg)[1]) == int(np.abs(merged).max())
+        # the same maximum under the receiving layer's mask
+        assert int(host(mg)[2]) == int(np.abs(merged * maskb.reshape(ishape)).max())
     e4o, E4o = oo.sq_acc(want, -13 - 7)
     assert np.array_equal(host(e4), e4o) and int(host(sl)[2]) == E4o
     assert int(host(sl)[0]) == int(np.abs(want).max())
@@ -292,7 +294,7 @@ def test_relu_bwd_and_sq_passes(ctx, n):
                np.frombuffer(np.packbits(maskb, bitorder="little").tobytes() + b"\0\0", dtype=np.int32))
     e1 = zeros((n,), torch.int8)
     sums = zeros((4,), torch.int64)
-    slots = zeros((10,), torch.int32)
+    slots = zeros((12,), torch.int32)
     ctx.relu_bwd(dev(e0), mask, dev(t), e1, sums[0:1], sums[1:2], slots[0:1])
     e1o = (e0.astype(np.int64) * maskb).astype(np.int8)
     assert np.array_equal(host(e1), e1o)
@@ -341,6 +343,22 @@ def test_relu_bwd_and_sq_passes(ctx, n):
             assert np.array_equal(host(out), e1m) and int(host(slots)[7]) == Em
             assert int(host(st)[0]) == int(e1m.astype(np.int64).sum())
             assert int(host(slots)[8]) == int(np.abs(e1m.astype(np.int64)).max())
+            # ... and with Q_e(e1 * gamma) as a second output of the pass (the largest masked merged value comes
+            # from the backward-data call in the network; here from the definition)
+            Emn = min(Ea, Eb)
+            mv = ea.astype(np.int64) * (1 << (Ea - Emn)) + eb.astype(np.int64) * (1 << (Eb - Emn))
+            for gcode, msk in ((117, mk), (-3, mk), (128, None), (0, mk)):
+                mbb = mb if msk is not None else np.ones_like(mb)
+                slots[9] = int(np.abs(mv * mbb).max())
+                gd = dev(np.array([gcode], dtype=np.int32))
+                out2 = zeros((n,), torch.int8)
+                ctx.requant_epilogue(eoq.RQ_SQ_MERGE, n, src_a=dev(ea), src_b=dev(eb), exp_in=ex[0:1], exp_b=ex[1:2],
+                                     absmax=slots[6:7], out=out, exp_out=slots[7:8], mask=msk, gamma=gd, out_b=out2,
+                                     exp_out_b=slots[10:11], absmax_masked=slots[9:10] if msk is not None else None)
+                e1x = (em.astype(np.int64) * mbb).astype(np.int8)
+                e3x, E3x = oo.sq_error_gamma(e1x, Em, gcode)
+                assert np.array_equal(host(out), e1x) and int(host(slots)[7]) == Em
+                assert np.array_equal(host(out2), e3x) and int(host(slots)[10]) == E3x, (gcode, Ea, Eb)
     # all-zero tensors keep their exponent
     slots[3] = 0
     ctx.requant_epilogue(eoq.RQ_SQ_ACC, n, acc=zeros((n,), torch.int32), absmax=slots[3:4], exp_in=slots[1:2],
