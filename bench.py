@@ -158,7 +158,9 @@ def main():
         "config": {"workload": f"Fixup {wl} full-int8 training step, batch {N}, {cfg['in_hw']}x{cfg['in_hw']}x3 "
                                f"~N(0,1) inputs, {cfg['classes']} classes, lr={lr_m}*2^{-lr_j}", "global_batch": N,
                    "launch": "eager" if graph is None else "hip graph replay (one graph = one step)",
-                   "streams": 1 if args.no_overlap else 2},
+                   "streams": 1 if args.no_overlap else 2,
+                   "stream_use": "one stream" if args.no_overlap else
+                                 "forward of the blocks: two half-batch chains; backward: error chain | weight-gradient chain"},
         "loss": loss,
         "device_flags": flags,
         "conv_tops_all": round(tot_ops / (tot_ms * 1e-3) / 1e12, 2),
@@ -174,7 +176,9 @@ def main():
                      "algorithmic_bytes_per_launch": round(fwd_bytes / fwd[2]),
                      "hbm_gbs_at_algorithmic_bytes": round(fwd_bytes / (fwd[1] * 1e-3) / 1e9, 1),
                      "note": "int8 multiply-add counted as 2 ops; algorithmic ops 2*N*P*Q*K*C*R*S summed over the forward "
-                             "launches of one step divided by their summed event-timed durations; traffic = measured HBM "
+                             "launches of one step divided by their summed event-timed durations, taken in one extra step "
+                             "launched eagerly on ONE stream with whole-batch launches (the timed steps run the same kernel "
+                             "on half batches in two concurrent chains, where a launch's duration is not its own); traffic = measured HBM "
                              "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy); measured MFMA "
                              "ceilings on this chip: 4.9 POP/s with all-zero operands, 3.3 POP/s with random int8 operands "
                              "(power-limited)"},

@@ -298,10 +298,13 @@ int eoq_maxpool_bwd(eoq_ctx *ctx, const uint8_t *arg, const int8_t *e, int32_t N
                     int32_t R, int32_t S, int32_t stride, int32_t pad, int32_t *d, int32_t *absmax_slot);
 /* The same sums followed by Q_e (Eq.11) without the int32 tensor: the sums are formed twice, first for max|d|
  * (max-combined into *absmax_slot, which must hold 0 or a valid partial maximum), then for the codes
- * e_out = SQ(d) with *exp_out = *exp_in + R(log2 max|d|) - 7 (all-zero d: codes 0, exponent passed through). */
+ * e_out = SQ(d) with *exp_out = *exp_in + R(log2 max|d|) - 7 (all-zero d: codes 0, exponent passed through).
+ * mask_bits (may be NULL; one bit per element of e_out, 4-byte aligned): the ReLU backward step of the layer whose
+ * output was pooled (Eq.3 line e1) in the same pass -- e_out = code where the bit is set, 0 elsewhere; *sum_out
+ * (may be NULL) += sum of the codes written (the bias gradient of Eq.4). */
 int eoq_maxpool_bwd_sq(eoq_ctx *ctx, const uint8_t *arg, const int8_t *e, int32_t N, int32_t H, int32_t W, int32_t C,
                        int32_t R, int32_t S, int32_t stride, int32_t pad, int8_t *e_out, int32_t *absmax_slot,
-                       const int32_t *exp_in, int32_t *exp_out);
+                       const int32_t *exp_in, int32_t *exp_out, const uint32_t *mask_bits, int64_t *sum_out);
 /* Global average pool, integer part: sum[n][c] = sum_{h,w} y[n,h,w,c]. */
 int eoq_gap_sum(eoq_ctx *ctx, const int8_t *y, int32_t N, int32_t HW, int32_t C, int32_t *sum);
 /* e[n,h,w,c] = codes[n][c] for all HW positions (error of the average pool, already quantised). */

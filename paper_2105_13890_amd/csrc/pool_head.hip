@@ -71,11 +71,13 @@ __global__ void maxpool_fwd_kernel(PoolGeom g, const int8_t *a, int8_t *y, const
 // written.
 template <int OUT>
 __global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t *e, int32_t *d, int32_t *absmax,
-                                   int8_t *q, const int32_t *exp_in, int32_t *exp_out)
+                                   int8_t *q, const int32_t *exp_in, int32_t *exp_out, const uint16_t *mask16,
+                                   int64_t *sum_out)
 {
     const int c16 = g.C / 16;
     const size_t total = (size_t)g.N * g.H * g.W * c16;
     int mx = 0, r = 7;
+    long long sum = 0;
     if (OUT == 2) {
         const uint32_t M = (uint32_t)*absmax;
         r = M ? sq_exponent_u32(M) : 7;
@@ -118,8 +120,15 @@ __global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t 
         }
         if (OUT == 2) {
             v4i o = {0, 0, 0, 0};
+            const uint32_t mk = mask16 ? (uint32_t)mask16[pix * c16 + cc] : 0xffffu;
+            int ls = 0;
 #pragma unroll
-            for (int k = 0; k < 16; ++k) set_byte(o, k, sq_code((int64_t)acc[k], r));
+            for (int k = 0; k < 16; ++k) {
+                const int cd = ((mk >> k) & 1u) ? sq_code((int64_t)acc[k], r) : 0;
+                set_byte(o, k, cd);
+                ls += cd;
+            }
+            sum += ls;
             *(v4i *)(q + pix * g.C + cc * 16) = o;
         } else {
 #pragma unroll
@@ -130,6 +139,86 @@ __global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t 
         }
     }
     if (OUT != 2) block_atomic_max_i32(mx, absmax);
+    if (OUT == 2 && sum_out) block_atomic_add_i64(sum, sum_out);
+}
+
+// The 3x3 / stride 2 / padding 1 pool of the ImageNet-shaped nets: a lane owns 16 channels of a 2x2 block of input
+// pixels (rows 2i, 2i+1, columns 2j, 2j+1).  The block lies in the four windows (i | i+1, j | j+1) and in no other,
+// so each window's error and winner index are fetched once for four pixels.  OUT 1: abs-max of the sums; OUT 2: codes.
+template <int OUT>
+__global__ void __launch_bounds__(256) maxpool_bwd_3s2_kernel(PoolGeom g, const uint8_t *arg, const int8_t *e, int32_t *absmax, int8_t *q,
+                                       const int32_t *exp_in, int32_t *exp_out, const uint16_t *mask16,
+                                       int64_t *sum_out)
+{
+    const int c16 = g.C / 16;
+    const int H2 = (g.H + 1) / 2, W2 = (g.W + 1) / 2;
+    const size_t total = (size_t)g.N * H2 * W2 * c16;
+    int mx = 0, r = 7;
+    long long sum = 0;
+    if (OUT == 2) {
+        const uint32_t M = (uint32_t)*absmax;
+        r = M ? sq_exponent_u32(M) : 7;
+        if (blockIdx.x == 0 && threadIdx.x == 0) *exp_out = M ? *exp_in + r - 7 : *exp_in;
+    }
+    for (size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i0 < total; i0 += (size_t)gridDim.x * blockDim.x) {
+        const int cc = (int)(i0 % c16);
+        size_t t = i0 / c16;
+        const int j = (int)(t % W2); t /= W2;
+        const int i = (int)(t % H2), n = (int)(t / H2);
+        int acc[4][16];
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) acc[b][k] = 0;
+#pragma unroll
+        for (int dp = 0; dp < 2; ++dp)
+#pragma unroll
+            for (int dq = 0; dq < 2; ++dq) {
+                const int p = i + dp, qq = j + dq;
+                if (p >= g.P || qq >= g.Q) continue;
+                const size_t o = (((size_t)n * g.P + p) * g.Q + qq) * g.C + cc * 16;
+                const v4i av = *(const v4i *)(arg + o), ev = *(const v4i *)(e + o);
+                // pixel (2i+a, 2j+b) is cell (a + 1 - 2dp, b + 1 - 2dq) of window (p, qq)
+#pragma unroll
+                for (int a = dp; a < 2; ++a)
+#pragma unroll
+                    for (int b = dq; b < 2; ++b) {
+                        const int my = (a + 1 - 2 * dp) * 3 + (b + 1 - 2 * dq);
+#pragma unroll
+                        for (int k = 0; k < 16; ++k)
+                            if ((byte_at(av, k) & 0xff) == my) acc[a * 2 + b][k] += byte_at(ev, k);
+                    }
+            }
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int h = 2 * i + a, x = 2 * j + b;
+                if (h >= g.H || x >= g.W) continue;
+                if (OUT == 2) {
+                    const size_t pix = ((size_t)n * g.H + h) * g.W + x;
+                    const uint32_t mk = mask16 ? (uint32_t)mask16[pix * c16 + cc] : 0xffffu;
+                    v4i o = {0, 0, 0, 0};
+                    int ls = 0;
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const int cd = ((mk >> k) & 1u) ? sq_code((int64_t)acc[a * 2 + b][k], r) : 0;
+                        set_byte(o, k, cd);
+                        ls += cd;
+                    }
+                    sum += ls;
+                    *(v4i *)(q + pix * g.C + cc * 16) = o;
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const int v = acc[a * 2 + b][k] < 0 ? -acc[a * 2 + b][k] : acc[a * 2 + b][k];
+                        mx = v > mx ? v : mx;
+                    }
+                }
+            }
+    }
+    if (OUT == 1) block_atomic_max_i32(mx, absmax);
+    if (OUT == 2 && sum_out) block_atomic_add_i64(sum, sum_out);
 }
 
 __global__ void gap_sum_kernel(const int8_t *y, int N, int HW, int C, int32_t *sum)
@@ -407,27 +496,40 @@ extern "C" int eoq_maxpool_bwd(eoq_ctx *c, const uint8_t *arg, const int8_t *e, 
     PoolGeom g{N, H, W, C, R, S, stride, pad, conv_out_dim(H, pad, R, stride), conv_out_dim(W, pad, S, stride)};
     if (g.P <= 0 || g.Q <= 0) return EOQ_ERR_SHAPE;
     hipLaunchKernelGGL(maxpool_bwd_kernel<0>, dim3(grid_for((size_t)N * H * W * (C / 16))), dim3(256), 0, c->stream, g,
-                       arg, e, d, absmax_slot, (int8_t *)nullptr, (const int32_t *)nullptr, (int32_t *)nullptr);
+                       arg, e, d, absmax_slot, (int8_t *)nullptr, (const int32_t *)nullptr, (int32_t *)nullptr,
+                       (const uint16_t *)nullptr, (int64_t *)nullptr);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }
 
 extern "C" int eoq_maxpool_bwd_sq(eoq_ctx *c, const uint8_t *arg, const int8_t *e, int32_t N, int32_t H, int32_t W,
                                   int32_t C, int32_t R, int32_t S, int32_t stride, int32_t pad, int8_t *e_out,
-                                  int32_t *absmax_slot, const int32_t *exp_in, int32_t *exp_out)
+                                  int32_t *absmax_slot, const int32_t *exp_in, int32_t *exp_out,
+                                  const uint32_t *mask_bits, int64_t *sum_out)
 {
     if (!c || !arg || !e || !e_out || !absmax_slot || !exp_in || !exp_out || N <= 0 || H <= 0 || W <= 0 || C <= 0 ||
         R <= 0 || S <= 0 || stride <= 0 || pad < 0)
         return EOQ_ERR_ARG;
     if (C % 16 || pad >= R || pad >= S) return EOQ_ERR_SHAPE;
-    if (((uintptr_t)arg | (uintptr_t)e | (uintptr_t)e_out) & 15) return EOQ_ERR_ARG;
+    if (((uintptr_t)arg | (uintptr_t)e | (uintptr_t)e_out) & 15 || ((uintptr_t)mask_bits & 3)) return EOQ_ERR_ARG;
     PoolGeom g{N, H, W, C, R, S, stride, pad, conv_out_dim(H, pad, R, stride), conv_out_dim(W, pad, S, stride)};
     if (g.P <= 0 || g.Q <= 0) return EOQ_ERR_SHAPE;
+    const uint16_t *mask16 = (const uint16_t *)mask_bits;
     const dim3 grid(grid_for((size_t)N * H * W * (C / 16)));
-    hipLaunchKernelGGL(maxpool_bwd_kernel<1>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr, absmax_slot,
-                       (int8_t *)nullptr, (const int32_t *)nullptr, (int32_t *)nullptr);
+    if (R == 3 && S == 3 && stride == 2 && pad == 1) {
+        // the abs-max pass gains from fetching each window once per 2x2 block of pixels; the coding pass does not:
+        // its stores want consecutive lanes on consecutive pixels
+        const dim3 grid2(grid_for((size_t)N * ((H + 1) / 2) * ((W + 1) / 2) * (C / 16)));
+        hipLaunchKernelGGL(maxpool_bwd_3s2_kernel<1>, grid2, dim3(256), 0, c->stream, g, arg, e, absmax_slot,
+                           (int8_t *)nullptr, (const int32_t *)nullptr, (int32_t *)nullptr, (const uint16_t *)nullptr,
+                           (int64_t *)nullptr);
+    } else {
+        hipLaunchKernelGGL(maxpool_bwd_kernel<1>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr,
+                           absmax_slot, (int8_t *)nullptr, (const int32_t *)nullptr, (int32_t *)nullptr,
+                           (const uint16_t *)nullptr, (int64_t *)nullptr);
+    }
     hipLaunchKernelGGL(maxpool_bwd_kernel<2>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr, absmax_slot,
-                       e_out, exp_in, exp_out);
+                       e_out, exp_in, exp_out, mask16, sum_out);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }

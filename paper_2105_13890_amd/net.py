@@ -647,16 +647,20 @@ class FixupNet:
         c = self.ctx
         s = self.stem
         d = s.desc
+        masked = False
         if self.pool:
             n = int(np.prod(s.out_shape))
             e2 = self._acquire(bufs)
+            # pool backward + Q_e; outside tracing also the stem's ReLU backward step (its mask, its bias-gradient sum)
+            fuse = {} if self.tracing else dict(mask=s.mask, sum_out=self.s64(s.name + ".S_e1"))
             c.maxpool_bwd_sq(self.pool_arg, e, d.N, d.P, d.Q, d.K, 3, 3, 2, 1, e2[:n], self.s32("pool.M"),
-                             self.s32(self.blocks[0].name + ".E_in"), self.s32("pool.E"))
+                             self.s32(self.blocks[0].name + ".E_in"), self.s32("pool.E"), **fuse)
+            masked = not self.tracing
             bufs.append(e)
             e = e2
             if self.tracing:
                 self._rec("pool.e", e[:n].view(s.out_shape))
-        self._unit_bwd(s, e, bufs, need_dx=False)
+        self._unit_bwd(s, e, bufs, need_dx=False, relu_done=masked)
         bufs.append(e)
 
     def _update_scalars(self):

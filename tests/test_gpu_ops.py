@@ -448,6 +448,28 @@ def test_pool_gap_broadcast(ctx):
         ctx.maxpool_bwd_sq(argd, dev(ee), N, H, W, Cc, 3, 3, 2, 1, q, slot2, ex[0:1], ex[1:2])
         codes, E_out = oq.sq_int(oo.maxpool_bwd(ee, arg, a.shape), E_in)
         assert np.array_equal(host(q), codes) and int(host(ex)[1]) == E_out
+    # other extents and window geometries (the 3x3 / stride 2 / padding 1 pool has a kernel of its own), with the ReLU
+    # backward step of the pooled layer in the same pass
+    for (H2, W2, R, S, st, pad) in ((13, 15, 3, 3, 2, 1), (12, 16, 3, 3, 2, 1), (2, 2, 3, 3, 2, 1), (9, 8, 2, 2, 2, 0),
+                                    (7, 7, 3, 3, 1, 1)):
+        a2 = si.uniform_int8(9, "a2", (N, H2, W2, Cc), -6, 6)
+        y2, arg2 = oo.maxpool_fwd(a2, R, S, st, pad)
+        e2 = si.uniform_int8(9, "e2", y2.shape)
+        mb = (si.words(9, "poolmask", a2.size) & np.uint64(1)).astype(bool)
+        pk = np.packbits(mb, bitorder="little")
+        mk = dev(np.frombuffer(pk.tobytes() + b"\0" * (-len(pk) % 4), dtype=np.int32))
+        for use_mask in (False, True):
+            q, slot2, sm = zeros(a2.shape, torch.int8), zeros((1,), torch.int32), zeros((1,), torch.int64)
+            ex = dev(np.array([-9, 99], dtype=np.int32))
+            ctx.maxpool_bwd_sq(dev(arg2), dev(e2), N, H2, W2, Cc, R, S, st, pad, q, slot2, ex[0:1], ex[1:2],
+                               mask=mk if use_mask else None, sum_out=sm)
+            want2 = oo.maxpool_bwd(e2, arg2, a2.shape, R, S, st, pad)
+            codes, E_out = oq.sq_int(want2, -9)
+            if use_mask:
+                codes = codes * mb.reshape(a2.shape)
+            assert np.array_equal(host(q), codes) and int(host(ex)[1]) == E_out, (H2, W2, R, S, st, pad, use_mask)
+            assert int(host(slot2)[0]) == int(np.abs(want2).max())
+            assert int(host(sm)[0]) == int(codes.astype(np.int64).sum())
     s = zeros((N, Cc), torch.int32)
     ctx.gap_sum(dev(a), N, H * W, Cc, s)
     assert np.array_equal(host(s), a.astype(np.int64).sum(axis=(1, 2)))
