@@ -312,31 +312,62 @@ __global__ void wgrad_finalize_kernel(const int32_t *part, size_t part_stride, i
     if (bad) atomicOr(status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);
 }
 
-// the same for few partial buffers and contiguous rows: one lane owns 4 consecutive elements and issues
-// the loads of all buffers back to back
-__global__ void wgrad_finalize_direct_kernel(const int32_t *part, size_t part_stride, int splits, size_t total4,
-                                             int32_t *g, int32_t *absmax, uint32_t *status)
+// contiguous partial buffers (the usual case): a lane owns 4 consecutive elements and sums every SL-th buffer, four
+// loads in flight at a time; the SL lanes of a group combine through LDS.  Many loads in flight matter more than
+// anything else here: the data is a few megabytes, the kernel's time is memory latency.
+template <int SL>
+__global__ void __launch_bounds__(256) wgrad_finalize_v4_kernel(const int32_t *part, size_t part_stride, int splits,
+                                                                size_t total4, int32_t *g, int32_t *absmax,
+                                                                uint32_t *status)
 {
+    constexpr int QB = 256 / SL;
+    __shared__ long long red[SL > 1 ? 256 * 4 : 4];
+    const int tx = threadIdx.x % QB, ty = threadIdx.x / QB;
     int mx = 0;
     bool bad = false;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total4; i += (size_t)gridDim.x * blockDim.x) {
+    for (size_t q0 = (size_t)blockIdx.x * QB; q0 < total4; q0 += (size_t)gridDim.x * QB) {
+        const size_t q = q0 + tx;
         long long s[4] = {0, 0, 0, 0};
-        for (int sp = 0; sp < splits; ++sp) {
-            const v4i v = *(const v4i *)(part + (size_t)sp * part_stride + i * 4);
+        if (q < total4) {
+            const int32_t *src = part + q * 4;
+            int sp = ty;
+            for (; sp + 3 * SL < splits; sp += 4 * SL) {
+                const v4i a = *(const v4i *)(src + (size_t)sp * part_stride);
+                const v4i b = *(const v4i *)(src + (size_t)(sp + SL) * part_stride);
+                const v4i c = *(const v4i *)(src + (size_t)(sp + 2 * SL) * part_stride);
+                const v4i d = *(const v4i *)(src + (size_t)(sp + 3 * SL) * part_stride);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) s[e] += v[e];
-        }
-        v4i o;
+                for (int e = 0; e < 4; ++e) s[e] += (long long)a[e] + b[e] + c[e] + d[e];
+            }
+            for (; sp < splits; sp += SL) {
+                const v4i a = *(const v4i *)(src + (size_t)sp * part_stride);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            long long t = s[e];
-            if (t > 2147483647LL || t < -2147483648LL) { bad = true; t = t > 0 ? 2147483647LL : -2147483647LL; }
-            o[e] = (int)t;
-            const long long a = t < 0 ? -t : t;
-            const int ai = a > 2147483647LL ? 2147483647 : (int)a;
-            mx = ai > mx ? ai : mx;
+                for (int e = 0; e < 4; ++e) s[e] += a[e];
+            }
         }
-        *(v4i *)(g + i * 4) = o;
+        if (SL > 1) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) red[(ty * QB + tx) * 4 + e] = s[e];
+            __syncthreads();
+            if (ty == 0)
+                for (int y = 1; y < SL; ++y)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) s[e] += red[(y * QB + tx) * 4 + e];
+        }
+        if (ty == 0 && q < total4) {
+            v4i o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                long long t = s[e];
+                if (t > 2147483647LL || t < -2147483648LL) { bad = true; t = t > 0 ? 2147483647LL : -2147483647LL; }
+                o[e] = (int)t;
+                const long long a = t < 0 ? -t : t;
+                const int ai = a > 2147483647LL ? 2147483647 : (int)a;
+                mx = ai > mx ? ai : mx;
+            }
+            *(v4i *)(g + q * 4) = o;
+        }
+        if (SL > 1) __syncthreads();
     }
     block_atomic_max_i32(mx, absmax);
     if (bad) atomicOr(status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);
@@ -537,10 +568,19 @@ extern "C" int eoq_conv_bwd_weight(eoq_ctx *c, const eoq_conv_desc *d, const int
     }
     if (rc != EOQ_OK) return rc;
     const size_t total = (size_t)d->K * rsc;
-    if (splits <= 16 && ld_in == rsc && total % 4 == 0)
-        hipLaunchKernelGGL(wgrad_finalize_direct_kernel, dim3(grid_for(total / 4)), dim3(256), 0, c->stream, part,
-                           p.part_stride, splits, total / 4, g_acc, absmax_slot, c->d_status);
-    else
+    if (ld_in == rsc && total % 4 == 0) {
+        const size_t t4 = total / 4;
+        auto blocks = [&](int qb) { size_t b = (t4 + qb - 1) / qb; return dim3((unsigned)(b > 4096 ? 4096 : b)); };
+        if (splits <= 4)
+            hipLaunchKernelGGL(wgrad_finalize_v4_kernel<1>, blocks(256), dim3(256), 0, c->stream, part, p.part_stride, splits,
+                               t4, g_acc, absmax_slot, c->d_status);
+        else if (splits <= 32)
+            hipLaunchKernelGGL(wgrad_finalize_v4_kernel<4>, blocks(64), dim3(256), 0, c->stream, part, p.part_stride, splits,
+                               t4, g_acc, absmax_slot, c->d_status);
+        else
+            hipLaunchKernelGGL(wgrad_finalize_v4_kernel<16>, blocks(16), dim3(256), 0, c->stream, part, p.part_stride, splits,
+                               t4, g_acc, absmax_slot, c->d_status);
+    } else
         hipLaunchKernelGGL(wgrad_finalize_kernel, dim3(grid_for(total * 4)), dim3(256), 0, c->stream, part,
                            p.part_stride, splits, d->K, ld_in, rsc, g_acc, absmax_slot, c->d_status, pad4 ? d->S : 0,
                            d->C, pad4 ? p.pad4_S4 : 0);
