@@ -196,7 +196,11 @@ def _bwd_data_sq_case(ctx, d, e, w, with_mask):
     maskb = (si.words(5, "mask", n) & np.uint64(1)).astype(bool)
     packed = np.packbits(maskb, bitorder="little")
     mask = dev(np.frombuffer(packed.tobytes() + b"\0" * (-len(packed) % 4), dtype=np.int32))
-    if with_mask:
+    if with_mask is None:
+        # nothing fused: codes, exponent, abs-max, sum
+        ctx.conv_bwd_data_sq(desc_of(d), dev(e), dev(w), e4, sl[0:1], sl[1:2], -7, sl[2:3], sums[0:1],
+                             ws_for(d, eoq.OP_CONV_BWD_DATA))
+    elif with_mask:
         ctx.conv_bwd_data_sq(desc_of(d), dev(e), dev(w), e4, sl[0:1], sl[1:2], -7, sl[2:3], sums[0:1],
                              ws_for(d, eoq.OP_CONV_BWD_DATA), mask=mask, e1=e1, sum_e1=sums[1:2], absmax_e1=sl[3:4])
     else:
@@ -228,7 +232,11 @@ SQ_SHAPES = CONV_SHAPES[:8] + [ConvShape(2, 17, 13, 32, 64, 1, 1, 2, 0),     # s
                                ConvShape(1, 10, 10, 16, 48, 1, 1, 3, 0),     # stride 3
                                ConvShape(2, 28, 28, 64, 128, 3, 3, 2, 1),    # stride-2 3x3: four parity classes
                                ConvShape(2, 12, 9, 32, 32, 5, 5, 2, 2),      # 5x5 stride 2, pad 2
-                               ConvShape(1, 11, 14, 16, 16, 2, 2, 2, 0)]     # 2x2 stride 2, no padding
+                               ConvShape(1, 11, 14, 16, 16, 2, 2, 2, 0),     # 2x2 stride 2, no padding
+                               # 1x1 with a short reduction and many outputs (first layer of a bottleneck block, from behind)
+                               ConvShape(3, 12, 10, 256, 64, 1, 1, 1, 0),    # ragged rows, two column tiles
+                               ConvShape(2, 9, 7, 48, 16, 1, 1, 1, 0),       # ragged columns
+                               ConvShape(2, 16, 16, 512, 128, 1, 1, 1, 0)]
 
 
 @pytest.mark.parametrize("d", SQ_SHAPES, ids=[f"{d.N}x{d.H}x{d.W}x{d.C}-k{d.K}r{d.R}s{d.stride}" for d in SQ_SHAPES])
@@ -240,6 +248,7 @@ def test_conv_bwd_data_sq(ctx, d):
     w = si.uniform_int8(3, "w", (d.K, d.R, d.S, d.C))
     _bwd_data_sq_case(ctx, d, e, w, with_mask=True)
     _bwd_data_sq_case(ctx, d, e, w, with_mask=False)
+    _bwd_data_sq_case(ctx, d, e, w, with_mask=None)
     spread = e.copy()
     spread[:, ::2] = np.clip(spread[:, ::2], -1, 1)            # every other row of every image carries tiny errors
     spread[0] = np.clip(spread[0], -2, 2)
@@ -248,6 +257,9 @@ def test_conv_bwd_data_sq(ctx, d):
     tiny_w = np.where(si.words(3, "sparse", w.size).reshape(w.shape) % np.uint64(37) == 0, np.clip(w, -1, 1), 0).astype(np.int8)
     _bwd_data_sq_case(ctx, d, tiny_e, tiny_w, with_mask=True)
     _bwd_data_sq_case(ctx, d, np.zeros_like(e), w, with_mask=True)
+    _bwd_data_sq_case(ctx, d, spread, w, with_mask=False)
+    _bwd_data_sq_case(ctx, d, tiny_e, tiny_w, with_mask=None)
+    _bwd_data_sq_case(ctx, d, np.zeros_like(e), w, with_mask=False)
 
 
 @pytest.mark.parametrize("d", CONV_SHAPES, ids=IDS)
