@@ -131,6 +131,11 @@ def main():
         a[2] += 1
         rows.append((kind, unit, work, ms))
     net.prof = None
+    # streaming passes (requantisation, update, input quantisation): algorithmic bytes over event-timed duration
+    hbm = {k[4:]: {"calls": v[2], "ms": round(v[1], 4), "gbs": round(v[0] / (v[1] * 1e-3) / 1e9, 1),
+                   "frac_of_hbm_peak": round(v[0] / (v[1] * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)}
+           for k, v in agg.items() if k.startswith("hbm_")}
+    agg = {k: v for k, v in agg.items() if not k.startswith("hbm_")}
     conv = {k: {"calls": v[2], "ms": round(v[1], 4), "tops": round(v[0] / (v[1] * 1e-3) / 1e12, 2)}
             for k, v in agg.items()}
     tot_ops = sum(v[0] for v in agg.values())
@@ -139,8 +144,12 @@ def main():
     fwd_tops = fwd[0] / (fwd[1] * 1e-3) / 1e12
     if args.per_layer:
         for kind, unit, work, ms in rows:
-            print(f"{kind:16s} {unit:10s} {work / 1e9:10.2f} GOP {ms:8.4f} ms {work / (ms * 1e-3) / 1e12:8.1f} TOP/s",
-                  file=sys.stderr)
+            if kind.startswith("hbm_"):
+                print(f"{kind:16s} {unit:10s} {work / 1e6:10.2f} MB  {ms:8.4f} ms {work / (ms * 1e-3) / 1e9:8.1f} GB/s",
+                      file=sys.stderr)
+            else:
+                print(f"{kind:16s} {unit:10s} {work / 1e9:10.2f} GOP {ms:8.4f} ms {work / (ms * 1e-3) / 1e12:8.1f} TOP/s",
+                      file=sys.stderr)
 
     out = {
         "metric": "int8 training images/sec (fwd+bwd+update); conv int8 TOPS as % of MFMA peak",
@@ -167,6 +176,7 @@ def main():
         "conv_pct_of_int8_peak": round(100.0 * tot_ops / (tot_ms * 1e-3) / 1e12 / PEAK_INT8_TOPS, 2),
         "conv_ms_of_step": round(tot_ms, 3),
         "conv": conv,
+        "hbm_passes": hbm,
         "roofline": {"bound": "mfma", "kernel": "igemm_kernel (forward convolution launches of one step)",
                      "achieved": round(fwd_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s",
                      "frac": round(fwd_tops / PEAK_INT8_TOPS, 4),

@@ -436,7 +436,8 @@ class FixupNet:
         """x_in (fp32 NHWC) -> Q input, stem, (pool), blocks, pooled integer sums."""
         c = self.ctx
         b0 = self.blocks[0]
-        c.quantize(self.x_in, eoq.CQ, -2, self.a0)                  # network input: CQ(x / 4)
+        # network input: CQ(x / 4); a streaming pass, 4 B in + 1 B out per element
+        self._call("hbm_quantize", "input", 5.0 * self.x_in.numel(), c.quantize, self.x_in, eoq.CQ, -2, self.a0)
         self._rec("in.a", self.a0)
         s = self.stem
         if self.pool:
@@ -507,7 +508,10 @@ class FixupNet:
         c = self.ctx_w if self.overlap else self.ctx
         M_G, Eg, gmax = self.s32(u.name + ".M_G"), self.s32(u.name + ".Eg"), self.s32(u.name + ".gmax")
         if not self.tracing:
-            c.grad_update(u.desc, G, M_G, self.s32(u.E3), -7, self.lr, u.w, wt=u.wt, exp_out=Eg, max_code_out=gmax)
+            n = u.w.numel()
+            self._call("hbm_grad_update", u.name, (4 + 1 + (2 if u.wt is not None else 1)) * float(n), c.grad_update, u.desc,
+                       G, M_G, self.s32(u.E3), -7, self.lr, u.w, wt=u.wt, exp_out=Eg, max_code_out=gmax,
+                       stream=self.side if self.overlap else self.main)
             return
         n = u.w.numel()
         g = self.gq[:n]
@@ -631,9 +635,11 @@ class FixupNet:
                 e3_low = self._acquire(bufs)
                 extra = dict(mask=low.mask, sum_out=self.s64(low.name + ".S_e1"), gamma=self.sc(low.gamma),
                              out_b=e3_low[:n_in], exp_out_b=self.s32(low.E3), absmax_masked=self.s32(M_inm))
-            c.requant_epilogue(eoq.RQ_SQ_MERGE, n_in, src_a=cur[:n_in], src_b=other[:n_in], exp_in=self.s32(first.E4),
-                               exp_b=self.s32(E_other), absmax=self.s32(M_in), out=out[:n_in],
-                               exp_out=self.s32(b.name + ".E_in"), **extra)
+            # 2 B in + 1 B out per element (+ 1/8 B of mask and a second output byte when the next layer rides along)
+            self._call("hbm_merge", b.name, (3 + (1.125 if low is not None else 0)) * float(n_in), c.requant_epilogue,
+                       eoq.RQ_SQ_MERGE, n_in, src_a=cur[:n_in], src_b=other[:n_in], exp_in=self.s32(first.E4),
+                       exp_b=self.s32(E_other), absmax=self.s32(M_in), out=out[:n_in],
+                       exp_out=self.s32(b.name + ".E_in"), **extra)
             masked = low is not None
             if b.ds:
                 bufs.append(e4d)

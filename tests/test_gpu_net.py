@@ -102,3 +102,32 @@ def test_network_steps(wl, N, steps, lr):
         compare_params(g, o, f"{wl} step{step}")
         assert g.status() == 0
     assert changed_fraction(W0, o.W) > 0.01, "test would be vacuous: no weight code moved"
+
+
+@pytest.mark.parametrize("wl,N,steps,lr", [("tiny_basic", 4, 3, (1, 1)), ("tiny_bottleneck", 4, 3, (3, 2)),
+                                           ("tiny_bottleneck", 3, 2, (3, 2)),     # odd batch: whole-batch forward
+                                           ("resnet50", 2, 1, (1, 0)), ("resnet50", 4, 1, (1, 0)),
+                                           # the paper's other two networks
+                                           ("resnet34", 2, 1, (1, 2)), ("resnet110", 4, 2, (1, -2))])
+def test_network_steps_untraced(wl, N, steps, lr):
+    """The same comparison on the path the benchmark runs: without tracing the step uses its fused calls (ReLU
+    backward and Q_e(e1*gamma) inside the merge pass, Q_g + update + transpose in one kernel, pool backward with the
+    stem's mask, two half-batch forward chains, deferred updates on the side stream).  Loss and every parameter
+    after every step must equal the oracle's."""
+    from paper_2105_13890_amd.net import FixupNet
+    cfg = si.WORKLOADS[wl]
+    g, o = FixupNet(cfg, N, seed=0), OracleNet(cfg, N, seed=0)
+    W0 = {k: v.copy() for k, v in o.W.items()}
+    for step in range(steps):
+        x = si.batch_images(0, step, N, cfg["in_hw"])
+        lab = si.batch_labels(0, step, N, cfg["classes"])
+        lo = o.step(x, lab, *lr)
+        lg = g.step(x, lab, *lr)
+        assert lg == pytest.approx(lo, rel=1e-5)
+        compare_params(g, o, f"{wl} step{step}")
+        # scalar gradients as well (their sums come from the fused kernels)
+        gc, ge = host(g.g_code), host(g.g_exp)
+        for i, p in enumerate(g.sgrad_params):
+            assert int(gc[i]) == o.trace[p + ".gs"] and int(ge[i]) == o.trace[p + ".Egs"], (wl, step, p)
+        assert g.status() == 0
+    assert changed_fraction(W0, o.W) > 0.01, "test would be vacuous: no weight code moved"
