@@ -47,6 +47,40 @@ __device__ __forceinline__ int32_t rne_shift7(int32_t v)   // |v| < 2^30
     return (v + 63 + ((v >> 7) & 1)) >> 7;
 }
 
+// 32-bit forms for |v| < 2^30; LEFT selects the exact left shift (s <= 0) at compile time so that the streaming kernels,
+// whose shift is the same for every element, carry no per-element branch
+template <bool LEFT>
+__device__ __forceinline__ int rne_shift32(int v, int s)
+{
+    if (LEFT) return v << (-s);
+    return (v + ((1 << (s - 1)) - 1) + ((v >> s) & 1)) >> s;
+}
+
+template <bool LEFT>
+__device__ __forceinline__ int sq_code32(int v, int s)      // clamp(R(v * 2^-s), -127, 127)
+{
+    const int c = rne_shift32<LEFT>(v, s);
+    return c < -CODE_MAX ? -CODE_MAX : (c > CODE_MAX ? CODE_MAX : c);
+}
+
+// four codes in [-127, 127] -> one dword of bytes
+__device__ __forceinline__ uint32_t pack4_i8(int c0, int c1, int c2, int c3)
+{
+    return ((uint32_t)c0 & 0xffu) | (((uint32_t)c1 & 0xffu) << 8) | (((uint32_t)c2 & 0xffu) << 16) | ((uint32_t)c3 << 24);
+}
+
+// 4 mask bits (bit k for byte k) -> 0xff in every byte whose bit is set
+__device__ __forceinline__ uint32_t byte_mask4(uint32_t m4)
+{
+    return (((m4 & 0xfu) * 0x00204081u) & 0x01010101u) * 0xffu;
+}
+
+// sum of the four signed bytes of a dword, added to acc
+__device__ __forceinline__ int sum4_i8(uint32_t packed, int acc)
+{
+    return __builtin_amdgcn_sdot4((int)packed, 0x01010101, acc, false);
+}
+
 __device__ __forceinline__ int clamp_i(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 // ---- R(log2 M) for an integer M >= 1 (Eq.7's scale exponent): floor(log2 M), plus one iff

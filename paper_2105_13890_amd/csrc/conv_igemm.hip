@@ -978,46 +978,57 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
             hi = ((const v4i *)(p.d16 + src))[1];
         }
         const int T = sh - s + 1;                          // rounding position inside the stored 16-bit value
-        int v[16];
-#pragma unroll
-        for (int k = 0; k < 16; k += 2) {
-            const int w = k < 8 ? lo[k >> 1] : hi[(k - 8) >> 1];
-            v[k] = (int)(int16_t)(w & 0xffff);
-            v[k + 1] = w >> 16;
-        }
-        int code[16];
-        if (T >= 1) {
-            const int half = (1 << (T - 1)) - 1;
-#pragma unroll
-            for (int k = 0; k < 16; ++k) code[k] = (v[k] + half + ((v[k] >> T) & 1)) >> T;
-        } else {                                           // every sum is below 2^7: the stored value is exactly 2*d
-#pragma unroll
-            for (int k = 0; k < 16; ++k) code[k] = (v[k] >> 1) << (-sh);
-        }
-        uint32_t o4[4] = {0, 0, 0, 0}, o1[4] = {0, 0, 0, 0};
+        uint32_t o4[4], o1[4] = {0, 0, 0, 0};
         uint32_t mk = 0xffffu;
         if (RELU && p.mask16) mk = (uint32_t)p.mask16[off >> 4];
         v4i ov = {0, 0, 0, 0};
         if (!RELU && p.mg_other) ov = *(const v4i *)(p.mg_other + off);
         if (!RELU && p.mg_mask16) mk = (uint32_t)p.mg_mask16[off >> 4];
+        int cd[16];
+        if (T >= 1) {
+            const int half = (1 << (T - 1)) - 1;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const int cd = clamp_i(code[k], -CODE_MAX, CODE_MAX);
-            o4[k >> 2] |= ((uint32_t)cd & 0xffu) << (8 * (k & 3));
-            s4 += cd;
-            if (!RELU) {
-                int mv = (cd << mg_sa) + (byte_at(ov, k) << mg_sb);
-                mv = mv < 0 ? -mv : mv;
-                mg_mx = mv > mg_mx ? mv : mg_mx;
-                const int mm = ((mk >> k) & 1u) ? mv : 0;
-                mg_mxm = mm > mg_mxm ? mm : mg_mxm;
+            for (int k = 0; k < 16; k += 2) {
+                const int w = k < 8 ? lo[k >> 1] : hi[(k - 8) >> 1];
+                const int v0 = __builtin_amdgcn_sbfe(w, 0, 16), v1 = w >> 16;
+                cd[k] = clamp_i((v0 + half + ((v0 >> T) & 1)) >> T, -CODE_MAX, CODE_MAX);
+                cd[k + 1] = clamp_i((v1 + half + ((v1 >> T) & 1)) >> T, -CODE_MAX, CODE_MAX);
             }
+        } else {                                           // every sum is below 2^7: the stored value is exactly 2*d
+#pragma unroll
+            for (int k = 0; k < 16; k += 2) {
+                const int w = k < 8 ? lo[k >> 1] : hi[(k - 8) >> 1];
+                cd[k] = clamp_i((__builtin_amdgcn_sbfe(w, 0, 16) >> 1) << (-sh), -CODE_MAX, CODE_MAX);
+                cd[k + 1] = clamp_i((w >> 17) << (-sh), -CODE_MAX, CODE_MAX);
+            }
+        }
+        // four codes (one output dword) at a time: sums and masks work on packed bytes
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t pk = pack4_i8(cd[4 * q], cd[4 * q + 1], cd[4 * q + 2], cd[4 * q + 3]);
+            o4[q] = pk;
+            s4 = sum4_i8(pk, s4);
             if (RELU) {
-                const int e = ((mk >> k) & 1u) ? cd : 0;
-                o1[k >> 2] |= ((uint32_t)e & 0xffu) << (8 * (k & 3));
-                s1 += e;
-                const int ae = e < 0 ? -e : e;
-                mx1 = ae > mx1 ? ae : mx1;
+                const uint32_t pm = pk & byte_mask4(mk >> (4 * q));
+                o1[q] = pm;
+                s1 = sum4_i8(pm, s1);
+                if (p.absmax_e1) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int e = __builtin_amdgcn_sbfe((int)pm, 8 * k, 8);
+                        const int ae = e < 0 ? -e : e;
+                        mx1 = ae > mx1 ? ae : mx1;
+                    }
+                }
+            } else if (p.mg_other) {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    int mv = (cd[4 * q + k] << mg_sa) + (__builtin_amdgcn_sbfe(ov[q], 8 * k, 8) << mg_sb);
+                    mv = mv < 0 ? -mv : mv;
+                    mg_mx = mv > mg_mx ? mv : mg_mx;
+                    const int mm = ((mk >> (4 * q + k)) & 1u) ? mv : 0;
+                    mg_mxm = mm > mg_mxm ? mm : mg_mxm;
+                }
             }
         }
         if (p.e4) *(v4i *)(p.e4 + off) = v4i{(int)o4[0], (int)o4[1], (int)o4[2], (int)o4[3]};

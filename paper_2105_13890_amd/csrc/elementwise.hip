@@ -87,6 +87,25 @@ __global__ void quantize_f32_kernel(const float *x, size_t n, int pre_shift, voi
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     bool bad = false;
+    if (MODE != EOQ_Q && (((uintptr_t)x | (uintptr_t)q) & 15) == 0) {
+        // int8 output: four elements per lane and iteration (one 16-byte load, one 4-byte store)
+        const size_t n4 = n / 4;
+        for (size_t j = i; j < n4; j += stride) {
+            const float4 xv = ((const float4 *)x)[j];
+            const float xs[4] = {xv.x, xv.y, xv.z, xv.w};
+            int cd[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float xf = xs[k];
+                if (MODE != EOQ_SQ && (__float_as_uint(xf) & 0x7fffffffu) >= 0x7f800000u) { bad = true; xf = 0.f; }
+                double v = zero ? 0.0 : rint(ldexp((double)xf, sh));
+                v = v < -127.0 ? -127.0 : (v > 127.0 ? 127.0 : v);
+                cd[k] = (int)v;
+            }
+            ((uint32_t *)q)[j] = pack4_i8(cd[0], cd[1], cd[2], cd[3]);
+        }
+        i += n4 * 4;               // the ragged tail, one element per lane
+    }
     for (; i < n; i += stride) {
         float xf = x[i];
         if (MODE != EOQ_SQ && (__float_as_uint(xf) & 0x7fffffffu) >= 0x7f800000u) { bad = true; xf = 0.f; }
@@ -221,6 +240,32 @@ struct SqArgs {
     const int32_t *absmax_m;     // SQ_MERGE with out_b and a mask: max|v| over the elements whose mask bit is set
 };
 
+// One 16-element vector of the merge pass in 32-bit arithmetic (|v| < 2^30, |code * gamma| < 2^30): codes of
+// a * 2^sa + b * 2^sb under the mask, their sum, optionally Q_e(code * gamma) as a second vector.
+template <bool L1, bool L2, bool TWO>
+__device__ __forceinline__ void merge_vec32(const v4i a, const v4i b, uint32_t mk, int sa, int sb, int s1, int g, int s2,
+                                            v4i &o, v4i &o2, int &sum)
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        int c[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int av = __builtin_amdgcn_sbfe(a[q], 8 * k, 8), bv = __builtin_amdgcn_sbfe(b[q], 8 * k, 8);
+            c[k] = sq_code32<L1>((av << sa) + (bv << sb), s1);
+        }
+        const uint32_t pk = pack4_i8(c[0], c[1], c[2], c[3]) & byte_mask4(mk >> (4 * q));
+        sum = sum4_i8(pk, sum);
+        o[q] = (int)pk;
+        if (TWO) {
+            int d[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) d[k] = sq_code32<L2>(__builtin_amdgcn_sbfe((int)pk, 8 * k, 8) * g, s2);
+            o2[q] = (int)pack4_i8(d[0], d[1], d[2], d[3]);
+        }
+    }
+}
+
 template <int MODE>
 __global__ void sq_pass_kernel(SqArgs p)
 {
@@ -258,6 +303,34 @@ __global__ void sq_pass_kernel(SqArgs p)
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     int64_t s = 0;
     int mxo = 0;
+    if (MODE == EOQ_RQ_SQ_MERGE && !p.absmax_out && (p.n & 15) == 0 && sa <= 22 && sb <= 22 && g > -(1 << 22) && g < (1 << 22)) {
+        // the usual case in 32-bit arithmetic, the shifts' directions resolved outside the element loop
+        const int s1 = r - 7, s2 = r2 - 7;
+        int ls = 0, since = 0;
+        for (; i < nv; i += stride) {
+            const v4i a = ((const v4i *)p.src_a)[i], b = ((const v4i *)p.src_b)[i];
+            const uint32_t mk = p.mask16 ? (uint32_t)p.mask16[i] : 0xffffu;
+            v4i o, o2;
+            if (!p.out_b) {
+                if (s1 <= 0) merge_vec32<true, true, false>(a, b, mk, sa, sb, s1, 0, 0, o, o2, ls);
+                else merge_vec32<false, true, false>(a, b, mk, sa, sb, s1, 0, 0, o, o2, ls);
+            } else {
+                if (s1 <= 0) {
+                    if (s2 <= 0) merge_vec32<true, true, true>(a, b, mk, sa, sb, s1, g, s2, o, o2, ls);
+                    else merge_vec32<true, false, true>(a, b, mk, sa, sb, s1, g, s2, o, o2, ls);
+                } else {
+                    if (s2 <= 0) merge_vec32<false, true, true>(a, b, mk, sa, sb, s1, g, s2, o, o2, ls);
+                    else merge_vec32<false, false, true>(a, b, mk, sa, sb, s1, g, s2, o, o2, ls);
+                }
+                ((v4i *)p.out_b)[i] = o2;
+            }
+            ((v4i *)p.out)[i] = o;
+            if (++since == 1 << 16) { s += ls; ls = 0; since = 0; }      // long before 32 bits fill
+        }
+        s += ls;
+        if (p.sum_out) block_atomic_add_i64(s, p.sum_out);
+        return;
+    }
     for (; i < nv; i += stride) {
         v4i o = {0, 0, 0, 0};
         int ls = 0;

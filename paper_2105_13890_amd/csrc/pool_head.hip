@@ -119,14 +119,25 @@ __global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t 
             }
         }
         if (OUT == 2) {
-            v4i o = {0, 0, 0, 0};
+            // a sum of at most R*S int8 errors: 32-bit arithmetic, four codes per packed dword
+            v4i o;
             const uint32_t mk = mask16 ? (uint32_t)mask16[pix * c16 + cc] : 0xffffu;
             int ls = 0;
+            const int sh = r - 7;
+            int cd[16];
+            if (sh <= 0) {
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const int cd = ((mk >> k) & 1u) ? sq_code((int64_t)acc[k], r) : 0;
-                set_byte(o, k, cd);
-                ls += cd;
+                for (int k = 0; k < 16; ++k) cd[k] = sq_code32<true>(acc[k], sh);
+            } else {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) cd[k] = sq_code32<false>(acc[k], sh);
+            }
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const uint32_t pk = pack4_i8(cd[4 * q4], cd[4 * q4 + 1], cd[4 * q4 + 2], cd[4 * q4 + 3]) &
+                                    byte_mask4(mk >> (4 * q4));
+                ls = sum4_i8(pk, ls);
+                o[q4] = (int)pk;
             }
             sum += ls;
             *(v4i *)(q + pix * g.C + cc * 16) = o;

@@ -570,7 +570,8 @@ class FixupNet:
                 self._call("conv_bwd_data", u.name, self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
                            e4_dbg, self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
                            self.s64(u.name + ".S_e4"), self.ws, w_transposed=u.wt, mask=f.mask, e1=e4[:n_in],
-                           sum_e1=self.s64(f.name + ".S_e1"), absmax_e1=self.s32(f.name + ".M_e1"))
+                           sum_e1=self.s64(f.name + ".S_e1"),
+                           absmax_e1=self.s32(f.name + ".M_e1") if self.tracing else None)   # only Q_e(e1*gamma) reads it
                 if self.tracing:
                     self._rec(u.name + ".e4", e4_dbg)
             else:
