@@ -606,9 +606,10 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
     }
     // per wave, 32 rows at a time through LDS
     long long sq_sum = 0, rb_st = 0;
-    int32_t *stg = (int32_t *)lds + wave * 32 * EPI_LD;
     constexpr int GROUPS = WTN / 16;              // 16-channel groups per row of the wave tile
     constexpr int ROWS_PER_PASS = 64 / GROUPS;
+    constexpr int SR = ROWS_PER_PASS <= 16 ? 16 : 32;
+    int32_t *stg = (int32_t *)lds + wave * SR * EPI_LD;
     const int grp = lane % GROUPS, prow = lane / GROUPS;
     int gamma = 128, bpost = 0, bnext = 0;
     bool fast = false;
@@ -647,25 +648,30 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
                 }
             }
     }
+    // SR rows of a 32-row accumulator block are staged at a time: 16 where a pass covers at most 16 rows, which
+    // halves the staging area -- for 128-column wave tiles that is the difference between two and four workgroups
+    // per compute unit
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
+      for (int hf = 0; hf < 32 / SR; ++hf) {
+#pragma unroll
         for (int jn = 0; jn < TN; ++jn)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                int row = (e >> 2) * 8 + lhalf * 4 + (e & 3);
+            for (int e = hf * (SR / 2); e < (hf + 1) * (SR / 2); ++e) {
+                int row = (e >> 2) * 8 + lhalf * 4 + (e & 3) - hf * SR;
                 stg[row * EPI_LD + jn * 32 + lrow32] = acc[i][jn][e];
             }
         __syncthreads();   // (each wave reads back only what it wrote itself)
 #pragma unroll
-        for (int ps = 0; ps < 32 / ROWS_PER_PASS; ++ps) {
+        for (int ps = hf * (SR / ROWS_PER_PASS); ps < (hf + 1) * (SR / ROWS_PER_PASS); ++ps) {
             const int row = ps * ROWS_PER_PASS + prow;
             const int m = m0 + wm * WTM + i * 32 + row;
             const int ch = n0 + wn * WTN + grp * 16;
             int v[16];
 #pragma unroll
             for (int k4 = 0; k4 < 4; ++k4) {
-                v4i w = *(const v4i *)(stg + row * EPI_LD + grp * 16 + 4 * k4);
+                v4i w = *(const v4i *)(stg + (row - hf * SR) * EPI_LD + grp * 16 + 4 * k4);
                 v[4 * k4] = w[0]; v[4 * k4 + 1] = w[1]; v[4 * k4 + 2] = w[2]; v[4 * k4 + 3] = w[3];
             }
             if (m < p.M && ch < p.NOUT) {
@@ -729,6 +735,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
             }
         }
         __syncthreads();
+      }
     }
     if (EPI == EPI_FWD && range_bad) atomicOr(p.status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);
     if (EPI == EPI_ACC && p.absmax) block_atomic_max_i32(mx, p.absmax);
@@ -1059,7 +1066,8 @@ template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, i
 int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
 {
     constexpr int NW = WGM * WGN;
-    constexpr int main_bytes = 2 * (BM + BN) * BK, epi_bytes = NW * 32 * (BN / WGN + 4) * 4;
+    constexpr int epi_rows = (BN / WGN) >= 64 ? 16 : 32;        // rows staged at a time (SR in the kernel)
+    constexpr int main_bytes = 2 * (BM + BN) * BK, epi_bytes = NW * epi_rows * (BN / WGN + 4) * 4;
     constexpr int lds_bytes = main_bytes > epi_bytes ? main_bytes : epi_bytes;
     static bool attr_done = false;
     auto kern = igemm_kernel<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>;
