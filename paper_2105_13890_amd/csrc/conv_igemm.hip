@@ -195,9 +195,17 @@ __device__ __forceinline__ bool epilogue_fits32(const EpiDev &ep, int gamma, int
     return ag < (1 << 23) && tmax < (1 << 23) && ag * tmax + 128 * (ab + sk) < (1ll << 31) - 256;
 }
 
+// D = 2 selects the low-register form: no ring of prefetched stages, no double-buffered fragments, the stages strictly
+// one after the other, epilogue side inputs fetched where they are used.  The pipelined form holds about 250
+// registers per lane, i.e. TWO workgroups per compute unit; this one is compiled for 128 (FOUR workgroups).  Measured
+// per workgroup on a 1x1 layer with a 64-byte reduction: 9 us of life, 6.6 of them in the epilogue -- such layers want
+// more workgroups in flight, not a deeper pipeline.  Measured over the whole net: the low-register form wins for
+// reductions of up to about 80 sixteen-byte chunks and ties with the pipelined form beyond (a variant with one stage
+// of prefetch and two LDS buffers was no better than the strictly serial loop).
 template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
-__global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
+__device__ __forceinline__ void igemm_body(const IgemmParams &pin)
 {
+    constexpr bool LOWREG = D == 2;
     IgemmParams p = pin;           // uniform; patched below when the launch covers several classes
     constexpr int NW = WGM * WGN, NT = NW * 64;
     static_assert(NW == 4 || NW == 8, "4 or 8 waves");
@@ -211,7 +219,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
     constexpr int A_ROWS = (BM + RPP - 1) / RPP, B_ROWS = (BN + RPP - 1) / RPP;
     constexpr int STAGE_BYTES = (BM + BN) * BK;
     constexpr int EPI_LD = WTN + 4;                       // int32 row stride of the epilogue staging
-    static_assert(D >= 4 && D % 2 == 0, "global-load stages in flight");
+    static_assert(D == 2 || (D >= 4 && D % 2 == 0), "global-load stages in flight");
 
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
 
@@ -417,7 +425,35 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
     };
 
     const int nstages = (p.nk16 + CH - 1) / CH;
-    if constexpr (BK == 128) {
+    if constexpr (LOWREG) {
+        // One stage of global loads in flight, two LDS buffers, fragments read one reduction step at a time: while
+        // stage st is multiplied out of one buffer, stage st+1 is on its way from memory and is stored into the other
+        // buffer after the multiplication; one barrier per stage.  The load past the last stage is out of range
+        // (zeros, no traffic), so the loop has no conditional load.
+        static_assert(BK == 64, "low-register form");
+        for (int st = 0; st < nstages; ++st) {
+            {
+                v4i ra0[A_ROWS], rb0[B_ROWS];
+                load_stage(ra0, rb0);
+                store_stage(0, ra0, rb0);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < CH / 2; ++j) {
+                v4i fa0[TM], fb0[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fa0[i] = *(const v4i *)(lds + rd_a[j] + i * 32 * BK);
+#pragma unroll
+                for (int i = 0; i < TN; ++i) fb0[i] = *(const v4i *)(lds + rd_b[j] + i * 32 * BK);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int jn = 0; jn < TN; ++jn)
+                        acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa0[i], fb0[jn], acc[i][jn], 0, 0, 0);
+            }
+            __syncthreads();
+        }
+    } else if constexpr (BK == 128) {
         // 128-byte stages: every row of a stage is one full 128-byte cache line per global load instruction (8
         // lanes per row).  With 64-byte stages and rows longer than 64 bytes each instruction takes half of
         // 16 different lines and the other halves are fetched again one stage later -- measured on this chip,
@@ -627,7 +663,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
     constexpr int NPASS = 32 / ROWS_PER_PASS;
     v4i pre8[TM][NPASS];
     uint32_t premk[TM][NPASS];
-    if (EPI == EPI_FWD || EPI == EPI_RELU_BWD) {
+    if (!LOWREG && (EPI == EPI_FWD || EPI == EPI_RELU_BWD)) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -682,13 +718,26 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
                     const int gh = r / p.rm_Wc, gw = r - gh * p.rm_Wc;
                     off = ((size_t)(n * p.rm_H + 2 * gh + p.rm_h0) * p.rm_W + 2 * gw + p.rm_w0) * p.NOUT + ch;
                 }
+                v4i side8 = v4i{0, 0, 0, 0};
+                uint32_t sidemk = 0xffffu;
+                if (LOWREG) {
+                    if (EPI == EPI_FWD) {
+                        if (p.ep.skip && p.ep.relu && !p.ep.skip_wide) side8 = *(const v4i *)((const int8_t *)p.ep.skip + off);
+                    } else if (EPI == EPI_RELU_BWD) {
+                        side8 = *(const v4i *)(p.rb_e0 + off);
+                        if (p.rb_mask16) sidemk = (uint32_t)p.rb_mask16[off >> 4];
+                    }
+                } else {
+                    side8 = pre8[i][ps];
+                    sidemk = premk[i][ps];
+                }
                 if (EPI == EPI_FWD) {
-                    if (fast) epilogue16<true>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad, pre8[i][ps]);
-                    else epilogue16<false>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad, pre8[i][ps]);
+                    if (fast) epilogue16<true>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad, side8);
+                    else epilogue16<false>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad, side8);
                 } else if (EPI == EPI_RELU_BWD) {
                     // Eq.3 e1 = e0 * relu'(x4); Eq.4 sums for g_b2 and g_gamma with x2 = R(acc/128) recomputed
-                    const v4i ev = pre8[i][ps];
-                    const uint32_t mk = premk[i][ps];
+                    const v4i ev = side8;
+                    const uint32_t mk = sidemk;
                     v4i o = {0, 0, 0, 0};
                     int ls = 0, lst = 0;
                     // |x2| <= 127^2 * (reduction length) / 128 and |e| <= 127: for reductions of up to 8192
@@ -754,6 +803,19 @@ __global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
             if (lane == 0) slot_atomic_max_i32(p.rb_absmax, wm_);
         }
     }
+}
+
+template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
+__global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
+{
+    igemm_body<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>(pin);
+}
+
+// the low-register form is compiled for four waves per SIMD (128 registers per lane)
+template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
+__global__ __launch_bounds__(WGM * WGN * 64, 4) void igemm_lr_kernel(IgemmParams pin)
+{
+    igemm_body<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>(pin);
 }
 
 // ---- small layout kernels -------------------------------------------------------------------
@@ -1070,7 +1132,8 @@ int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
     constexpr int main_bytes = 2 * (BM + BN) * BK, epi_bytes = NW * epi_rows * (BN / WGN + 4) * 4;
     constexpr int lds_bytes = main_bytes > epi_bytes ? main_bytes : epi_bytes;
     static bool attr_done = false;
-    auto kern = igemm_kernel<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>;
+    void (*kern)(IgemmParams) = igemm_kernel<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>;
+    if constexpr (D == 2) kern = igemm_lr_kernel<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>;
     if (lds_bytes > 48 * 1024 && !attr_done) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
             return EOQ_ERR_HIP;
@@ -1106,10 +1169,21 @@ int forced_tile()
     return v;
 }
 
+// longest reduction (in 16-byte chunks) that takes the low-register form; EOQ_LOWREG overrides it (0 = never)
+static int lowreg_max_nk16()
+{
+    static const int v = [] { const char *e = getenv("EOQ_LOWREG"); return e ? atoi(e) : 80; }();
+    return v;
+}
+
 template <int BM, int BN, int WGM, int WGN, int BK, int MODE, int EPI>
 int launch_igemm(eoq_ctx *c, const IgemmParams &p)
 {
     if (p.c16 % (BK / 16) == 0) {
+        if constexpr (BK == 64 && WGM * WGN == 4 && (EPI == EPI_FWD || EPI == EPI_D16 || EPI == EPI_RELU_BWD)) {
+            if (p.nk16 <= lowreg_max_nk16())
+                return launch_igemm_u<BM, BN, WGM, WGN, BK, 2, true, MODE, EPI>(c, p);
+        }
         return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, true, MODE, EPI>(c, p);
     }
     return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, false, MODE, EPI>(c, p);
