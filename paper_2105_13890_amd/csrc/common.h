@@ -239,6 +239,10 @@ static inline Pad4Geom pad4_geom(const eoq_conv_desc *d)
 
 // most partial-sum buffers the weight-gradient kernel may write for a filter of `elems` int32 elements:
 // as many as keep the chip busy for small filters, few enough for large ones that their traffic stays small
+// Partial-sum buffers lie WGRAD_PART_PAD elements further apart than they need to: filter sizes are powers of two (or
+// nine times one), and buffers exactly such a distance apart start on the same memory channels -- the finalize
+// kernel, which reads the same element of every buffer at once, then queues up on a few channels.
+constexpr size_t WGRAD_PART_PAD = 1088;      // 4352 bytes
 static inline int wgrad_max_splits(size_t elems)
 {
     size_t cap = ((size_t)48 << 20) / (elems * 4 + 1);

@@ -1278,7 +1278,7 @@ extern "C" size_t eoq_workspace_bytes(const eoq_conv_desc *d, int op)
                round_up(4 * (((size_t)d->N * d->H * d->W + 63) / 64) * (((size_t)d->C + 31) / 32), 256);
     case EOQ_OP_CONV_BWD_WEIGHT:
         // staged input + split partial sums (int32) sized for the worst split count, see conv_wgrad.hip
-        return im2col + round_up((size_t)d->K * kp * 4 * wgrad_max_splits((size_t)d->K * kp), 256);
+        return im2col + round_up(((size_t)d->K * kp + WGRAD_PART_PAD) * 4 * wgrad_max_splits((size_t)d->K * kp), 256);
     default: return 0;
     }
 }

@@ -46,7 +46,7 @@ __device__ __forceinline__ v2i lds_read_tr8(const int8_t *p)
 }
 
 template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL>
-__global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
+__device__ __forceinline__ void wgrad_body(const WgradParams &p)
 {
     static_assert(WK * WC == 4, "4 waves");
     constexpr int KT = WK * TK * 32, CT = WC * TC * 32;
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
     // buffer.  Every load of a step is unconditional (past the range it is out of range: no traffic, zeros), so the
     // number of loads in flight at the wait before the LDS stores is a compile-time constant and only the oldest
     // set is waited for; the order of the phases is pinned with scheduling barriers.
-    constexpr int D = U_LOADS > 2 ? 2 : 4;
+    constexpr int D = (U_LOADS > 2 || TAPS == 1) ? 2 : 4;
     static_assert(D % 2 == 0, "buffer parity follows the chunk index");
     v4i re[D][E_LOADS], ru[D][U_LOADS];
 #pragma unroll
@@ -267,6 +267,20 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
                 }
             }
         }
+}
+
+template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL>
+__global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
+{
+    wgrad_body<WK, WC, TK, TC, TAPS, U_LOADS, FULL>(p);
+}
+
+// the single-tap (1x1) kernels keep two stages of loads in flight instead of four and are compiled for three waves
+// per SIMD: 152 registers instead of 184, three workgroups per compute unit instead of two
+template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL>
+__global__ __launch_bounds__(256, 3) void wgrad_occ3_kernel(WgradParams p)
+{
+    wgrad_body<WK, WC, TK, TC, TAPS, U_LOADS, FULL>(p);
 }
 
 // exact combination of the partial sums; int32 range check; abs-max for Q_g.
@@ -471,7 +485,7 @@ int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int *splits_out)
     }
     int splits = target_wgs / tiles;
     if (splits < 1) splits = 1;
-    const int max_splits = wgrad_max_splits(p.part_stride);
+    const int max_splits = wgrad_max_splits(p.part_stride - WGRAD_PART_PAD);
     if (splits > max_splits) splits = max_splits;
     if (splits > p.nchunks) splits = p.nchunks;
     p.chunks_per_split = (p.nchunks + splits - 1) / splits;
@@ -481,8 +495,12 @@ int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int *splits_out)
     splits = (p.nchunks + p.chunks_per_split - 1) / p.chunks_per_split;
     if (splits > max_splits) return EOQ_ERR_SHAPE;
     static bool attr_done = false;
-    auto kern_full = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true>;
-    auto kern_part = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false>;
+    void (*kern_full)(WgradParams) = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true>;
+    void (*kern_part)(WgradParams) = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false>;
+    if constexpr (TAPS == 1) {
+        kern_full = wgrad_occ3_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true>;
+        kern_part = wgrad_occ3_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false>;
+    }
     if (lds_bytes > 48 * 1024 && !attr_done) {
         if (hipFuncSetAttribute((const void *)kern_full, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess ||
             hipFuncSetAttribute((const void *)kern_part, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
@@ -557,7 +575,7 @@ extern "C" int eoq_conv_bwd_weight(eoq_ctx *c, const eoq_conv_desc *d, const int
     }
     p.RS = p.R * p.S;
     p.part = part;
-    p.part_stride = (size_t)p.K * p.RS * p.C;
+    p.part_stride = (size_t)p.K * p.RS * p.C + WGRAD_PART_PAD;
     int splits = 0, rc;
     if (p.RS == 1) {
         if (p.K >= 128) rc = launch_wgrad<2, 2, 2, 2, 1, 2>(c, p, p.RS, &splits);
@@ -571,10 +589,11 @@ extern "C" int eoq_conv_bwd_weight(eoq_ctx *c, const eoq_conv_desc *d, const int
     if (ld_in == rsc && total % 4 == 0) {
         const size_t t4 = total / 4;
         auto blocks = [&](int qb) { size_t b = (t4 + qb - 1) / qb; return dim3((unsigned)(b > 4096 ? 4096 : b)); };
-        if (splits <= 4)
+        // enough element groups to fill the chip: no split lanes (no LDS, no barriers); otherwise trade them in
+        if (splits <= 4 || t4 >= 131072)
             hipLaunchKernelGGL(wgrad_finalize_v4_kernel<1>, blocks(256), dim3(256), 0, c->stream, part, p.part_stride, splits,
                                t4, g_acc, absmax_slot, c->d_status);
-        else if (splits <= 32)
+        else if (splits <= 32 || t4 >= 32768)
             hipLaunchKernelGGL(wgrad_finalize_v4_kernel<4>, blocks(64), dim3(256), 0, c->stream, part, p.part_stride, splits,
                                t4, g_acc, absmax_slot, c->d_status);
         else
