@@ -213,7 +213,7 @@ __device__ __forceinline__ void wgrad_body(const WgradParams &p)
     // buffer.  Every load of a step is unconditional (past the range it is out of range: no traffic, zeros), so the
     // number of loads in flight at the wait before the LDS stores is a compile-time constant and only the oldest
     // set is waited for; the order of the phases is pinned with scheduling barriers.
-    constexpr int D = (U_LOADS > 2 || TAPS == 1) ? 2 : 4;
+    constexpr int D = 2;
     static_assert(D % 2 == 0, "buffer parity follows the chunk index");
     v4i re[D][E_LOADS], ru[D][U_LOADS];
 #pragma unroll
@@ -275,8 +275,15 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
     wgrad_body<WK, WC, TK, TC, TAPS, U_LOADS, FULL>(p);
 }
 
-// the single-tap (1x1) kernels keep two stages of loads in flight instead of four and are compiled for three waves
-// per SIMD: 152 registers instead of 184, three workgroups per compute unit instead of two
+// Occupancy decides more here than prefetch depth: with two stages of loads in flight instead of four, the single-tap
+// (1x1) kernels fit 152 registers (three workgroups per compute unit instead of two) and the nine-tap stride-1 kernel,
+// whose 9 x 16 accumulators alone take 144, fits 256 (two instead of one).
+template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL>
+__global__ __launch_bounds__(256, 2) void wgrad_occ2_kernel(WgradParams p)
+{
+    wgrad_body<WK, WC, TK, TC, TAPS, U_LOADS, FULL>(p);
+}
+
 template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL>
 __global__ __launch_bounds__(256, 3) void wgrad_occ3_kernel(WgradParams p)
 {
@@ -500,6 +507,9 @@ int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int *splits_out)
     if constexpr (TAPS == 1) {
         kern_full = wgrad_occ3_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true>;
         kern_part = wgrad_occ3_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false>;
+    } else if constexpr (U_LOADS == 2) {
+        kern_full = wgrad_occ2_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true>;
+        kern_part = wgrad_occ2_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false>;
     }
     if (lds_bytes > 48 * 1024 && !attr_done) {
         if (hipFuncSetAttribute((const void *)kern_full, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess ||
