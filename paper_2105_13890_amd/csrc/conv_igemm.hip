@@ -1186,6 +1186,9 @@ int launch_igemm(eoq_ctx *c, const IgemmParams &p)
         }
         return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, true, MODE, EPI>(c, p);
     }
+    if constexpr (BK == 64 && WGM * WGN == 4 && (EPI == EPI_FWD || EPI == EPI_D16 || EPI == EPI_RELU_BWD)) {
+        if (p.nk16 <= lowreg_max_nk16()) return launch_igemm_u<BM, BN, WGM, WGN, BK, 2, false, MODE, EPI>(c, p);
+    }
     return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, false, MODE, EPI>(c, p);
 }
 
