@@ -155,6 +155,12 @@ int eoq_conv_bwd_data(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, 
  *  - w_transposed non-NULL: the filters in C x R x S x K order, as written by eoq_transpose_filters from the same
  *    w; the call then skips its own transposition (a caller that updates w once per step transposes it once,
  *    off the critical path).
+ *  - spec_state non-NULL (one int32 per layer, owned by the caller, device memory, -1 before the first call and
+ *    otherwise left alone): the exponent r of the previous call.  r rarely changes from one training step to the
+ *    next, so the call first codes its sums with that exponent while taking the true max|d|; if the exponent was
+ *    right the work is done (no 16-bit intermediate is written or read), if not the call falls back to the path
+ *    described above.  The result is the same either way; *spec_state receives this call's r.  Ignored (left
+ *    untouched) for strided 1x1 filters, for stride-2 filters larger than 1x1 and when absmax_e1 is requested.
  * Requires 127^2 * R*S*K < 2^30. */
 typedef struct eoq_bwd_fuse {
     const uint32_t *mask_bits;
@@ -167,6 +173,7 @@ typedef struct eoq_bwd_fuse {
     const int8_t *w_transposed;
     const uint32_t *merge_mask_bits;
     int32_t *merge_absmax_masked;
+    int32_t *spec_state;
 } eoq_bwd_fuse;
 int eoq_conv_bwd_data_sq(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, const int8_t *w, int8_t *e4,
                          int32_t *absmax_slot, const int32_t *exp_in, int32_t exp_in_off, int32_t *exp_out,

@@ -71,10 +71,38 @@ struct IgemmParams {
     int64_t *rb_sum_e1, *rb_sum_e1t;
     int64_t *rb_part;          // per-workgroup partial sums [tiles][2] (NULL: atomics on the two slots)
     int32_t *rb_absmax;
+    // EPI_SPEC: speculative coding of the backward-data sums.  The scale quantiser's shift follows from max|d| of
+    // the whole tensor, which is only known when the launch ends -- but it rarely changes from one training step
+    // to the next.  The launch codes with the exponent of the previous step (spec[0]) and takes the true maximum on
+    // the way; the two launches behind it compare (sp_check) and either commit the staged statistics or redo the
+    // work the exact way (EPI_D16 + finishing kernel).  Results are those of the exact path in both cases.
+    const int32_t *spec;       // [0] exponent r to try (negative: none yet); EPI_D16 / finish: non-NULL = check first
+    int32_t *spec_used;        // scratch copy of spec[0], written by this launch for the two behind it
+    int8_t *sp_e4, *sp_e1;     // codes, codes under the mask (either may be NULL)
+    const uint16_t *sp_mask16; // mask of sp_e1, or of the merge statistics
+    const int8_t *sp_other;    // merge statistics against this tensor ...
+    const int32_t *sp_exp_in, *sp_exp_other;
+    int32_t sp_exp_off;
+    int64_t *sp_part;          // per-wave records {sum e4, sum e1, max merged, max merged under the mask}
 };
 
 enum { MODE_FWD = 0, MODE_BWD_DATA = 1 };
-enum { EPI_FWD = 0, EPI_ACC = 1, EPI_RELU_BWD = 4, EPI_D16 = 5 };
+enum { EPI_FWD = 0, EPI_ACC = 1, EPI_SPEC = 3, EPI_RELU_BWD = 4, EPI_D16 = 5 };
+
+// did the speculative launch use the right exponent?  (every workgroup of the two launches behind it asks)
+__device__ __forceinline__ bool spec_hit(const int32_t *absmax, const int32_t *spec_used)
+{
+    const uint32_t Mx = (uint32_t)*absmax;
+    return (Mx ? sq_exponent_u32(Mx) : 7) == *spec_used;
+}
+
+// shifts of the merge (as merge_shifts) without raising a flag: the speculative launch must have no side effect
+__device__ __forceinline__ void merge_shifts_quiet(int Ea, int Eb, int &sa, int &sb)
+{
+    const int Em = Ea < Eb ? Ea : Eb;
+    sa = Ea - Em; sb = Eb - Em;
+    sa = sa > 24 ? 24 : sa; sb = sb > 24 ? 24 : sb;
+}
 
 __device__ __forceinline__ void set_byte(v4i &v, int i, int code)
 {
@@ -206,6 +234,7 @@ template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, i
 __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
 {
     constexpr bool LOWREG = D == 2;
+    if (EPI == EPI_D16 && pin.spec && spec_hit(pin.absmax, pin.spec_used)) return;     // the speculative launch was right
     IgemmParams p = pin;           // uniform; patched below when the launch covers several classes
     constexpr int NW = WGM * WGN, NT = NW * 64;
     static_assert(NW == 4 || NW == 8, "4 or 8 waves");
@@ -612,6 +641,15 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     // bit set) -- 16 bits per element.  The final rounding position r-7 (r from the global maximum) lies at least 6
     // bits above the dropped bits of every tile, so round-half-even of the exact sum is recovered exactly from
     // (kept bits, sticky bit): the rounding bit is a kept bit and the sticky bit joins the bits below it.
+    int sp_sh = 0, sp_sa = 0, sp_sb = 0, sp_mx = 0, sp_mxm = 0, sp_tmax = 0;
+    long long sp_s1 = 0;
+    if (EPI == EPI_SPEC) {
+        int r = p.spec[0];
+        if (blockIdx.x == 0 && tid == 0) *p.spec_used = r;
+        r = r < 0 ? 7 : (r > 31 ? 31 : r);                     // nothing to try yet: any shift will do, the result is redone
+        sp_sh = r - 7;
+        if (p.sp_other) merge_shifts_quiet(*p.sp_exp_in + p.sp_exp_off + sp_sh, *p.sp_exp_other, sp_sa, sp_sb);
+    }
     int d16_s = 0;
     if (EPI == EPI_D16) {
         int mx0 = 0;
@@ -663,7 +701,7 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     constexpr int NPASS = 32 / ROWS_PER_PASS;
     v4i pre8[TM][NPASS];
     uint32_t premk[TM][NPASS];
-    if (!LOWREG && (EPI == EPI_FWD || EPI == EPI_RELU_BWD)) {
+    if (!LOWREG && (EPI == EPI_FWD || EPI == EPI_RELU_BWD || EPI == EPI_SPEC)) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -677,6 +715,9 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
                     if (EPI == EPI_FWD) {
                         if (p.ep.skip && p.ep.relu && !p.ep.skip_wide)
                             pre8[i][ps] = *(const v4i *)((const int8_t *)p.ep.skip + off);
+                    } else if (EPI == EPI_SPEC) {
+                        if (p.sp_other) pre8[i][ps] = *(const v4i *)(p.sp_other + off);
+                        if (p.sp_mask16) premk[i][ps] = (uint32_t)p.sp_mask16[off >> 4];
                     } else {
                         pre8[i][ps] = *(const v4i *)(p.rb_e0 + off);
                         if (p.rb_mask16) premk[i][ps] = (uint32_t)p.rb_mask16[off >> 4];
@@ -726,6 +767,9 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
                     } else if (EPI == EPI_RELU_BWD) {
                         side8 = *(const v4i *)(p.rb_e0 + off);
                         if (p.rb_mask16) sidemk = (uint32_t)p.rb_mask16[off >> 4];
+                    } else if (EPI == EPI_SPEC) {
+                        if (p.sp_other) side8 = *(const v4i *)(p.sp_other + off);
+                        if (p.sp_mask16) sidemk = (uint32_t)p.sp_mask16[off >> 4];
                     }
                 } else {
                     side8 = pre8[i][ps];
@@ -756,6 +800,49 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
                     sq_sum += ls;
                     rb_st += lst;
                     if (p.rb_e1) *(v4i *)(p.rb_e1 + off) = o;
+                } else if (EPI == EPI_SPEC) {
+                    // Q_e (Eq.11) with the exponent being tried: clamp(R(v * 2^-sh)); |v| < 2^30, 32 bits are exact
+                    uint32_t o4[4], o1[4];
+                    int ls4 = 0, ls1 = 0;
+                    int cd16[16];
+                    if (sp_sh <= 0) {                          // (uniform; two loops so that no element carries a branch)
+#pragma unroll
+                        for (int k = 0; k < 16; ++k) cd16[k] = sq_code32<true>(v[k], sp_sh);
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 16; ++k) cd16[k] = sq_code32<false>(v[k], sp_sh);
+                    }
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const int ax = v[k] < 0 ? -v[k] : v[k];
+                        sp_tmax = ax > sp_tmax ? ax : sp_tmax;
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int *cd = cd16 + 4 * q;
+                        const uint32_t pk = pack4_i8(cd[0], cd[1], cd[2], cd[3]);
+                        o4[q] = pk;
+                        ls4 = sum4_i8(pk, ls4);
+                        if (p.sp_e1) {
+                            const uint32_t pm = pk & byte_mask4(sidemk >> (4 * q));
+                            o1[q] = pm;
+                            ls1 = sum4_i8(pm, ls1);
+                        }
+                        if (p.sp_other) {
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) {
+                                int mv = (cd[k] << sp_sa) + (__builtin_amdgcn_sbfe(side8[q], 8 * k, 8) << sp_sb);
+                                mv = mv < 0 ? -mv : mv;
+                                sp_mx = mv > sp_mx ? mv : sp_mx;
+                                const int mm = ((sidemk >> (4 * q + k)) & 1u) ? mv : 0;
+                                sp_mxm = mm > sp_mxm ? mm : sp_mxm;
+                            }
+                        }
+                    }
+                    sq_sum += ls4;
+                    sp_s1 += ls1;
+                    if (p.sp_e4) *(v4i *)(p.sp_e4 + off) = v4i{(int)o4[0], (int)o4[1], (int)o4[2], (int)o4[3]};
+                    if (p.sp_e1) *(v4i *)(p.sp_e1 + off) = v4i{(int)o1[0], (int)o1[1], (int)o1[2], (int)o1[3]};
                 } else if (EPI == EPI_D16) {
                     const int smask = (1 << d16_s) - 1;
                     uint32_t w8[8];
@@ -788,6 +875,17 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     }
     if (EPI == EPI_FWD && range_bad) atomicOr(p.status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);
     if (EPI == EPI_ACC && p.absmax) block_atomic_max_i32(mx, p.absmax);
+    if (EPI == EPI_SPEC) {
+        // the true maximum (needed whatever the guess was) and this wave's record for the committing launch
+        const int tm = wave_max_i32(sp_tmax);
+        const int64_t a = wave_sum_i64(sq_sum), b = wave_sum_i64(sp_s1);
+        const int ma = wave_max_i32(sp_mx), mb = wave_max_i32(sp_mxm);
+        if (lane == 0) {
+            slot_atomic_max_i32(p.absmax, tm);
+            int64_t *rec = p.sp_part + 4 * (size_t)(NW * bid + wave);
+            rec[0] = a; rec[1] = b; rec[2] = ma; rec[3] = mb;
+        }
+    }
     if (EPI == EPI_RELU_BWD) {
         if (p.rb_part) {
             // thousands of workgroups adding to two slots would queue up behind each other: each wave stores its
@@ -989,6 +1087,12 @@ struct D16Finish {
     int cls_on, cls_pad;
     int cls_hh0[2], cls_ww0[2], cls_Hc[2], cls_Wc[2];
     int cls_base[4], cls_bm_shift[4], cls_bn_shift[4], cls_tiles_n[4];
+    // behind a speculative launch (see IgemmParams::spec): if its exponent was right, this kernel only commits what
+    // that launch staged -- the per-wave records of sums and maxima -- and stores the exponent for the next step
+    int32_t *spec;
+    const int32_t *spec_used;
+    const int64_t *sp_part;
+    int sp_records;
 };
 
 template <bool RELU>
@@ -1002,7 +1106,27 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
     int mg_sa = 0, mg_sb = 0, mg_mx = 0, mg_mxm = 0;
     if (p.mg_other) {
         int Em;
-        merge_shifts(E4, *p.mg_exp_other, mg_sa, mg_sb, Em, p.status);
+        merge_shifts(E4, *p.mg_exp_other, mg_sa, mg_sb, Em, p.status);     // (also on the commit path: the flag is real)
+    }
+    if (p.spec) {
+        const bool hit = r == *p.spec_used && (Mx != 0 || r == 7);
+        if (hit) {
+            // the codes are in place; add up the staged records
+            long long a = 0, b = 0;
+            int ma = 0, mb = 0;
+            for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < p.sp_records; i += gridDim.x * blockDim.x) {
+                const int64_t *rec = p.sp_part + 4 * (size_t)i;
+                a += rec[0]; b += rec[1];
+                ma = (int)rec[2] > ma ? (int)rec[2] : ma;
+                mb = (int)rec[3] > mb ? (int)rec[3] : mb;
+            }
+            if (p.sum_e4) block_atomic_add_i64(a, p.sum_e4);
+            if (RELU && p.sum_e1) block_atomic_add_i64(b, p.sum_e1);
+            if (!RELU && p.mg_other) block_atomic_max_i32(ma, p.mg_absmax);
+            if (!RELU && p.mg_mask16) block_atomic_max_i32(mb, p.mg_absmax_m);
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0) p.spec[0] = r;                // what the next step will try
+        if (hit) return;
     }
     const uint32_t c16 = (uint32_t)p.C >> 4;
     const uint32_t total = (uint32_t)p.M * c16;            // the host checked that this fits 32 bits
@@ -1180,13 +1304,13 @@ template <int BM, int BN, int WGM, int WGN, int BK, int MODE, int EPI>
 int launch_igemm(eoq_ctx *c, const IgemmParams &p)
 {
     if (p.c16 % (BK / 16) == 0) {
-        if constexpr (BK == 64 && WGM * WGN == 4 && (EPI == EPI_FWD || EPI == EPI_D16 || EPI == EPI_RELU_BWD)) {
+        if constexpr (BK == 64 && WGM * WGN == 4 && (EPI == EPI_FWD || EPI == EPI_D16 || EPI == EPI_RELU_BWD || EPI == EPI_SPEC)) {
             if (p.nk16 <= lowreg_max_nk16())
                 return launch_igemm_u<BM, BN, WGM, WGN, BK, 2, true, MODE, EPI>(c, p);
         }
         return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, true, MODE, EPI>(c, p);
     }
-    if constexpr (BK == 64 && WGM * WGN == 4 && (EPI == EPI_FWD || EPI == EPI_D16 || EPI == EPI_RELU_BWD)) {
+    if constexpr (BK == 64 && WGM * WGN == 4 && (EPI == EPI_FWD || EPI == EPI_D16 || EPI == EPI_RELU_BWD || EPI == EPI_SPEC)) {
         if (p.nk16 <= lowreg_max_nk16()) return launch_igemm_u<BM, BN, WGM, WGN, BK, 2, false, MODE, EPI>(c, p);
     }
     return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, false, MODE, EPI>(c, p);
@@ -1544,6 +1668,26 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
     } else {
     if (int rc = bwd_data_params(sub ? &dsub : d, e, wt, p)) return rc;
     p.absmax = absmax_slot;
+    // speculative launch first (see IgemmParams::spec): general gathers only, and not when max|e1| is wanted (the
+    // exact path takes it for free, here it would be one more staged maximum that no caller of this path needs)
+    int32_t *spec = (fuse && !sub && !absmax_e1) ? fuse->spec_state : nullptr;
+    const long max_tiles = (long)((p.M + 63) / 64) * ((p.NOUT + 31) / 32);
+    if (spec && 16 * max_tiles > EOQ_PARTIAL_SLOTS) spec = nullptr;
+    if (spec) {
+        IgemmParams q = p;
+        q.spec = spec; q.spec_used = c->d_scratch + 8;
+        q.sp_e4 = e4; q.sp_e1 = e1;
+        q.sp_mask16 = e1 ? (const uint16_t *)mask_bits : (const uint16_t *)mg_mask;
+        q.sp_other = mg_other;
+        q.sp_exp_in = exp_in; q.sp_exp_off = exp_in_off;
+        q.sp_exp_other = mg_other ? fuse->merge_exp_other : nullptr;
+        q.sp_part = c->d_partials;
+        int bm1 = 0, bn1 = 0, nw1 = 4;
+        if (int rc = dispatch_igemm<MODE_BWD_DATA, EPI_SPEC>(c, q, &bm1, &bn1, &nw1)) return rc;
+        f.spec = spec; f.spec_used = q.spec_used; f.sp_part = c->d_partials;
+        f.sp_records = nw1 * (int)(((p.M + bm1 - 1) / bm1) * ((p.NOUT + bn1 - 1) / bn1));
+        p.spec = spec; p.spec_used = q.spec_used;
+    }
     p.d16 = d16;
     p.tile_shift = tile_shift;
     if (int rc = dispatch_igemm<MODE_BWD_DATA, EPI_D16>(c, p, &bm, &bn)) return rc;

@@ -29,7 +29,7 @@ EXPORTS = [
 
 class BwdFuse(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("mask_bits", "e1", "sum_e1", "absmax_e1", "merge_other", "merge_exp_other",
-                                          "merge_absmax", "w_transposed", "merge_mask_bits", "merge_absmax_masked")]
+                                          "merge_absmax", "w_transposed", "merge_mask_bits", "merge_absmax_masked", "spec_state")]
 
 
 class ConvDesc(C.Structure):
@@ -185,12 +185,12 @@ class Context:
 
     def conv_bwd_data_sq(self, desc, e, w, e4, absmax_slot, exp_in, exp_in_off, exp_out, sum_out, ws,
                          mask=None, e1=None, sum_e1=None, absmax_e1=None, merge_other=None, merge_exp_other=None,
-                         merge_absmax=None, w_transposed=None, merge_mask=None, merge_absmax_masked=None):
+                         merge_absmax=None, w_transposed=None, merge_mask=None, merge_absmax_masked=None, spec_state=None):
         fuse = None
-        if e1 is not None or merge_other is not None or w_transposed is not None:
+        if e1 is not None or merge_other is not None or w_transposed is not None or spec_state is not None:
             fuse = BwdFuse(_ptr(mask), _ptr(e1), _ptr(sum_e1), _ptr(absmax_e1), _ptr(merge_other),
                            _ptr(merge_exp_other), _ptr(merge_absmax), _ptr(w_transposed), _ptr(merge_mask),
-                           _ptr(merge_absmax_masked))
+                           _ptr(merge_absmax_masked), _ptr(spec_state))
         _check(_lib.eoq_conv_bwd_data_sq(self._h, C.byref(desc), _ptr(e), _ptr(w), _ptr(e4), _ptr(absmax_slot),
                                          _ptr(exp_in), exp_in_off, _ptr(exp_out), _ptr(sum_out),
                                          C.byref(fuse) if fuse is not None else None, _ptr(ws), _nbytes(ws)),

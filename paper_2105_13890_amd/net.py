@@ -211,6 +211,8 @@ class FixupNet:
         self.ws_w = torch.empty((ws_bytes,), dtype=torch.uint8, device=self.dev)     # the side stream's own scratch
         for u in all_units:
             u.ev_e3, u.ev_dx, u.ev_done = (torch.cuda.Event() for _ in range(3))
+            # exponent of this layer's backward-data sums in the previous step (what the next step tries first)
+            u.spec = torch.full((1,), -1, dtype=torch.int32, device=self.dev)
         # ---- slots -------------------------------------------------------------------------------
         self.sl = _Slots()
         self._plan_slots()
@@ -570,7 +572,7 @@ class FixupNet:
                 self._call("conv_bwd_data", u.name, self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
                            e4_dbg, self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
                            self.s64(u.name + ".S_e4"), self.ws, w_transposed=u.wt, mask=f.mask, e1=e4[:n_in],
-                           sum_e1=self.s64(f.name + ".S_e1"),
+                           spec_state=None if self.tracing else u.spec, sum_e1=self.s64(f.name + ".S_e1"),
                            absmax_e1=self.s32(f.name + ".M_e1") if self.tracing else None)   # only Q_e(e1*gamma) reads it
                 if self.tracing:
                     self._rec(u.name + ".e4", e4_dbg)
@@ -583,7 +585,8 @@ class FixupNet:
                         mg.update(merge_mask=merge[3], merge_absmax_masked=self.s32(merge[4]))
                 self._call("conv_bwd_data", u.name, self._conv_work(u), c.conv_bwd_data_sq, u.desc, e3[:n_out], u.w,
                            e4[:n_in], self.s32(u.name + ".M_D"), self.s32(u.E3), -7, self.s32(u.E4),
-                           self.s64(u.name + ".S_e4"), self.ws, w_transposed=u.wt, **mg)
+                           self.s64(u.name + ".S_e4"), self.ws, w_transposed=u.wt,
+                           spec_state=None if self.tracing else u.spec, **mg)
                 if self.tracing:
                     self._rec(u.name + ".e4", e4[:n_in].view(u.in_shape))
         # the update, once every reader of the old weights has run: behind the next layer's wait on the side stream
