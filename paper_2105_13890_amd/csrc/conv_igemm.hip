@@ -173,21 +173,24 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
     // (alignbit(mask, -z, 31) = mask << 1 | [z > 0]; z != INT_MIN on the 32-bit path).  The three variants are
     // three separate loops: a uniform test inside the loop is not hoisted by the compiler and turns into a branch
     // per element.
-    auto put = [&](int k, int yc) {
-        const int uc = clamp_i(yc + bnext, -CODE_MAX, CODE_MAX);
-        yw[k >> 2] |= (uint32_t)yc << (8 * (k & 3));
-        uw[k >> 2] |= ((uint32_t)uc & 0xffu) << (8 * (k & 3));
-    };
+    // y codes lie in [0, 127]: they are packed as they are produced, and the next layer's biased input
+    // u = clamp(y + b_next, -127, 127) is then formed on whole dwords (see below) instead of element by element
+    auto put = [&](int k, int yc) { yw[k >> 2] |= (uint32_t)yc << (8 * (k & 3)); };
     if (FAST && gamma == 128) {
         // multiplier exactly one (every layer without a multiplier, and a block's last layer until its multiplier
         // moves): z = 128 * (t + b + skip) is a multiple of 128, so Q_a2 rounds nothing and
-        // y = clamp(t + b + skip, 0, 127), [z > 0] = [t + b + skip > 0]
+        // y = clamp(t + b + skip, 0, 127), [z > 0] = [t + b + skip > 0] = [y > 0]
 #pragma unroll
-        for (int kk = 0; kk < 16; ++kk) {
-            const int k = 15 - kk;
+        for (int k = 0; k < 16; ++k) {
             const int w = t[k] + sk[k] + bpost;
-            mask = __builtin_amdgcn_alignbit(mask, (uint32_t)(-w), 31);
             put(k, w < 0 ? 0 : (w > CODE_MAX ? CODE_MAX : w));
+        }
+        // mask bits from the packed codes: byte + 127 carries into bit 7 iff the byte is non-zero (no carry between
+        // bytes, a byte is at most 127); one multiply gathers the four bits
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t nz = ((yw[q] + 0x7f7f7f7fu) & 0x80808080u) >> 7;
+            mask |= (((nz * 0x00204081u) >> 21) & 0xfu) << (4 * q);
         }
     } else if (FAST) {
 #pragma unroll
@@ -206,6 +209,29 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
             mask = (mask << 1) | (z > 0 ? 1u : 0u);
             const int64_t yy = rne_shift64(z > 0 ? z : 0, 7);
             put(k, (int)(yy > CODE_MAX ? CODE_MAX : yy));
+        }
+    }
+    if (ep.u_next) {
+        // bytes of yw are in [0, 127]
+        if (bnext >= 0) {
+            // min(y + b, 127): the byte sums stay below 256; a sum with bit 7 set saturates to 127
+            const uint32_t b4 = (uint32_t)(bnext > CODE_MAX ? CODE_MAX : bnext) * 0x01010101u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t sm = yw[q] + b4, ov = sm & 0x80808080u;
+                uw[q] = (sm | (ov - (ov >> 7))) & 0x7f7f7f7fu;
+            }
+        } else if (bnext >= -CODE_MAX) {
+            // y + b lies in [-127, 126]: no clamp; add the low seven bits (no carry between bytes), then fix bit 7
+            const uint32_t b4 = ((uint32_t)bnext & 0xffu) * 0x01010101u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) uw[q] = (yw[q] + (b4 & 0x7f7f7f7fu)) ^ 0x80808080u;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const int uc = clamp_i((int)((yw[k >> 2] >> (8 * (k & 3))) & 0xffu) + bnext, -CODE_MAX, CODE_MAX);
+                uw[k >> 2] |= ((uint32_t)uc & 0xffu) << (8 * (k & 3));
+            }
         }
     }
     if (ep.y) *(v4i *)(ep.y + off) = v4i{(int)yw[0], (int)yw[1], (int)yw[2], (int)yw[3]};

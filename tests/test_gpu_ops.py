@@ -78,7 +78,11 @@ def test_conv_fwd_fused_epilogue(ctx, d):
     u = si.uniform_int8(1, "u", (d.N, d.H, d.W, d.C))
     w = si.uniform_int8(1, "w", (d.K, d.R, d.S, d.C), -30, 30)
     oshape = (d.N, d.P, d.Q, d.K)
-    for case, (gam, bpost, bnext, skip_kind) in enumerate([(None, 3, -2, None), (117, -5, 4, "i8"), (140, 2, 0, "wide")]):
+    cases = [(None, 3, -2, None), (117, -5, 4, "i8"), (140, 2, 0, "wide"),
+             # the next layer's bias at and beyond the ends of the int8 range (u = clamp(y + b) saturates / never clamps)
+             (None, 0, 127, None), (None, 1, 300, "i8"), (None, -1, -127, None), (None, 2, -128, "i8"),
+             (117, 0, -300, "i8"), (None, 0, 90, "i8"), (131, 0, -90, None)]
+    for case, (gam, bpost, bnext, skip_kind) in enumerate(cases):
         skip = None
         if skip_kind == "i8":
             skip = si.uniform_int8(2, "skip", oshape, 0, 127)
