@@ -21,7 +21,7 @@ PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
 # HBM bytes per forward-igemm launch of the ResNet-50 / batch-128 step, from two rocprofv3 --pmc runs (FETCH_SIZE,
 # WRITE_SIZE) scaled by a 1 GiB elementwise kernel: profiles/resnet50_b128_step_hbm_traffic.txt
-MEASURED_FWD_TRAFFIC_BYTES = {"resnet50": 105.3e6}
+MEASURED_FWD_TRAFFIC_BYTES = {"resnet50": 105.4e6}
 
 # learning rate m * 2^-j per workload.  With one learning rate for weights and scalars and deterministic
 # rounding, a rate large enough to move >= 1% of the int8 weight codes per step drives the biases far enough
