@@ -487,8 +487,8 @@ int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int *splits_out)
     static int target_wgs = 0;
     if (!target_wgs) {
         const char *e = getenv("EOQ_WGRAD_WGS");     // tuning aid: workgroups aimed for when splitting the reduction
-        target_wgs = e ? atoi(e) : 256;
-        if (target_wgs < 1) target_wgs = 256;
+        target_wgs = e ? atoi(e) : 448;
+        if (target_wgs < 1) target_wgs = 448;
     }
     int splits = target_wgs / tiles;
     if (splits < 1) splits = 1;
