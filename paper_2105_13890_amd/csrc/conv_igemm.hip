@@ -1374,7 +1374,8 @@ int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in, int *bm_out = nullptr, i
     // so small tiles win through occupancy and grid size; the 128x128 tile pays off only for wide outputs with
     // enough workgroups to fill the chip.
     if (nout <= 32) { chosen(128, 32); return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p); }
-    if (nout >= 128 && wgs(128, 128) >= 256) {
+    static const long min128 = [] { const char *e = getenv("EOQ_MIN128"); return e ? atol(e) : 256l; }();
+    if (nout >= 128 && wgs(128, 128) >= min128) {
         chosen(128, 128);
         // The forward epilogue with int8 outputs stacks the four waves along M, so that a wave owns whole 128-byte
         // output rows and its stores fill cache lines (measured: 3-9 % on the wide 1x1 layers, a loss elsewhere).
