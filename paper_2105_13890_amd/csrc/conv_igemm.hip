@@ -813,6 +813,16 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
                     // |x2| <= 127^2 * (reduction length) / 128 and |e| <= 127: for reductions of up to 8192
                     // terms sixteen products sum to less than 2^31 and are added in 32 bits
                     const bool narrow = p.nk16 <= 512;
+                    if (narrow && !p.rb_e1 && !p.rb_absmax && !p.rb_mask16) {
+                        // sums only (the multiplier's gradient): no codes to store, no mask, no maximum
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            ls = sum4_i8((uint32_t)ev[q], ls);
+#pragma unroll
+                            for (int k = 0; k < 4; ++k)
+                                lst += __mul24(__builtin_amdgcn_sbfe(ev[q], 8 * k, 8), rne_shift7(v[4 * q + k]));
+                        }
+                    } else
 #pragma unroll
                     for (int k = 0; k < 16; ++k) {
                         const int e = ((mk >> k) & 1u) ? byte_at(ev, k) : 0;
