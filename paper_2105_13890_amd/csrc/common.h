@@ -66,7 +66,10 @@ __device__ __forceinline__ int sq_code32(int v, int s)      // clamp(R(v * 2^-s)
 // four codes in [-127, 127] -> one dword of bytes
 __device__ __forceinline__ uint32_t pack4_i8(int c0, int c1, int c2, int c3)
 {
-    return ((uint32_t)c0 & 0xffu) | (((uint32_t)c1 & 0xffu) << 8) | (((uint32_t)c2 & 0xffu) << 16) | ((uint32_t)c3 << 24);
+    // v_perm_b32: selector bytes 0-3 take bytes of the second operand, 4-7 of the first, 0x0c gives zero
+    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)c1, (uint32_t)c0, 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)c3, (uint32_t)c2, 0x0c0c0400u);
+    return lo | (hi << 16);
 }
 
 // 4 mask bits (bit k for byte k) -> 0xff in every byte whose bit is set
