@@ -667,7 +667,7 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     // bit set) -- 16 bits per element.  The final rounding position r-7 (r from the global maximum) lies at least 6
     // bits above the dropped bits of every tile, so round-half-even of the exact sum is recovered exactly from
     // (kept bits, sticky bit): the rounding bit is a kept bit and the sticky bit joins the bits below it.
-    int sp_sh = 0, sp_sa = 0, sp_sb = 0, sp_mx = 0, sp_mxm = 0, sp_tmax = 0;
+    int sp_sh = 0, sp_sa = 0, sp_sb = 0, sp_mx = 0, sp_mxm = 0, sp_tmax = 0, sp_tmin = 0;
     long long sp_s1 = 0;
     if (EPI == EPI_SPEC) {
         int r = p.spec[0];
@@ -678,18 +678,20 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     }
     int d16_s = 0;
     if (EPI == EPI_D16) {
-        int mx0 = 0;
+        int mx0 = 0, mn0 = 0;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int jn = 0; jn < TN; ++jn)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int v = acc[i][jn][e];
-                    const int av = v < 0 ? -v : v;
-                    mx0 = av > mx0 ? av : mx0;
+                for (int e = 0; e < 16; e += 2) {
+                    // largest and smallest value, two elements per max3 / min3 (one instruction per element; |v| via
+                    // negate-and-max would take two)
+                    const int a = acc[i][jn][e], b = acc[i][jn][e + 1];
+                    mx0 = max(max(mx0, a), b);
+                    mn0 = min(min(mn0, a), b);
                 }
-        mx0 = wave_max_i32(mx0);
+        mx0 = wave_max_i32(max(mx0, -mn0));
         int *red = (int *)lds;                       // the main loop is done with LDS (barrier above)
         if (lane == 0) red[wave] = mx0;
         __syncthreads();
@@ -849,9 +851,9 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
                         for (int k = 0; k < 16; ++k) cd16[k] = sq_code32<false>(v[k], sp_sh);
                     }
 #pragma unroll
-                    for (int k = 0; k < 16; ++k) {
-                        const int ax = v[k] < 0 ? -v[k] : v[k];
-                        sp_tmax = ax > sp_tmax ? ax : sp_tmax;
+                    for (int k = 0; k < 16; k += 2) {          // running maximum and minimum: max|v| = max(hi, -lo)
+                        sp_tmax = max(max(sp_tmax, v[k]), v[k + 1]);
+                        sp_tmin = min(min(sp_tmin, v[k]), v[k + 1]);
                     }
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -913,7 +915,7 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     if (EPI == EPI_ACC && p.absmax) block_atomic_max_i32(mx, p.absmax);
     if (EPI == EPI_SPEC) {
         // the true maximum (needed whatever the guess was) and this wave's record for the committing launch
-        const int tm = wave_max_i32(sp_tmax);
+        const int tm = wave_max_i32(max(sp_tmax, -sp_tmin));
         const int64_t a = wave_sum_i64(sq_sum), b = wave_sum_i64(sp_s1);
         const int ma = wave_max_i32(sp_mx), mb = wave_max_i32(sp_mxm);
         if (lane == 0) {
