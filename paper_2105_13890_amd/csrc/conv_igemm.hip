@@ -723,36 +723,40 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     }
     int mx = 0;
     uint32_t range_bad = 0;
-    // Side inputs of the epilogue (shortcut values; incoming error and mask words for the ReLU backward step) for
-    // ALL chunks this thread will process, requested before the first chunk is staged: the registers of the main
-    // loop's load ring are free by now, and the memory latency is paid once instead of once per chunk.
+    // Side inputs of the epilogue (shortcut values; incoming error and mask words for the ReLU backward step) are
+    // requested ahead of the chunk that uses them, so that their latency is not paid chunk by chunk.  The pipelined
+    // form asks for ALL chunks of the thread before the first is staged (the registers of the main loop's load ring
+    // are free by now); the low-register form keeps PD chunks in flight and refills a slot as soon as it is consumed.
     constexpr int NPASS = 32 / ROWS_PER_PASS;
-    v4i pre8[TM][NPASS];
-    uint32_t premk[TM][NPASS];
-    if (!LOWREG && (EPI == EPI_FWD || EPI == EPI_RELU_BWD || EPI == EPI_SPEC)) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int ps = 0; ps < NPASS; ++ps) {
-                const int m = m0 + wm * WTM + i * 32 + ps * ROWS_PER_PASS + prow;
-                const int ch = n0 + wn * WTN + grp * 16;
-                pre8[i][ps] = v4i{0, 0, 0, 0};
-                premk[i][ps] = 0xffffu;
-                if (m < p.M && ch < p.NOUT) {
-                    const size_t off = (size_t)m * p.NOUT + ch;
-                    if (EPI == EPI_FWD) {
-                        if (p.ep.skip && p.ep.relu && !p.ep.skip_wide)
-                            pre8[i][ps] = *(const v4i *)((const int8_t *)p.ep.skip + off);
-                    } else if (EPI == EPI_SPEC) {
-                        if (p.sp_other) pre8[i][ps] = *(const v4i *)(p.sp_other + off);
-                        if (p.sp_mask16) premk[i][ps] = (uint32_t)p.sp_mask16[off >> 4];
-                    } else {
-                        pre8[i][ps] = *(const v4i *)(p.rb_e0 + off);
-                        if (p.rb_mask16) premk[i][ps] = (uint32_t)p.rb_mask16[off >> 4];
-                    }
-                }
+    constexpr int TP = TM * NPASS;                                   // chunks per thread
+    constexpr bool HAS_SIDE = EPI == EPI_FWD || EPI == EPI_RELU_BWD || EPI == EPI_SPEC;
+    // (the 2 x 2 forward layout with 128-column tiles serves the layers without ReLU, which have no int8 side input,
+    // and is short of registers as it is)
+    constexpr bool NO_RING = LOWREG && EPI == EPI_FWD && WGN == 2 && BN == 128;
+    constexpr int PD = !HAS_SIDE || NO_RING ? 0 : (!LOWREG ? TP : (TP < 2 ? TP : 2));
+    v4i ring8[PD > 0 ? PD : 1];
+    uint32_t ringmk[PD > 0 ? PD : 1];
+    auto load_side = [&](int t, v4i &s8, uint32_t &smk) {
+        const int i = t / NPASS, ps = t % NPASS;
+        const int m = m0 + wm * WTM + i * 32 + ps * ROWS_PER_PASS + prow;
+        const int ch = n0 + wn * WTN + grp * 16;
+        s8 = v4i{0, 0, 0, 0};
+        smk = 0xffffu;
+        if (m < p.M && ch < p.NOUT) {
+            const size_t off = (size_t)m * p.NOUT + ch;
+            if (EPI == EPI_FWD) {
+                if (p.ep.skip && p.ep.relu && !p.ep.skip_wide) s8 = *(const v4i *)((const int8_t *)p.ep.skip + off);
+            } else if (EPI == EPI_SPEC) {
+                if (p.sp_other) s8 = *(const v4i *)(p.sp_other + off);
+                if (p.sp_mask16) smk = (uint32_t)p.sp_mask16[off >> 4];
+            } else if (EPI == EPI_RELU_BWD) {
+                s8 = *(const v4i *)(p.rb_e0 + off);
+                if (p.rb_mask16) smk = (uint32_t)p.rb_mask16[off >> 4];
             }
-    }
+        }
+    };
+#pragma unroll
+    for (int t = 0; t < PD; ++t) load_side(t, ring8[t], ringmk[t]);
     // SR rows of a 32-row accumulator block are staged at a time: 16 where a pass covers at most 16 rows, which
     // halves the staging area -- for 128-column wave tiles that is the difference between two and four workgroups
     // per compute unit
@@ -779,6 +783,18 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
                 v4i w = *(const v4i *)(stg + (row - hf * SR) * EPI_LD + grp * 16 + 4 * k4);
                 v[4 * k4] = w[0]; v[4 * k4 + 1] = w[1]; v[4 * k4 + 2] = w[2]; v[4 * k4 + 3] = w[3];
             }
+            v4i side8 = v4i{0, 0, 0, 0};
+            uint32_t sidemk = 0xffffu;
+            if (HAS_SIDE) {
+                const int t = i * NPASS + ps;
+                if (PD > 0) {
+                    side8 = ring8[t % (PD > 0 ? PD : 1)];
+                    sidemk = ringmk[t % (PD > 0 ? PD : 1)];
+                    if (t + PD < TP) load_side(t + PD, ring8[t % (PD > 0 ? PD : 1)], ringmk[t % (PD > 0 ? PD : 1)]);
+                } else {
+                    load_side(t, side8, sidemk);
+                }
+            }
             if (m < p.M && ch < p.NOUT) {
                 size_t off = (size_t)m * p.NOUT + ch;
                 if (EPI == EPI_D16 && p.rm_on) {
@@ -786,22 +802,6 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
                     const int n = m / hw, r = m - n * hw;
                     const int gh = r / p.rm_Wc, gw = r - gh * p.rm_Wc;
                     off = ((size_t)(n * p.rm_H + 2 * gh + p.rm_h0) * p.rm_W + 2 * gw + p.rm_w0) * p.NOUT + ch;
-                }
-                v4i side8 = v4i{0, 0, 0, 0};
-                uint32_t sidemk = 0xffffu;
-                if (LOWREG) {
-                    if (EPI == EPI_FWD) {
-                        if (p.ep.skip && p.ep.relu && !p.ep.skip_wide) side8 = *(const v4i *)((const int8_t *)p.ep.skip + off);
-                    } else if (EPI == EPI_RELU_BWD) {
-                        side8 = *(const v4i *)(p.rb_e0 + off);
-                        if (p.rb_mask16) sidemk = (uint32_t)p.rb_mask16[off >> 4];
-                    } else if (EPI == EPI_SPEC) {
-                        if (p.sp_other) side8 = *(const v4i *)(p.sp_other + off);
-                        if (p.sp_mask16) sidemk = (uint32_t)p.sp_mask16[off >> 4];
-                    }
-                } else {
-                    side8 = pre8[i][ps];
-                    sidemk = premk[i][ps];
                 }
                 if (EPI == EPI_FWD) {
                     if (fast) epilogue16<true>(v, off, p.ep, p.acc_out, gamma, bpost, bnext, range_bad, side8);
