@@ -98,10 +98,13 @@ int eoq_quantize(eoq_ctx *ctx, const float *x, size_t n, int mode, int pre_shift
  *   relu = 1:  y = clamp(R(max(z,0) / 128), 0, 127)   Q_a2;  mask bit = [z > 0]
  *              u_next = clamp(y + b_next_pre, -127, 127)   the next layer's x1 (Eq.2 line 2)
  *   relu = 0:  only t_wide is produced (1x1 shortcut convolution)
- * skip: the residual input of the block, NPQK layout, int8 codes (skip_is_wide = 0) or int32 codes on
- * the 2^-7 grid (skip_is_wide = 1; |value| < 2^22, which every Q_a1 output of a convolution with
+ * skip: the residual input of the block, NPQK layout, int8 codes (skip_is_wide = 0) or wide codes on
+ * the 2^-7 grid: int32 (skip_is_wide = 1; |value| < 2^22, which every Q_a1 output of a convolution with
  * R*S*C < 33000 satisfies -- a larger value sets EOQ_FLAG_ACC_OVERFLOW and the outputs of the call are
- * not valid).  Outputs that are NULL are not written.  relu_mask_bits holds one
+ * not valid) or int16 (skip_is_wide = 2).  t_wide receives t as int32, or as int16 when t_wide_is_16 = 1
+ * (t_wide then points to int16_t[n]; the caller chooses this when 127^2 * R*S*C / 128 < 2^15, i.e. R*S*C <= 260;
+ * a value that does not fit sets EOQ_FLAG_ACC_OVERFLOW).  The 16-bit forms halve the traffic of a shortcut
+ * convolution's output; the values are the same.  Outputs that are NULL are not written.  relu_mask_bits holds one
  * bit per output element: bit (i % 32) of word (i / 32), i = linear NPQK index.  Scalars are read from
  * device memory at kernel time. */
 typedef struct eoq_epilogue {
@@ -115,6 +118,7 @@ typedef struct eoq_epilogue {
     int8_t *u_next;
     uint32_t *relu_mask_bits;
     int32_t *t_wide;
+    int32_t t_wide_is_16;
 } eoq_epilogue;
 
 /* ---- Eq.2 line x1: u = clamp(a + b_pre, -127, 127) on int8 codes (b_pre: device scalar code) -- */

@@ -26,7 +26,8 @@ namespace {
 struct EpiDev {
     const int32_t *gamma, *b_post, *b_next;
     const void *skip;
-    int skip_wide, relu;
+    int skip_wide, relu;             // skip_wide: 0 = int8 codes, 1 = int32, 2 = int16
+    int t16;                         // t_wide points to int16 instead of int32
     int8_t *y, *u_next;
     uint16_t *mask16;
     int32_t *t_wide;
@@ -137,16 +138,41 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
 #pragma unroll
     for (int k = 0; k < 16; ++k) t[k] = rne_shift7(acc[k]);
     if (ep.t_wide) {
+        if (ep.t16) {
+            // 16-bit store (the caller knows |t| < 2^15 from the reduction length; a value that does not fit is
+            // reported through the status word)
+            uint32_t w2[8];
 #pragma unroll
-        for (int k4 = 0; k4 < 4; ++k4) {
-            v4i w = {t[4 * k4], t[4 * k4 + 1], t[4 * k4 + 2], t[4 * k4 + 3]};
-            ((v4i *)(ep.t_wide + off))[k4] = w;
+            for (int k = 0; k < 16; k += 2) {
+                range_bad |= (uint32_t)(t[k] ^ __builtin_amdgcn_sbfe(t[k], 0, 16)) |
+                             (uint32_t)(t[k + 1] ^ __builtin_amdgcn_sbfe(t[k + 1], 0, 16));
+                w2[k >> 1] = ((uint32_t)t[k] & 0xffffu) | ((uint32_t)t[k + 1] << 16);
+            }
+            v4i *dst = (v4i *)((int16_t *)ep.t_wide + off);
+            dst[0] = v4i{(int)w2[0], (int)w2[1], (int)w2[2], (int)w2[3]};
+            dst[1] = v4i{(int)w2[4], (int)w2[5], (int)w2[6], (int)w2[7]};
+        } else {
+#pragma unroll
+            for (int k4 = 0; k4 < 4; ++k4) {
+                v4i w = {t[4 * k4], t[4 * k4 + 1], t[4 * k4 + 2], t[4 * k4 + 3]};
+                ((v4i *)(ep.t_wide + off))[k4] = w;
+            }
         }
     }
     if (!ep.relu) return;
     int sk[16];
     if (ep.skip) {
-        if (ep.skip_wide) {
+        if (ep.skip_wide == 2) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const v4i w = ((const v4i *)((const int16_t *)ep.skip + off))[h];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    sk[8 * h + 2 * j] = __builtin_amdgcn_sbfe(w[j], 0, 16);
+                    sk[8 * h + 2 * j + 1] = w[j] >> 16;
+                }
+            }
+        } else if (ep.skip_wide) {
 #pragma unroll
             for (int k4 = 0; k4 < 4; ++k4) {
                 const v4i w = ((const v4i *)((const int32_t *)ep.skip + off))[k4];
@@ -245,7 +271,7 @@ __device__ __forceinline__ void epilogue16(const int acc[16], size_t off, const 
 __device__ __forceinline__ bool epilogue_fits32(const EpiDev &ep, int gamma, int bpost, long long tmax)
 {
     const long long ag = gamma < 0 ? -(long long)gamma : gamma, ab = bpost < 0 ? -(long long)bpost : bpost;
-    const long long sk = ep.skip ? (ep.skip_wide ? (1ll << 22) : 127) : 0;
+    const long long sk = ep.skip ? (ep.skip_wide == 1 ? (1ll << 22) : (ep.skip_wide == 2 ? (1ll << 15) : 127)) : 0;
     return ag < (1 << 23) && tmax < (1 << 23) && ag * tmax + 128 * (ab + sk) < (1ll << 31) - 256;
 }
 
@@ -1409,7 +1435,8 @@ int fill_epi(const eoq_epilogue *e, EpiDev &o)
 {
     o.gamma = e->gamma; o.b_post = e->b_post; o.b_next = e->b_next_pre; o.skip = e->skip;
     o.skip_wide = e->skip_is_wide; o.relu = e->relu; o.y = e->y; o.u_next = e->u_next;
-    o.mask16 = (uint16_t *)e->relu_mask_bits; o.t_wide = e->t_wide;
+    o.mask16 = (uint16_t *)e->relu_mask_bits; o.t_wide = e->t_wide; o.t16 = e->t_wide_is_16;
+    if (e->skip_is_wide < 0 || e->skip_is_wide > 2 || e->t_wide_is_16 < 0 || e->t_wide_is_16 > 1) return EOQ_ERR_ARG;
     uintptr_t al = (uintptr_t)e->skip | (uintptr_t)e->y | (uintptr_t)e->u_next | (uintptr_t)e->t_wide;
     if ((al & 15) || ((uintptr_t)e->relu_mask_bits & 3)) return EOQ_ERR_ARG;
     if (!e->relu && !e->t_wide) return EOQ_ERR_ARG;

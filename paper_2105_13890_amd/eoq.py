@@ -47,7 +47,7 @@ class ConvDesc(C.Structure):
 class Epilogue(C.Structure):
     _fields_ = [("gamma", C.c_void_p), ("b_post", C.c_void_p), ("skip", C.c_void_p), ("skip_is_wide", C.c_int32),
                 ("relu", C.c_int32), ("b_next_pre", C.c_void_p), ("y", C.c_void_p), ("u_next", C.c_void_p),
-                ("relu_mask_bits", C.c_void_p), ("t_wide", C.c_void_p)]
+                ("relu_mask_bits", C.c_void_p), ("t_wide", C.c_void_p), ("t_wide_is_16", C.c_int32)]
 
 
 class RequantArgs(C.Structure):
@@ -168,9 +168,12 @@ class Context:
     @staticmethod
     def epilogue(gamma=None, b_post=None, skip=None, relu=1, b_next_pre=None, y=None, u_next=None, mask=None,
                  t_wide=None) -> Epilogue:
-        wide = 1 if (skip is not None and not isinstance(skip, int) and skip.dtype == torch.int32) else 0
+        wide = 0
+        if skip is not None and not isinstance(skip, int):
+            wide = {torch.int32: 1, torch.int16: 2}.get(skip.dtype, 0)
+        t16 = 1 if (t_wide is not None and not isinstance(t_wide, int) and t_wide.dtype == torch.int16) else 0
         return Epilogue(_ptr(gamma), _ptr(b_post), _ptr(skip), wide, relu, _ptr(b_next_pre), _ptr(y), _ptr(u_next),
-                        _ptr(mask), _ptr(t_wide))
+                        _ptr(mask), _ptr(t_wide), t16)
 
     def conv_fwd(self, desc, u, w, acc=None, ep: Epilogue | None = None, ws=None):
         _check(_lib.eoq_conv_fwd(self._h, C.byref(desc), _ptr(u), _ptr(w), _ptr(acc),

@@ -179,7 +179,13 @@ class FixupNet:
             n_out = int(np.prod(u.out_shape))
             if u.relu:
                 u.mask = i32(((n_out + 31) // 32,))
-            if not u.relu or (u.gamma and trace):
+            if not u.relu:
+                # shortcut convolution: its output is read once more, as the wide skip input of the block's last
+                # layer.  |t| <= 127^2 * R*S*C / 128 fits 16 bits for R*S*C <= 260, which halves that traffic.
+                d = u.desc
+                narrow = 127 * 127 * d.R * d.S * d.C // 128 + 1 < 2 ** 15
+                u.t = torch.empty(u.out_shape, dtype=torch.int16 if narrow else torch.int32, device=self.dev)
+            elif u.gamma and trace:
                 u.t = i32(u.out_shape)       # multiplier layers: x2 is recomputed in the backward pass, stored only for inspection
         if self.stem:
             self.a0 = i8(self.stem.in_shape)

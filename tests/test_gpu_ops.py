@@ -78,7 +78,7 @@ def test_conv_fwd_fused_epilogue(ctx, d):
     u = si.uniform_int8(1, "u", (d.N, d.H, d.W, d.C))
     w = si.uniform_int8(1, "w", (d.K, d.R, d.S, d.C), -30, 30)
     oshape = (d.N, d.P, d.Q, d.K)
-    cases = [(None, 3, -2, None), (117, -5, 4, "i8"), (140, 2, 0, "wide"),
+    cases = [(None, 3, -2, None), (117, -5, 4, "i8"), (140, 2, 0, "wide"), (None, -3, 1, "wide16"), (119, 4, -2, "wide16"),
              # the next layer's bias at and beyond the ends of the int8 range (u = clamp(y + b) saturates / never clamps)
              (None, 0, 127, None), (None, 1, 300, "i8"), (None, -1, -127, None), (None, 2, -128, "i8"),
              (117, 0, -300, "i8"), (None, 0, 90, "i8"), (131, 0, -90, None)]
@@ -88,6 +88,9 @@ def test_conv_fwd_fused_epilogue(ctx, d):
             skip = si.uniform_int8(2, "skip", oshape, 0, 127)
         elif skip_kind == "wide":
             skip = (si.uniform_int8(2, "skipw", oshape).astype(np.int32) * 9)
+        elif skip_kind == "wide16":             # 16-bit wide shortcut values, up to the ends of the int16 range
+            skip = (si.uniform_int8(2, "skipw", oshape).astype(np.int32) * 258).astype(np.int16)
+            skip.reshape(-1)[:3] = [32767, -32768, 0]
         y, un, tw = zeros(oshape, torch.int8), zeros(oshape, torch.int8), zeros(oshape, torch.int32)
         n = int(np.prod(oshape))
         mask = zeros(((n + 31) // 32,), torch.int32)
@@ -97,7 +100,7 @@ def test_conv_fwd_fused_epilogue(ctx, d):
                           relu=1, b_next_pre=sc[2:3], y=y, u_next=un, mask=mask, t_wide=tw)
         ctx.conv_fwd(desc_of(d), dev(u), dev(w), ep=ep, ws=ws_for(d, eoq.OP_CONV_FWD))
         t = oo.q_a1(oo.conv_fwd(d, u, w))
-        z = oo.post_conv(t, gam if gam is not None else 128, bpost, skip)
+        z = oo.post_conv(t, gam if gam is not None else 128, bpost, skip.astype(np.int64) if skip is not None else None)
         yo, mo = oo.relu_q_a2(z)
         assert np.array_equal(host(tw), t), case
         assert np.array_equal(host(y), yo), case
@@ -109,6 +112,32 @@ def test_conv_fwd_fused_epilogue(ctx, d):
     ep = ctx.epilogue(relu=0, t_wide=tw)
     ctx.conv_fwd(desc_of(d), dev(u), dev(w), ep=ep, ws=ws_for(d, eoq.OP_CONV_FWD))
     assert np.array_equal(host(tw), oo.q_a1(oo.conv_fwd(d, u, w)))
+    # the same as 16-bit values: exact when they fit, flagged when one does not
+    t_ref = oo.q_a1(oo.conv_fwd(d, u, w))
+    c2 = eoq.Context()
+    tw16 = zeros(oshape, torch.int16)
+    ep = c2.epilogue(relu=0, t_wide=tw16)
+    c2.conv_fwd(desc_of(d), dev(u), dev(w), ep=ep, ws=ws_for(d, eoq.OP_CONV_FWD))
+    fits = np.abs(t_ref).max() < 2 ** 15
+    if fits:
+        assert np.array_equal(host(tw16), t_ref) and c2.status() == 0
+    else:
+        assert c2.status() & eoq.FLAG_ACC_OVERFLOW
+    c2.close()
+
+
+def test_conv_fwd_t16_overflow_is_flagged():
+    """A reduction long enough for |t| >= 2^15 with a 16-bit t output must raise the status flag."""
+    from paper_2105_13890_amd import eoq
+    c = eoq.Context()
+    d = ConvShape(1, 4, 4, 512, 16, 1, 1, 1, 0)
+    u = np.full((d.N, d.H, d.W, d.C), 127, dtype=np.int8)
+    w = np.full((d.K, 1, 1, d.C), 127, dtype=np.int8)          # t = 127^2 * 512 / 128 = 64516
+    tw16 = zeros((d.N, d.P, d.Q, d.K), torch.int16)
+    ep = c.epilogue(relu=0, t_wide=tw16)
+    c.conv_fwd(desc_of(d), dev(u), dev(w), ep=ep, ws=ws_for(d, eoq.OP_CONV_FWD))
+    assert c.status() & eoq.FLAG_ACC_OVERFLOW
+    c.close()
 
 
 def test_conv_fwd_epilogue_wide_ranges():
