@@ -21,7 +21,7 @@ PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
 # HBM bytes per forward-igemm launch of the ResNet-50 / batch-128 step, from two rocprofv3 --pmc runs (FETCH_SIZE,
 # WRITE_SIZE) scaled by a 1 GiB elementwise kernel: profiles/resnet50_b128_step_hbm_traffic.txt
-MEASURED_FWD_TRAFFIC_BYTES = {"resnet50": 105.4e6}
+MEASURED_FWD_TRAFFIC_BYTES = {"resnet50": 93.7e6}
 
 # learning rate m * 2^-j per workload.  With one learning rate for weights and scalars and deterministic
 # rounding, a rate large enough to move >= 1% of the int8 weight codes per step drives the biases far enough
@@ -137,12 +137,13 @@ def main():
         d = u.desc
         n_out = d.N * d.P * d.Q * d.K
         fwd_bytes += d.N * d.H * d.W * d.C + d.K * d.R * d.S * d.C
-        fwd_bytes += 4 * n_out if not u.relu else n_out / 8 + n_out          # wide shortcut conv | mask + one int8 out
+        # wide shortcut conv output (2 or 4 bytes per element, as allocated) | mask + one int8 out
+        fwd_bytes += u.t.element_size() * n_out if not u.relu else n_out / 8 + n_out
     for b in net.blocks:
         last = b.units[-1].desc
         n_out = last.N * last.P * last.Q * last.K
         fwd_bytes += n_out                                                      # block outputs are written twice (y, u_next)
-        fwd_bytes += 4 * n_out if b.ds else n_out                               # shortcut read
+        fwd_bytes += b.ds.t.element_size() * n_out if b.ds else n_out           # shortcut read
     agg = {}
     rows = []
     for kind, unit, work, e0, e1 in prof_list:
