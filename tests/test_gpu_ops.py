@@ -601,3 +601,46 @@ def test_head_bit_exact(ctx, N, F, J, HW):
     lrf = m * 2.0 ** -j
     assert np.array_equal(host(Wd), Wfc - lrf * dW_o)
     assert np.array_equal(host(bd), bfc - lrf * db_o)
+
+
+def test_empty_inputs_and_rejected_arguments(ctx):
+    """Edge cases that never reach a kernel's arithmetic: empty tensors are accepted and write nothing but the
+    documented exponent; shapes, alignments and workspaces outside the contract are refused on the host with the
+    documented code, before anything is launched."""
+    from paper_2105_13890_amd import eoq
+    # ---- empty inputs
+    slot = torch.full((1,), 5, dtype=torch.int32, device="cuda")
+    q8 = torch.full((16,), 7, dtype=torch.int8, device="cuda")
+    empty_f = torch.empty((0,), dtype=torch.float32, device="cuda")
+    ctx.quantize(empty_f, eoq.SQ, 0, q8[:0], slot)
+    assert int(host(slot)[0]) == 0 and (host(q8) == 7).all()       # all-zero (here: empty) tensor: exponent 0
+    ctx.quantize(empty_f, eoq.CQ, -2, q8[:0])
+    sc = dev(np.array([3], dtype=np.int32))
+    ctx.pre_bias(q8[:0], sc, q8[:0])
+    assert (host(q8) == 7).all() and ctx.status() == 0
+    # ---- refused on the host
+    def refused(code, fn, *a, **k):
+        with pytest.raises(eoq.EoqError) as ei:
+            fn(*a, **k)
+        assert f"(code {code})" in str(ei.value), str(ei.value)
+    d = ConvShape(2, 8, 8, 32, 32, 3, 3, 1, 1)
+    u, w = dev(si.uniform_int8(40, "u", (2, 8, 8, 32))), dev(si.uniform_int8(40, "w", (32, 3, 3, 32)))
+    acc = zeros((2, 8, 8, 32), torch.int32)
+    bad_k = eoq.ConvDesc(2, 8, 8, 32, 24, 3, 3, 1, 1)                 # output channels not a multiple of 16
+    refused(eoq.ERR_SHAPE, ctx.conv_fwd, bad_k, u, w, acc=acc)
+    no_out = eoq.ConvDesc(2, 2, 2, 32, 32, 5, 5, 1, 0)               # filter larger than the padded input
+    refused(eoq.ERR_SHAPE, ctx.conv_fwd, no_out, u, w, acc=acc)
+    flat = zeros((2 * 8 * 8 * 32 + 16,), torch.int8)
+    refused(eoq.ERR_ARG, ctx.conv_fwd, desc_of(d), flat[1:1 + 2 * 8 * 8 * 32], w, acc=acc)      # misaligned input
+    refused(eoq.ERR_ARG, ctx.conv_fwd, desc_of(d), u, w, ep=ctx.epilogue(relu=0))              # no output asked for
+    refused(eoq.ERR_ARG, ctx.quantize, dev(np.zeros(4, dtype=np.float32)), 7, 0, q8[:4])        # unknown mode
+    e = dev(si.uniform_int8(40, "e", (2, 8, 8, 32)))
+    g = zeros((32, 3, 3, 32), torch.int32)
+    small_ws = zeros((16,), torch.uint8)
+    if eoq.Context.workspace_bytes(desc_of(d), eoq.OP_CONV_BWD_WEIGHT) > 16:
+        refused(eoq.ERR_WORKSPACE, ctx.conv_bwd_weight, desc_of(d), e, u, g, slot, small_ws)
+    refused(eoq.ERR_WORKSPACE, ctx.conv_bwd_data, desc_of(d), e, w, acc, slot, small_ws)
+    assert ctx.status() == 0
+    # the context still works after the refusals
+    ctx.conv_fwd(desc_of(d), u, w, acc=acc, ws=ws_for(d, eoq.OP_CONV_FWD))
+    assert np.array_equal(host(acc), oo.conv_fwd(d, host(u), host(w)))
