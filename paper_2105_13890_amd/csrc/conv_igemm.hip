@@ -276,7 +276,7 @@ __device__ __forceinline__ bool epilogue_fits32(const EpiDev &ep, int gamma, int
 }
 
 // D = 2 selects the low-register form: no ring of prefetched stages, no double-buffered fragments, the stages strictly
-// one after the other, epilogue side inputs fetched where they are used.  The pipelined form holds about 250
+// one after the other, epilogue side inputs fetched two chunks ahead of their use.  The pipelined form holds about 250
 // registers per lane, i.e. TWO workgroups per compute unit; this one is compiled for 128 (FOUR workgroups).  Measured
 // per workgroup on a 1x1 layer with a 64-byte reduction: 9 us of life, 6.6 of them in the epilogue -- such layers want
 // more workgroups in flight, not a deeper pipeline.  Measured over the whole net: the low-register form wins for
@@ -507,10 +507,9 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
 
     const int nstages = (p.nk16 + CH - 1) / CH;
     if constexpr (LOWREG) {
-        // One stage of global loads in flight, two LDS buffers, fragments read one reduction step at a time: while
-        // stage st is multiplied out of one buffer, stage st+1 is on its way from memory and is stored into the other
-        // buffer after the multiplication; one barrier per stage.  The load past the last stage is out of range
-        // (zeros, no traffic), so the loop has no conditional load.
+        // Strictly serial: a stage is loaded, stored into the one LDS buffer, multiplied (fragments read one reduction
+        // step at a time), and only then the next stage is requested; two barriers per stage.  The latency of a
+        // stage is covered by the three other workgroups of the compute unit, not by this one's own prefetch.
         static_assert(BK == 64, "low-register form");
         for (int st = 0; st < nstages; ++st) {
             {
