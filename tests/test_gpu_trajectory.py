@@ -4,7 +4,7 @@ codes and the float classifier of the HIP path must equal the oracle's, bit for 
 
 The suite runs short trajectories; the full 200-step runs are started by hand:
     python tests/test_gpu_trajectory.py --batch 1 --steps 200
-and their summaries are kept in the design doc.
+and print one summary line per run.
 """
 import json
 import sys
