@@ -287,6 +287,8 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
 {
     constexpr bool LOWREG = D == 2;
     if (EPI == EPI_D16 && pin.spec && spec_hit(pin.absmax, pin.spec_used)) return;     // the speculative launch was right
+    // (the recompute runs on the weight-gradient chain: see the note on wave priority in conv_wgrad.hip)
+    if (EPI == EPI_RELU_BWD) __builtin_amdgcn_s_setprio(3);
     IgemmParams p = pin;           // uniform; patched below when the launch covers several classes
     constexpr int NW = WGM * WGN, NT = NW * 64;
     static_assert(NW == 4 || NW == 8, "4 or 8 waves");

@@ -532,6 +532,7 @@ __global__ void grad_update_flat_kernel(GradUpdate p)
 constexpr int GU_LD = 80;
 __global__ void __launch_bounds__(256) grad_update_tiled_kernel(GradUpdate p)
 {
+    __builtin_amdgcn_s_setprio(3);
     __shared__ __align__(16) int8_t tile[64 * GU_LD];
     const GradRule gr = make_grad_rule(p, blockIdx.x == 0 && threadIdx.x == 0);
     const int tiles_c = (p.C + 63) / 64;
