@@ -312,10 +312,15 @@ int eoq_maxpool_bwd(eoq_ctx *ctx, const uint8_t *arg, const int8_t *e, int32_t N
  * e_out = SQ(d) with *exp_out = *exp_in + R(log2 max|d|) - 7 (all-zero d: codes 0, exponent passed through).
  * mask_bits (may be NULL; one bit per element of e_out, 4-byte aligned): the ReLU backward step of the layer whose
  * output was pooled (Eq.3 line e1) in the same pass -- e_out = code where the bit is set, 0 elsewhere; *sum_out
- * (may be NULL) += sum of the codes written (the bias gradient of Eq.4). */
+ * (may be NULL) += sum of the codes written (the bias gradient of Eq.4).
+ * spec_state (may be NULL): one int32 of device memory that the caller keeps from one training step to the next
+ * (-1 initially), as in eoq_bwd_fuse: the first pass then codes with the exponent it holds and takes max|d| on the
+ * way; when the exponent turns out right the second pass has nothing to do, otherwise it codes again.  The results
+ * are the same in both cases; the call leaves the exact exponent R(log2 max|d|) there. */
 int eoq_maxpool_bwd_sq(eoq_ctx *ctx, const uint8_t *arg, const int8_t *e, int32_t N, int32_t H, int32_t W, int32_t C,
                        int32_t R, int32_t S, int32_t stride, int32_t pad, int8_t *e_out, int32_t *absmax_slot,
-                       const int32_t *exp_in, int32_t *exp_out, const uint32_t *mask_bits, int64_t *sum_out);
+                       const int32_t *exp_in, int32_t *exp_out, const uint32_t *mask_bits, int64_t *sum_out,
+                       int32_t *spec_state);
 /* Global average pool, integer part: sum[n][c] = sum_{h,w} y[n,h,w,c]. */
 int eoq_gap_sum(eoq_ctx *ctx, const int8_t *y, int32_t N, int32_t HW, int32_t C, int32_t *sum);
 /* e[n,h,w,c] = codes[n][c] for all HW positions (error of the average pool, already quantised). */

@@ -69,19 +69,41 @@ __global__ void maxpool_fwd_kernel(PoolGeom g, const int8_t *a, int8_t *y, const
 // OUT 0: int32 sums + abs-max;  OUT 1: abs-max only;  OUT 2: Q_e codes (Eq.11) from the abs-max of an OUT 1 launch:
 // the sums are cheap to form twice (the gathered tensors are the small, pooled ones), so the wide tensor is never
 // written.
+// OUT 3 / OUT 4: the same result in one pass when the exponent did not change since the previous training step.  OUT 3
+// codes with the exponent of the previous step (spec[0]; copied to *spec_used), takes the true abs-max on the way and
+// adds the sum of its codes to *tmp_sum instead of *sum_out; OUT 4 compares: if the exponent was right it only
+// commits (exponent, sum) and every workgroup leaves at once, otherwise it is an OUT 2 launch.  Either way it stores
+// the exact exponent in spec[0] for the next step and leaves *tmp_sum at zero.
 template <int OUT>
 __global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t *e, int32_t *d, int32_t *absmax,
                                    int8_t *q, const int32_t *exp_in, int32_t *exp_out, const uint16_t *mask16,
-                                   int64_t *sum_out)
+                                   int64_t *sum_out, int32_t *spec, int32_t *spec_used, int64_t *tmp_sum)
 {
     const int c16 = g.C / 16;
     const size_t total = (size_t)g.N * g.H * g.W * c16;
     int mx = 0, r = 7;
     long long sum = 0;
-    if (OUT == 2) {
+    constexpr bool CODES = OUT >= 2, MAXIMUM = OUT != 2 && OUT != 4;
+    const bool first = blockIdx.x == 0 && threadIdx.x == 0;
+    if (OUT == 2 || OUT == 4) {
         const uint32_t M = (uint32_t)*absmax;
         r = M ? sq_exponent_u32(M) : 7;
-        if (blockIdx.x == 0 && threadIdx.x == 0) *exp_out = M ? *exp_in + r - 7 : *exp_in;
+        if (first) *exp_out = M ? *exp_in + r - 7 : *exp_in;
+    }
+    if (OUT == 4) {
+        const bool hit = r == *spec_used;
+        if (first) {
+            spec[0] = r;
+            const long long s = *tmp_sum;
+            *tmp_sum = 0;
+            if (hit && sum_out && s) atomic_add_i64(sum_out, s);
+        }
+        if (hit) return;
+    }
+    if (OUT == 3) {
+        const int rs = spec[0];
+        if (first) *spec_used = rs;
+        r = rs < 0 ? 7 : (rs > 31 ? 31 : rs);
     }
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         int cc = (int)(i % c16);
@@ -118,7 +140,7 @@ __global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t 
                 ((v4i *)o)[k4] = w;
             }
         }
-        if (OUT == 2) {
+        if (CODES) {
             // a sum of at most R*S int8 errors: 32-bit arithmetic, four codes per packed dword
             v4i o;
             const uint32_t mk = mask16 ? (uint32_t)mask16[pix * c16 + cc] : 0xffffu;
@@ -141,7 +163,8 @@ __global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t 
             }
             sum += ls;
             *(v4i *)(q + pix * g.C + cc * 16) = o;
-        } else {
+        }
+        if (MAXIMUM) {
 #pragma unroll
             for (int k = 0; k < 16; ++k) {
                 int av = acc[k] < 0 ? -acc[k] : acc[k];
@@ -149,8 +172,9 @@ __global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t 
             }
         }
     }
-    if (OUT != 2) block_atomic_max_i32(mx, absmax);
-    if (OUT == 2 && sum_out) block_atomic_add_i64(sum, sum_out);
+    if (MAXIMUM) block_atomic_max_i32(mx, absmax);
+    if ((OUT == 2 || OUT == 4) && sum_out) block_atomic_add_i64(sum, sum_out);
+    if (OUT == 3) block_atomic_add_i64(sum, tmp_sum);
 }
 
 // The 3x3 / stride 2 / padding 1 pool of the ImageNet-shaped nets: a lane owns 16 channels of a 2x2 block of input
@@ -508,7 +532,8 @@ extern "C" int eoq_maxpool_bwd(eoq_ctx *c, const uint8_t *arg, const int8_t *e, 
     if (g.P <= 0 || g.Q <= 0) return EOQ_ERR_SHAPE;
     hipLaunchKernelGGL(maxpool_bwd_kernel<0>, dim3(grid_for((size_t)N * H * W * (C / 16))), dim3(256), 0, c->stream, g,
                        arg, e, d, absmax_slot, (int8_t *)nullptr, (const int32_t *)nullptr, (int32_t *)nullptr,
-                       (const uint16_t *)nullptr, (int64_t *)nullptr);
+                       (const uint16_t *)nullptr, (int64_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr,
+                       (int64_t *)nullptr);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }
@@ -516,7 +541,7 @@ extern "C" int eoq_maxpool_bwd(eoq_ctx *c, const uint8_t *arg, const int8_t *e, 
 extern "C" int eoq_maxpool_bwd_sq(eoq_ctx *c, const uint8_t *arg, const int8_t *e, int32_t N, int32_t H, int32_t W,
                                   int32_t C, int32_t R, int32_t S, int32_t stride, int32_t pad, int8_t *e_out,
                                   int32_t *absmax_slot, const int32_t *exp_in, int32_t *exp_out,
-                                  const uint32_t *mask_bits, int64_t *sum_out)
+                                  const uint32_t *mask_bits, int64_t *sum_out, int32_t *spec_state)
 {
     if (!c || !arg || !e || !e_out || !absmax_slot || !exp_in || !exp_out || N <= 0 || H <= 0 || W <= 0 || C <= 0 ||
         R <= 0 || S <= 0 || stride <= 0 || pad < 0)
@@ -527,6 +552,16 @@ extern "C" int eoq_maxpool_bwd_sq(eoq_ctx *c, const uint8_t *arg, const int8_t *
     if (g.P <= 0 || g.Q <= 0) return EOQ_ERR_SHAPE;
     const uint16_t *mask16 = (const uint16_t *)mask_bits;
     const dim3 grid(grid_for((size_t)N * H * W * (C / 16)));
+    if (spec_state) {
+        int32_t *used = c->d_scratch + 8;
+        int64_t *tmp = (int64_t *)(c->d_scratch + 16);          // zero between calls (context creation; OUT 4 resets it)
+        hipLaunchKernelGGL(maxpool_bwd_kernel<3>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr, absmax_slot,
+                           e_out, exp_in, exp_out, mask16, sum_out, spec_state, used, tmp);
+        hipLaunchKernelGGL(maxpool_bwd_kernel<4>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr, absmax_slot,
+                           e_out, exp_in, exp_out, mask16, sum_out, spec_state, used, tmp);
+        EOQ_LAUNCH_CHECK();
+        return EOQ_OK;
+    }
     if (R == 3 && S == 3 && stride == 2 && pad == 1) {
         // the abs-max pass gains from fetching each window once per 2x2 block of pixels; the coding pass does not:
         // its stores want consecutive lanes on consecutive pixels
@@ -537,10 +572,12 @@ extern "C" int eoq_maxpool_bwd_sq(eoq_ctx *c, const uint8_t *arg, const int8_t *
     } else {
         hipLaunchKernelGGL(maxpool_bwd_kernel<1>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr,
                            absmax_slot, (int8_t *)nullptr, (const int32_t *)nullptr, (int32_t *)nullptr,
-                           (const uint16_t *)nullptr, (int64_t *)nullptr);
+                           (const uint16_t *)nullptr, (int64_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr,
+                           (int64_t *)nullptr);
     }
     hipLaunchKernelGGL(maxpool_bwd_kernel<2>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr, absmax_slot,
-                       e_out, exp_in, exp_out, mask16, sum_out);
+                       e_out, exp_in, exp_out, mask16, sum_out, (int32_t *)nullptr, (int32_t *)nullptr,
+                       (int64_t *)nullptr);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }

@@ -94,7 +94,7 @@ def _load():
     lib.eoq_update_scalars.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.eoq_maxpool_fwd.argtypes = [vp, vp] + [i32] * 8 + [vp, vp, vp, vp]
     lib.eoq_maxpool_bwd.argtypes = [vp, vp, vp] + [i32] * 8 + [vp, vp]
-    lib.eoq_maxpool_bwd_sq.argtypes = [vp, vp, vp] + [i32] * 8 + [vp, vp, vp, vp, vp, vp]
+    lib.eoq_maxpool_bwd_sq.argtypes = [vp, vp, vp] + [i32] * 8 + [vp, vp, vp, vp, vp, vp, vp]
     lib.eoq_gap_sum.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.eoq_broadcast_hw.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.eoq_head_workspace_bytes.argtypes = [i32, i32, i32]
@@ -248,10 +248,10 @@ class Context:
                                     _ptr(absmax_slot)), "eoq_maxpool_bwd")
 
     def maxpool_bwd_sq(self, arg, e, N, H, W, Cc, R, S, stride, pad, e_out, absmax_slot, exp_in, exp_out, mask=None,
-                       sum_out=None):
+                       sum_out=None, spec_state=None):
         _check(_lib.eoq_maxpool_bwd_sq(self._h, _ptr(arg), _ptr(e), N, H, W, Cc, R, S, stride, pad, _ptr(e_out),
-                                       _ptr(absmax_slot), _ptr(exp_in), _ptr(exp_out), _ptr(mask), _ptr(sum_out)),
-               "eoq_maxpool_bwd_sq")
+                                       _ptr(absmax_slot), _ptr(exp_in), _ptr(exp_out), _ptr(mask), _ptr(sum_out),
+                                       _ptr(spec_state)), "eoq_maxpool_bwd_sq")
 
     def gap_sum(self, y, N, HW, Cc, out):
         _check(_lib.eoq_gap_sum(self._h, _ptr(y), N, HW, Cc, _ptr(out)), "eoq_gap_sum")

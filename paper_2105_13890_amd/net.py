@@ -19,6 +19,7 @@ before that read has finished.  The two chains share no scratch memory.
 from __future__ import annotations
 
 import math
+import os
 from collections import deque
 from dataclasses import dataclass, field
 
@@ -193,6 +194,7 @@ class FixupNet:
             if self.pool:
                 self.prepool = i8(self.stem.out_shape)
                 self.pool_arg = torch.empty(self.blocks_in_shape(cfg, N), dtype=torch.uint8, device=self.dev)
+                self.pool_spec = torch.full((1,), -1, dtype=torch.int32, device=self.dev)     # exponent of the pool's error, step to step
         for bi, b in enumerate(self.blocks):
             b.units[0].u = i8(b.units[0].in_shape)
             if b.ds:
@@ -668,7 +670,8 @@ class FixupNet:
             n = int(np.prod(s.out_shape))
             e2 = self._acquire(bufs)
             # pool backward + Q_e; outside tracing also the stem's ReLU backward step (its mask, its bias-gradient sum)
-            fuse = {} if self.tracing else dict(mask=s.mask, sum_out=self.s64(s.name + ".S_e1"))
+            fuse = {} if self.tracing else dict(mask=s.mask, sum_out=self.s64(s.name + ".S_e1"),
+                                                spec_state=self.pool_spec)
             c.maxpool_bwd_sq(self.pool_arg, e, d.N, d.P, d.Q, d.K, 3, 3, 2, 1, e2[:n], self.s32("pool.M"),
                              self.s32(self.blocks[0].name + ".E_in"), self.s32("pool.E"), **fuse)
             masked = not self.tracing

@@ -573,6 +573,27 @@ def test_pool_gap_broadcast(ctx):
             assert np.array_equal(host(q), codes) and int(host(ex)[1]) == E_out, (H2, W2, R, S, st, pad, use_mask)
             assert int(host(slot2)[0]) == int(np.abs(want2).max())
             assert int(host(sm)[0]) == int(codes.astype(np.int64).sum())
+    # the exponent carried from call to call: first call (nothing to try), same scale again (right), other scales (wrong,
+    # then right again) -- codes, exponent, sum and stored exponent must be those of the two-pass form every time
+    spec = dev(np.array([-1], dtype=np.int32))
+    a2 = si.uniform_int8(10, "a3", (N, 13, 15, Cc), -6, 6)
+    y2, arg2 = oo.maxpool_fwd(a2, 3, 3, 2, 1)
+    mb = (si.words(10, "poolmask3", a2.size) & np.uint64(1)).astype(bool)
+    pk = np.packbits(mb, bitorder="little")
+    mk = dev(np.frombuffer(pk.tobytes() + b"\0" * (-len(pk) % 4), dtype=np.int32))
+    for scale in (127, 127, 30, 30, 3, 127, 0, 0, 127):
+        e2 = si.uniform_int8(10, "e3", y2.shape, -scale, scale) if scale else np.zeros(y2.shape, dtype=np.int8)
+        q, slot2, sm = zeros(a2.shape, torch.int8), zeros((1,), torch.int32), zeros((1,), torch.int64)
+        ex = dev(np.array([-9, 99], dtype=np.int32))
+        ctx.maxpool_bwd_sq(dev(arg2), dev(e2), N, 13, 15, Cc, 3, 3, 2, 1, q, slot2, ex[0:1], ex[1:2], mask=mk, sum_out=sm,
+                           spec_state=spec)
+        want2 = oo.maxpool_bwd(e2, arg2, a2.shape, 3, 3, 2, 1)
+        codes, E_out = oq.sq_int(want2, -9)
+        codes = codes * mb.reshape(a2.shape)
+        M = int(np.abs(want2).max())
+        assert np.array_equal(host(q), codes) and int(host(ex)[1]) == E_out, scale
+        assert int(host(slot2)[0]) == M and int(host(sm)[0]) == int(codes.astype(np.int64).sum()), scale
+        assert int(host(spec)[0]) == (oq.scale_exponent_int(M) if M else 7), scale
     s = zeros((N, Cc), torch.int32)
     ctx.gap_sum(dev(a), N, H * W, Cc, s)
     assert np.array_equal(host(s), a.astype(np.int64).sum(axis=(1, 2)))
