@@ -59,13 +59,22 @@ enum eoq_flag_bits {
 typedef struct eoq_ctx eoq_ctx;
 
 /* Create a context bound to `hip_stream` (a hipStream_t; NULL = the default stream) on the
- * current device.  Allocates a few KB of device memory for the status word and scratch slots. */
+ * current device.  Allocates device memory that the context owns until eoq_destroy: 512 bytes for the status
+ * word and the call-internal statistics slots, and 8 MiB (2^20 int64) for the per-wave partial sums that
+ * eoq_relu_bwd_recompute and the speculative form of eoq_conv_bwd_data_sq stage between their kernels (calls whose
+ * records do not fit fall back to atomics / to the exact path).  Calls on one context are ordered by its stream;
+ * two contexts share nothing. */
 int eoq_create(eoq_ctx **ctx, void *hip_stream);
 int eoq_destroy(eoq_ctx *ctx);
 const char *eoq_strerror(int code);
 /* Synchronise the stream, copy the device status word to *flags (host) and clear it.
  * Returns EOQ_ERR_RANGE when any bit was set. */
 int eoq_status(eoq_ctx *ctx, uint32_t *flags);
+
+/* Speculation statistics (see eoq_bwd_fuse::spec_state and eoq_maxpool_bwd_sq): synchronises the stream and
+ * returns how many speculative calls on this context, since it was created, found their exponent right (*hits:
+ * one evaluation, no intermediate) and how many had to be redone the exact way (*misses).  Either may be NULL. */
+int eoq_spec_counters(eoq_ctx *ctx, int64_t *hits, int64_t *misses);
 
 /* Convolution geometry.  Input N x H x W x C, filters K x R x S x C. */
 typedef struct eoq_conv_desc {
@@ -208,6 +217,12 @@ int eoq_relu_bwd(eoq_ctx *ctx, const int8_t *e0, const uint32_t *mask_bits, cons
 int eoq_relu_bwd_recompute(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *u, const int8_t *w,
                            const int8_t *e0, const uint32_t *mask_bits, int8_t *e1, int64_t *sum_e1,
                            int64_t *sum_e1t, int32_t *absmax_e1);
+
+/* ---- the sums of Eq.4 for a scalar parameter, on their own: *sum += sum_i e[i] (t NULL: g_b1, g_b2) or
+ * *sum += sum_i e[i] * t[i] (g_gamma, t = the wide Q_a1 output x2), exact in int64.  e: int8[n], t: int32[n],
+ * both 16-byte aligned; any n.  The training step takes these sums inside the kernels that produce e (ReLU backward,
+ * backward-data finishing pass, merge pass); this call is the same reduction for callers that hold e already. */
+int eoq_reduce_sum_i64(eoq_ctx *ctx, const int8_t *e, const int32_t *t, size_t n, int64_t *sum);
 
 /* ---- abs-max of the exact sum of two errors with different exponents (first phase of the merge
  * of branch and shortcut errors at a block input): v = a*2^(Ea-Em) + b*2^(Eb-Em), Em = min(Ea,Eb).

@@ -15,6 +15,10 @@ struct eoq_ctx {
 };
 
 constexpr int EOQ_SCRATCH_SLOTS = 64;
+// d_scratch slots with a fixed meaning (0, 1: abs-max of eoq_quantize / eoq_update_int8 when the caller gives none)
+constexpr int EOQ_SLOT_SPEC_USED = 8;   // exponent the speculative launch in flight coded with
+constexpr int EOQ_SLOT_POOL_TMP = 16;   // int64 (two slots): sum of the codes of a speculative pool-backward pass
+constexpr int EOQ_SLOT_SPEC_HITS = 24;  // [0] speculative calls whose exponent was right, [1] those that were redone
 constexpr int EOQ_PARTIAL_SLOTS = 1 << 20;      // 8 MB: per-wave pairs of the largest benchmark layer
 constexpr int CODE_MAX = 127;
 

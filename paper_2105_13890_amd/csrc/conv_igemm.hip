@@ -18,8 +18,7 @@
 // output channels of one pixel (16-byte int8 stores, 16-bit mask stores, 64-byte int32 stores).
 #include "common.h"
 
-#include <cstdio>
-#include <cstdlib>
+#include <atomic>
 
 namespace {
 
@@ -1086,9 +1085,10 @@ __global__ void pad_filters_kernel(const int8_t *w, int K, int rsc, int KP, int8
 }
 
 // standalone forward epilogue on stored accumulators
-__global__ void requant_fwd_kernel(const int32_t *acc, size_t n16, EpiDev ep)
+__global__ void requant_fwd_kernel(const int32_t *acc, size_t n16, EpiDev ep, uint32_t *status)
 {
     const int gamma = ep.gamma ? *ep.gamma : 128, bpost = ep.b_post ? *ep.b_post : 0, bnext = ep.b_next ? *ep.b_next : 0;
+    uint32_t range_bad = 0;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) {
         int v[16];
 #pragma unroll
@@ -1096,11 +1096,11 @@ __global__ void requant_fwd_kernel(const int32_t *acc, size_t n16, EpiDev ep)
             v4i w = ((const v4i *)acc)[i * 4 + k4];
             v[4 * k4] = w[0]; v[4 * k4 + 1] = w[1]; v[4 * k4 + 2] = w[2]; v[4 * k4 + 3] = w[3];
         }
-        uint32_t unused = 0;
         v4i sk8 = {0, 0, 0, 0};
         if (ep.skip && ep.relu && !ep.skip_wide) sk8 = *(const v4i *)((const int8_t *)ep.skip + i * 16);
-        epilogue16<false>(v, i * 16, ep, nullptr, gamma, bpost, bnext, unused, sk8);
+        epilogue16<false>(v, i * 16, ep, nullptr, gamma, bpost, bnext, range_bad, sk8);
     }
+    if (range_bad) atomicOr(status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);      // a wide value that does not fit its 16-bit store
 }
 
 // adds up the per-wave pairs of partial sums (a handful of blocks: two atomics each)
@@ -1158,6 +1158,7 @@ struct D16Finish {
     const int32_t *spec_used;
     const int64_t *sp_part;
     int sp_records;
+    int32_t *counters;                 // [0] += 1 when the exponent tried was right, [1] += 1 when it was not
 };
 
 template <bool RELU>
@@ -1190,7 +1191,10 @@ __global__ __launch_bounds__(1024) void d16_finish_kernel(D16Finish p)
             if (!RELU && p.mg_other) block_atomic_max_i32(ma, p.mg_absmax);
             if (!RELU && p.mg_mask16) block_atomic_max_i32(mb, p.mg_absmax_m);
         }
-        if (blockIdx.x == 0 && threadIdx.x == 0) p.spec[0] = r;                // what the next step will try
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            p.spec[0] = r;                                                      // what the next step will try
+            atomicAdd(p.counters + (hit ? 0 : 1), 1);
+        }
         if (hit) return;
     }
     const uint32_t c16 = (uint32_t)p.C >> 4;
@@ -1320,13 +1324,13 @@ int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
     constexpr int epi_rows = (BN / WGN) >= 64 ? 16 : 32;        // rows staged at a time (SR in the kernel)
     constexpr int main_bytes = 2 * (BM + BN) * BK, epi_bytes = NW * epi_rows * (BN / WGN + 4) * 4;
     constexpr int lds_bytes = main_bytes > epi_bytes ? main_bytes : epi_bytes;
-    static bool attr_done = false;
+    static std::atomic<bool> attr_done{false};     // (setting the attribute twice from two threads is harmless)
     void (*kern)(IgemmParams) = igemm_kernel<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>;
     if constexpr (D == 2) kern = igemm_lr_kernel<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>;
-    if (lds_bytes > 48 * 1024 && !attr_done) {
+    if (lds_bytes > 48 * 1024 && !attr_done.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
             return EOQ_ERR_HIP;
-        attr_done = true;
+        attr_done.store(true, std::memory_order_release);
     }
     long tiles = (long)((p.M + BM - 1) / BM) * ((p.NOUT + BN - 1) / BN);
     if (p.ncls) {
@@ -1345,38 +1349,24 @@ int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
     return EOQ_OK;
 }
 
-// EOQ_IGEMM_TILE=BMxBNxBK (environment, read once) forces a tile shape: a tuning aid
-int forced_tile()
-{
-    static int v = -1;
-    if (v < 0) {
-        v = 0;
-        const char *e = getenv("EOQ_IGEMM_TILE");
-        int bm, bn, bk;
-        if (e && sscanf(e, "%dx%dx%d", &bm, &bn, &bk) == 3) v = bm * 1000000 + bn * 1000 + bk;
-    }
-    return v;
-}
-
-// longest reduction (in 16-byte chunks) that takes the low-register form; EOQ_LOWREG overrides it (0 = never)
-static int lowreg_max_nk16()
-{
-    static const int v = [] { const char *e = getenv("EOQ_LOWREG"); return e ? atoi(e) : 80; }();
-    return v;
-}
+// longest reduction (in 16-byte chunks) that takes the low-register form (swept over the layers of ResNet-50 at
+// batch 128: the low-register form wins up to about 80 chunks and ties beyond)
+constexpr int LOWREG_MAX_NK16 = 80;
+// fewest 128 x 128 workgroups for which that tile is chosen over 128 x 64 (one per compute unit)
+constexpr long MIN_WGS_128 = 256;
 
 template <int BM, int BN, int WGM, int WGN, int BK, int MODE, int EPI>
 int launch_igemm(eoq_ctx *c, const IgemmParams &p)
 {
     if (p.c16 % (BK / 16) == 0) {
         if constexpr (BK == 64 && WGM * WGN == 4 && (EPI == EPI_FWD || EPI == EPI_D16 || EPI == EPI_RELU_BWD || EPI == EPI_SPEC)) {
-            if (p.nk16 <= lowreg_max_nk16())
+            if (p.nk16 <= LOWREG_MAX_NK16)
                 return launch_igemm_u<BM, BN, WGM, WGN, BK, 2, true, MODE, EPI>(c, p);
         }
         return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, true, MODE, EPI>(c, p);
     }
     if constexpr (BK == 64 && WGM * WGN == 4 && (EPI == EPI_FWD || EPI == EPI_D16 || EPI == EPI_RELU_BWD || EPI == EPI_SPEC)) {
-        if (p.nk16 <= lowreg_max_nk16()) return launch_igemm_u<BM, BN, WGM, WGN, BK, 2, false, MODE, EPI>(c, p);
+        if (p.nk16 <= LOWREG_MAX_NK16) return launch_igemm_u<BM, BN, WGM, WGN, BK, 2, false, MODE, EPI>(c, p);
     }
     return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, false, MODE, EPI>(c, p);
 }
@@ -1397,24 +1387,11 @@ int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in, int *bm_out = nullptr, i
     if (p.ncls) p.gemm = 0;            // the classes differ in their grids and taps
     const int nout = p.NOUT;
     auto wgs = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((nout + bn - 1) / bn); };
-    switch (forced_tile()) {
-    case 128128064: chosen(128, 128); return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
-    case 128128065: chosen(128, 128); return launch_igemm<128, 128, 4, 1, 64, MODE, EPI>(c, p);   // waves stacked in M
-    case 128128128: if (p.c16 % 8 == 0) { chosen(128, 128); return launch_igemm_u<128, 128, 2, 2, 128, 4, true, MODE, EPI>(c, p); } break;
-    case 128064128: if (p.c16 % 8 == 0) { chosen(128, 64); return launch_igemm_u<128, 64, 2, 2, 128, 4, true, MODE, EPI>(c, p); } break;
-    case 256128064: chosen(256, 128, 8); return launch_igemm<256, 128, 4, 2, 64, MODE, EPI>(c, p);   // 8 waves
-    case 128128068: chosen(128, 128, 8); return launch_igemm<128, 128, 2, 4, 64, MODE, EPI>(c, p);
-    case 128064068: chosen(128, 64, 8); return launch_igemm<128, 64, 4, 2, 64, MODE, EPI>(c, p);
-    case 128064064: chosen(128, 64); return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
-    case 128032064: chosen(128, 32); return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p);
-    default: break;
-    }
     // Measured on MI355X: throughput is nearly flat in the tile shape and in the prefetch depth (4, 6, 8 stages),
     // so small tiles win through occupancy and grid size; the 128x128 tile pays off only for wide outputs with
     // enough workgroups to fill the chip.
     if (nout <= 32) { chosen(128, 32); return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p); }
-    static const long min128 = [] { const char *e = getenv("EOQ_MIN128"); return e ? atol(e) : 256l; }();
-    if (nout >= 128 && wgs(128, 128) >= min128) {
+    if (nout >= 128 && wgs(128, 128) >= MIN_WGS_128) {
         chosen(128, 128);
         // The forward epilogue with int8 outputs stacks the four waves along M, so that a wave owns whole 128-byte
         // output rows and its stores fill cache lines (measured: 3-9 % on the wide 1x1 layers, a loss elsewhere).
@@ -1742,7 +1719,7 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
     if (spec && 16 * max_tiles > EOQ_PARTIAL_SLOTS) spec = nullptr;
     if (spec) {
         IgemmParams q = p;
-        q.spec = spec; q.spec_used = c->d_scratch + 8;
+        q.spec = spec; q.spec_used = c->d_scratch + EOQ_SLOT_SPEC_USED;
         q.sp_e4 = e4; q.sp_e1 = e1;
         q.sp_mask16 = e1 ? (const uint16_t *)mask_bits : (const uint16_t *)mg_mask;
         q.sp_other = mg_other;
@@ -1751,7 +1728,7 @@ extern "C" int eoq_conv_bwd_data_sq(eoq_ctx *c, const eoq_conv_desc *d, const in
         q.sp_part = c->d_partials;
         int bm1 = 0, bn1 = 0, nw1 = 4;
         if (int rc = dispatch_igemm<MODE_BWD_DATA, EPI_SPEC>(c, q, &bm1, &bn1, &nw1)) return rc;
-        f.spec = spec; f.spec_used = q.spec_used; f.sp_part = c->d_partials;
+        f.spec = spec; f.spec_used = q.spec_used; f.sp_part = c->d_partials; f.counters = c->d_scratch + EOQ_SLOT_SPEC_HITS;
         f.sp_records = nw1 * (int)(((p.M + bm1 - 1) / bm1) * ((p.NOUT + bn1 - 1) / bn1));
         p.spec = spec; p.spec_used = q.spec_used;
     }
@@ -1790,7 +1767,7 @@ int eoq_requant_fwd_standalone(eoq_ctx *c, const eoq_requant_args *a)
     EpiDev ep;
     if (int rc = fill_epi(a->ep, ep)) return rc;
     if (!a->n) return EOQ_OK;
-    hipLaunchKernelGGL(requant_fwd_kernel, dim3(grid_for(a->n / 16)), dim3(256), 0, c->stream, a->acc, a->n / 16, ep);
+    hipLaunchKernelGGL(requant_fwd_kernel, dim3(grid_for(a->n / 16)), dim3(256), 0, c->stream, a->acc, a->n / 16, ep, c->d_status);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }

@@ -79,6 +79,17 @@ extern "C" int eoq_status(eoq_ctx *c, uint32_t *flags)
     return h ? EOQ_ERR_RANGE : EOQ_OK;
 }
 
+extern "C" int eoq_spec_counters(eoq_ctx *c, int64_t *hits, int64_t *misses)
+{
+    if (!c) return EOQ_ERR_ARG;
+    int32_t h[2] = {0, 0};
+    EOQ_HIP(hipStreamSynchronize(c->stream));
+    EOQ_HIP(hipMemcpy(h, c->d_scratch + EOQ_SLOT_SPEC_HITS, sizeof(h), hipMemcpyDeviceToHost));
+    if (hits) *hits = h[0];
+    if (misses) *misses = h[1];
+    return EOQ_OK;
+}
+
 extern "C" int eoq_fill_zero(eoq_ctx *c, void *ptr, size_t bytes)
 {
     if (!c || (!ptr && bytes) || (bytes & 3) || ((uintptr_t)ptr & 3)) return EOQ_ERR_ARG;

@@ -190,6 +190,38 @@ __global__ void relu_bwd_kernel(const int8_t *e0, const uint16_t *mask16, const 
 }
 
 // ------------------------------------------------------------------------------------------
+// sum e (* t): the scalar-parameter sums of Eq.4
+// ------------------------------------------------------------------------------------------
+__global__ void reduce_sum_kernel(const int8_t *e, const int32_t *t, size_t n, int64_t *sum)
+{
+    const size_t nv = n / 16;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    int64_t s = 0;
+    for (; i < nv; i += stride) {
+        const v4i v = ((const v4i *)e)[i];
+        if (t) {
+#pragma unroll
+            for (int k4 = 0; k4 < 4; ++k4) {
+                const v4i tv = ((const v4i *)t)[i * 4 + k4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) s += (int64_t)byte_at(v, 4 * k4 + k) * (int64_t)tv[k];
+            }
+        } else {
+            int ls = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) ls = sum4_i8((uint32_t)v[q], ls);
+            s += ls;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 15)) {
+        const size_t j = nv * 16 + threadIdx.x;
+        s += t ? (int64_t)e[j] * (int64_t)t[j] : (int64_t)e[j];
+    }
+    block_atomic_add_i64(s, sum);
+}
+
+// ------------------------------------------------------------------------------------------
 // merge: abs-max of a*2^(Ea-Em) + b*2^(Eb-Em)
 // ------------------------------------------------------------------------------------------
 __global__ void merge_absmax_kernel(const int8_t *a, const int32_t *exp_a, const int8_t *b, const int32_t *exp_b,
@@ -645,6 +677,15 @@ extern "C" int eoq_relu_bwd(eoq_ctx *c, const int8_t *e0, const uint32_t *mask_b
     if (!n) return EOQ_OK;
     hipLaunchKernelGGL(relu_bwd_kernel, dim3(ew_blocks(n / 16)), dim3(EW_THREADS), 0, c->stream, e0,
                        (const uint16_t *)mask_bits, t_wide, n, e1, sum_e1, sum_e1t, absmax_e1);
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}
+
+extern "C" int eoq_reduce_sum_i64(eoq_ctx *c, const int8_t *e, const int32_t *t, size_t n, int64_t *sum)
+{
+    if (!c || !sum || (n && !e) || !aligned16(e) || !aligned16(t)) return EOQ_ERR_ARG;
+    if (!n) return EOQ_OK;
+    hipLaunchKernelGGL(reduce_sum_kernel, dim3(ew_blocks(n / 16)), dim3(EW_THREADS), 0, c->stream, e, t, n, sum);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }

@@ -77,7 +77,8 @@ __global__ void maxpool_fwd_kernel(PoolGeom g, const int8_t *a, int8_t *y, const
 template <int OUT>
 __global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t *e, int32_t *d, int32_t *absmax,
                                    int8_t *q, const int32_t *exp_in, int32_t *exp_out, const uint16_t *mask16,
-                                   int64_t *sum_out, int32_t *spec, int32_t *spec_used, int64_t *tmp_sum)
+                                   int64_t *sum_out, int32_t *spec, int32_t *spec_used, int64_t *tmp_sum,
+                                   int32_t *counters)
 {
     const int c16 = g.C / 16;
     const size_t total = (size_t)g.N * g.H * g.W * c16;
@@ -94,6 +95,7 @@ __global__ void maxpool_bwd_kernel(PoolGeom g, const uint8_t *arg, const int8_t 
         const bool hit = r == *spec_used;
         if (first) {
             spec[0] = r;
+            atomicAdd(counters + (hit ? 0 : 1), 1);
             const long long s = *tmp_sum;
             *tmp_sum = 0;
             if (hit && sum_out && s) atomic_add_i64(sum_out, s);
@@ -533,7 +535,7 @@ extern "C" int eoq_maxpool_bwd(eoq_ctx *c, const uint8_t *arg, const int8_t *e, 
     hipLaunchKernelGGL(maxpool_bwd_kernel<0>, dim3(grid_for((size_t)N * H * W * (C / 16))), dim3(256), 0, c->stream, g,
                        arg, e, d, absmax_slot, (int8_t *)nullptr, (const int32_t *)nullptr, (int32_t *)nullptr,
                        (const uint16_t *)nullptr, (int64_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr,
-                       (int64_t *)nullptr);
+                       (int64_t *)nullptr, (int32_t *)nullptr);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }
@@ -553,12 +555,13 @@ extern "C" int eoq_maxpool_bwd_sq(eoq_ctx *c, const uint8_t *arg, const int8_t *
     const uint16_t *mask16 = (const uint16_t *)mask_bits;
     const dim3 grid(grid_for((size_t)N * H * W * (C / 16)));
     if (spec_state) {
-        int32_t *used = c->d_scratch + 8;
-        int64_t *tmp = (int64_t *)(c->d_scratch + 16);          // zero between calls (context creation; OUT 4 resets it)
+        int32_t *used = c->d_scratch + EOQ_SLOT_SPEC_USED;
+        int64_t *tmp = (int64_t *)(c->d_scratch + EOQ_SLOT_POOL_TMP);   // zero between calls (context creation; OUT 4 resets it)
+        int32_t *cnt = c->d_scratch + EOQ_SLOT_SPEC_HITS;
         hipLaunchKernelGGL(maxpool_bwd_kernel<3>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr, absmax_slot,
-                           e_out, exp_in, exp_out, mask16, sum_out, spec_state, used, tmp);
+                           e_out, exp_in, exp_out, mask16, sum_out, spec_state, used, tmp, cnt);
         hipLaunchKernelGGL(maxpool_bwd_kernel<4>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr, absmax_slot,
-                           e_out, exp_in, exp_out, mask16, sum_out, spec_state, used, tmp);
+                           e_out, exp_in, exp_out, mask16, sum_out, spec_state, used, tmp, cnt);
         EOQ_LAUNCH_CHECK();
         return EOQ_OK;
     }
@@ -573,11 +576,11 @@ extern "C" int eoq_maxpool_bwd_sq(eoq_ctx *c, const uint8_t *arg, const int8_t *
         hipLaunchKernelGGL(maxpool_bwd_kernel<1>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr,
                            absmax_slot, (int8_t *)nullptr, (const int32_t *)nullptr, (int32_t *)nullptr,
                            (const uint16_t *)nullptr, (int64_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr,
-                           (int64_t *)nullptr);
+                           (int64_t *)nullptr, (int32_t *)nullptr);
     }
     hipLaunchKernelGGL(maxpool_bwd_kernel<2>, grid, dim3(256), 0, c->stream, g, arg, e, (int32_t *)nullptr, absmax_slot,
                        e_out, exp_in, exp_out, mask16, sum_out, (int32_t *)nullptr, (int32_t *)nullptr,
-                       (int64_t *)nullptr);
+                       (int64_t *)nullptr, (int32_t *)nullptr);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }

@@ -19,7 +19,8 @@ OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT = 0, 1, 2
 RQ_FWD, RQ_SQ_ACC, RQ_SQ_GAMMA, RQ_SQ_MERGE = 0, 1, 2, 3
 
 EXPORTS = [
-    "eoq_create", "eoq_destroy", "eoq_strerror", "eoq_status", "eoq_workspace_bytes", "eoq_fill_zero",
+    "eoq_create", "eoq_destroy", "eoq_strerror", "eoq_status", "eoq_spec_counters", "eoq_workspace_bytes", "eoq_fill_zero",
+    "eoq_reduce_sum_i64",
     "eoq_quantize", "eoq_pre_bias", "eoq_conv_fwd", "eoq_conv_bwd_data", "eoq_conv_bwd_data_sq", "eoq_transpose_filters", "eoq_conv_bwd_weight",
     "eoq_relu_bwd", "eoq_relu_bwd_recompute", "eoq_merge_absmax", "eoq_requant_epilogue", "eoq_update_int8", "eoq_grad_update", "eoq_update_scalars",
     "eoq_maxpool_fwd", "eoq_maxpool_bwd", "eoq_maxpool_bwd_sq", "eoq_gap_sum", "eoq_broadcast_hw", "eoq_head_workspace_bytes",
@@ -76,6 +77,8 @@ def _load():
     lib.eoq_create.argtypes = [C.POINTER(vp), vp]
     lib.eoq_destroy.argtypes = [vp]
     lib.eoq_status.argtypes = [vp, C.POINTER(C.c_uint32)]
+    lib.eoq_spec_counters.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    lib.eoq_reduce_sum_i64.argtypes = [vp, vp, vp, sz, vp]
     lib.eoq_workspace_bytes.argtypes = [C.POINTER(ConvDesc), i32]
     lib.eoq_fill_zero.argtypes = [vp, vp, sz]
     lib.eoq_quantize.argtypes = [vp, vp, sz, i32, i32, vp, vp]
@@ -151,6 +154,14 @@ class Context:
         f = C.c_uint32(0)
         _lib.eoq_status(self._h, C.byref(f))
         return f.value
+
+    def spec_counters(self) -> tuple[int, int]:
+        h, m = C.c_int64(0), C.c_int64(0)
+        _check(_lib.eoq_spec_counters(self._h, C.byref(h), C.byref(m)), "eoq_spec_counters")
+        return h.value, m.value
+
+    def reduce_sum_i64(self, e, t, sum_slot):
+        _check(_lib.eoq_reduce_sum_i64(self._h, _ptr(e), _ptr(t), e.numel(), _ptr(sum_slot)), "eoq_reduce_sum_i64")
 
     @staticmethod
     def workspace_bytes(desc: ConvDesc, op: int) -> int:

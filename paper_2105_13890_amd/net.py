@@ -18,8 +18,6 @@ before that read has finished.  The two chains share no scratch memory.
 """
 from __future__ import annotations
 
-import math
-import os
 from collections import deque
 from dataclasses import dataclass, field
 
@@ -28,7 +26,7 @@ import torch
 
 import seeded_inputs as si
 
-from . import eoq
+from . import eoq, fixup_init
 
 
 @dataclass
@@ -82,7 +80,11 @@ class _Slots:
 class FixupNet:
     N_EBUF = 6     # rotating error buffers (at least 5: e1, e3, e4 of a layer, the shortcut error, the other merge input)
 
-    def __init__(self, cfg: dict, batch: int, seed: int = 0, trace: bool = False, overlap: bool = True):
+    def __init__(self, cfg: dict, batch: int, seed: int = 0, trace: bool = False, overlap: bool = True,
+                 weights: dict | None = None, classifier=None):
+        """weights: {layer name: int8 K x R x S x C codes} and classifier = (W fp64 [classes x features], b fp64):
+        the initial parameters as input data.  Left out, they are drawn by fixup_init from `seed` and coded with
+        Q_w by the library."""
         assert torch.cuda.is_available(), "libeoq needs the GPU; there is no CPU path"
         self.cfg, self.N, self.seed, self.tracing = dict(cfg), batch, seed, trace
         self.dev = torch.device("cuda")
@@ -100,9 +102,6 @@ class FixupNet:
         self.trace: dict[str, object] = {}
         self.prof = None                   # list of (kind, unit, work, start event, end event) while profiling
         bt = cfg["block"]
-        m = 2 if bt == "basic" else 3
-        L = int(sum(cfg["depths"]))
-        alpha = float(L) ** (-1.0 / (2 * m - 2))          # Eq.1
         N = batch
         hw, ch = cfg["in_hw"], cfg["in_ch"]
         self.scal_names: list[str] = []
@@ -158,20 +157,27 @@ class FixupNet:
         init = np.array([128 if n.endswith(".g") else 0 for n in self.scal_names] + [0], dtype=np.int32)
         self.scal = torch.from_numpy(init).to(self.dev)            # multiplier = 1 (code 128), biases = 0
         branch = {u.name for b in self.blocks for u in b.units}
+        coeff = fixup_init.branch_coefficient(int(sum(cfg["depths"])), 2 if bt == "basic" else 3)
         for u in all_units:
             d = u.desc
-            z = si.standard_normal(seed, u.name + ".w", (d.K, d.R, d.S, d.C))
-            std = math.sqrt(2.0 / (d.C * d.R * d.S)) * (alpha if u.name in branch else 1.0)
-            wf = torch.from_numpy((z * std).astype(np.float32)).to(self.dev)
-            u.w = torch.empty((d.K, d.R, d.S, d.C), dtype=torch.int8, device=self.dev)
-            self.ctx.quantize(wf, eoq.CQ, 0, u.w)                  # Q_w = CQ (Eq.8)
+            shape = (d.K, d.R, d.S, d.C)
+            if weights is not None:
+                w0 = np.ascontiguousarray(weights[u.name])
+                assert w0.dtype == np.int8 and w0.shape == shape, (u.name, w0.dtype, w0.shape)
+                u.w = torch.from_numpy(w0).to(self.dev)
+            else:
+                wf = torch.from_numpy(fixup_init.conv_weights_f32(seed, u.name, shape,
+                                                                  coeff if u.name in branch else 1.0)).to(self.dev)
+                u.w = torch.empty(shape, dtype=torch.int8, device=self.dev)
+                self.ctx.quantize(wf, eoq.CQ, 0, u.w)              # Q_w = CQ (Eq.8)
             if d.C % 16 == 0 and d.K % 16 == 0:
                 u.wt = torch.empty_like(u.w)                       # refreshed after every update, off the critical path
                 self.ctx.transpose_filters(d, u.w, u.wt)
         if self.classes:
-            z = si.standard_normal(seed, "fc.w", (self.classes, ch))
-            self.Wfc = torch.from_numpy(z * math.sqrt(2.0 / ch)).to(self.dev)
-            self.bfc = torch.zeros(self.classes, dtype=torch.float64, device=self.dev)
+            Wc, bc = classifier if classifier is not None else fixup_init.classifier_f64(seed, self.classes, ch)
+            self.Wfc = torch.from_numpy(np.ascontiguousarray(Wc, dtype=np.float64)).to(self.dev)
+            self.bfc = torch.from_numpy(np.ascontiguousarray(bc, dtype=np.float64)).to(self.dev)
+            assert self.Wfc.shape == (self.classes, ch) and self.bfc.shape == (self.classes,)
 
         # ---- buffers ---------------------------------------------------------------------------
         i8 = lambda shape: torch.empty(shape, dtype=torch.int8, device=self.dev)
@@ -794,3 +800,8 @@ class FixupNet:
 
     def status(self) -> int:
         return self.ctx.status() | self.ctx_w.status()
+
+    def spec_counters(self) -> tuple[int, int]:
+        """(hits, misses) of the speculative backward-data / pool-backward calls since the network was built."""
+        a, b = self.ctx.spec_counters(), self.ctx_w.spec_counters()
+        return a[0] + b[0], a[1] + b[1]
