@@ -202,6 +202,20 @@ int eoq_transpose_filters(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t 
 int eoq_conv_bwd_weight(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, const int8_t *u,
                         int32_t *g_acc, int32_t *absmax_slot, void *ws, size_t ws_bytes);
 
+/* The same call for callers that cannot allocate device memory and have no workspace to pass: code under HIP graph
+ * capture, tight serving or fine-tuning loops, harnesses that forbid hipMalloc.  It takes no workspace: the partial
+ * sums (and the staged copy of an input whose C is not a multiple of 16) go to a 32 MiB array that the library holds
+ * in device memory on every GPU it is loaded on, from load until the process ends; its address on the context's
+ * device was looked up by eoq_create.  The call itself allocates and frees nothing.  A problem whose staged input plus
+ * the partial sums of the shortest legal reduction ranges (131072 terms each) exceed 32 MiB returns
+ * EOQ_ERR_WORKSPACE before anything is launched; within the limit the reduction is split into as many ranges as fit
+ * (at most as many as eoq_conv_bwd_weight would use), so results are identical to eoq_conv_bwd_weight's.  Every partial
+ * sum that is read was written by the same call: nothing in the array has to start at zero, and what a call leaves
+ * behind is never read.  ALL calls on one GPU share that one array, whatever their context or stream: calls that overlap
+ * in time on one GPU race; order them on one stream or with events. */
+int eoq_conv_bwd_weight_static(eoq_ctx *ctx, const eoq_conv_desc *desc, const int8_t *e, const int8_t *u,
+                               int32_t *g_acc, int32_t *absmax_slot);
+
 /* ---- ReLU backward and the statistics of Eq.3 lines e1..e3 / Eq.4 lines g_b2, g_gamma ----------
  * e1 = e0 * [mask]; *sum_e1 += sum e1 (bias gradient); *sum_e1t += sum e1 * t (multiplier gradient,
  * t_wide and sum_e1t may be NULL); *absmax_e1 = max(*absmax_e1, max|e1|) (for Q_e of e1*gamma).

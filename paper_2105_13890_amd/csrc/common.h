@@ -12,7 +12,11 @@ struct eoq_ctx {
     uint32_t *d_status;   // device status word (eoq_flag_bits)
     int32_t *d_scratch;   // EOQ_SCRATCH_SLOTS int32 slots for call-internal statistics
     int64_t *d_partials;  // EOQ_PARTIAL_SLOTS int64 per-workgroup partial sums of the call in flight on this stream
+    void *static_scratch; // this device's copy of the file-scope scratch array of eoq_conv_bwd_weight_static
 };
+
+// conv_wgrad.hip: device address of that array on `device` (looked up once per device; `device` must be current)
+int wgrad_static_scratch_init(int device, void **ptr_out);
 
 constexpr int EOQ_SCRATCH_SLOTS = 64;
 // d_scratch slots with a fixed meaning (0, 1: abs-max of eoq_quantize / eoq_update_int8 when the caller gives none)

@@ -18,6 +18,7 @@
 #include "common.h"
 
 #include <atomic>
+#include <mutex>
 
 namespace {
 
@@ -479,7 +480,7 @@ void pick_chunk(int P, int Q, int stride, int R, int S, int max_patch, int &PR, 
 }
 
 template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS>
-int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int *splits_out)
+int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int max_splits, int *splits_out)
 {
     constexpr int KT = WK * TK * 32, CT = WC * TC * 32;
     constexpr int U_ROWS = U_LOADS * 256 / (CT / 16);
@@ -496,7 +497,6 @@ int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int *splits_out)
     constexpr int target_wgs = 448;
     int splits = target_wgs / tiles;
     if (splits < 1) splits = 1;
-    const int max_splits = wgrad_max_splits(p.part_stride - WGRAD_PART_PAD);
     if (splits > max_splits) splits = max_splits;
     if (splits > p.nchunks) splits = p.nchunks;
     p.chunks_per_split = (p.nchunks + splits - 1) / splits;
@@ -504,7 +504,7 @@ int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int *splits_out)
         p.chunks_per_split = 131072 / PIX;
     }
     splits = (p.nchunks + p.chunks_per_split - 1) / p.chunks_per_split;
-    if (splits > max_splits) return EOQ_ERR_SHAPE;
+    if (splits > max_splits) return EOQ_ERR_WORKSPACE;     // the partial sums of the shortest legal ranges do not fit
     static std::atomic<bool> attr_done{false};
     void (*kern_full)(WgradParams) = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true>;
     void (*kern_part)(WgradParams) = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false>;
@@ -529,10 +529,61 @@ int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int *splits_out)
     return EOQ_OK;
 }
 
+// ---- scratch of the entry point that allocates nothing (eoq_conv_bwd_weight_static) ----------------------
+// A file-scope device array: every GPU the library runs on holds its own copy, at its own address, until the
+// process ends.  In host code the array's NAME is only a stand-in for the symbol, not a device address: the
+// address is looked up once per device (wgrad_static_scratch_init, called by eoq_create with that device
+// current) and only that pointer is ever handed to kernels.
+constexpr size_t WGRAD_STATIC_BYTES = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char wgrad_static_scratch[WGRAD_STATIC_BYTES];
+constexpr int WGRAD_MAX_DEVICES = 64;
+std::mutex wgrad_static_mutex;
+void *wgrad_static_ptr[WGRAD_MAX_DEVICES];
+
+int wgrad_run(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *e, const int8_t *u, int32_t *g_acc,
+              int32_t *absmax_slot, void *ws, size_t ws_bytes, bool caller_ws);
+
 } // namespace
+
+int wgrad_static_scratch_init(int device, void **ptr_out)
+{
+    if (device < 0 || device >= WGRAD_MAX_DEVICES) return EOQ_ERR_ARG;
+    std::lock_guard<std::mutex> lock(wgrad_static_mutex);
+    if (!wgrad_static_ptr[device]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(wgrad_static_scratch)) != hipSuccess || !ptr) return EOQ_ERR_HIP;
+        wgrad_static_ptr[device] = ptr;
+    }
+    *ptr_out = wgrad_static_ptr[device];
+    return EOQ_OK;
+}
 
 extern "C" int eoq_conv_bwd_weight(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *e, const int8_t *u,
                                    int32_t *g_acc, int32_t *absmax_slot, void *ws, size_t ws_bytes)
+{
+    if (!c || !d) return EOQ_ERR_ARG;
+    if (!ws || ws_bytes < eoq_workspace_bytes(d, EOQ_OP_CONV_BWD_WEIGHT) || ((uintptr_t)ws & 15)) {
+        // (argument and shape errors are reported first, as before)
+        const int rc = wgrad_run(c, d, e, u, g_acc, absmax_slot, nullptr, 0, true);
+        return rc != EOQ_OK ? rc : EOQ_ERR_WORKSPACE;
+    }
+    return wgrad_run(c, d, e, u, g_acc, absmax_slot, ws, ws_bytes, true);
+}
+
+extern "C" int eoq_conv_bwd_weight_static(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *e, const int8_t *u,
+                                          int32_t *g_acc, int32_t *absmax_slot)
+{
+    if (!c || !d) return EOQ_ERR_ARG;
+    if (!c->static_scratch) return EOQ_ERR_HIP;
+    return wgrad_run(c, d, e, u, g_acc, absmax_slot, c->static_scratch, WGRAD_STATIC_BYTES, false);
+}
+
+namespace {
+
+// ws == nullptr: validate arguments and shape only (no launch).  caller_ws: the workspace was sized by
+// eoq_workspace_bytes (its split cap applies); otherwise the split count is whatever fits ws_bytes.
+int wgrad_run(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *e, const int8_t *u, int32_t *g_acc,
+              int32_t *absmax_slot, void *ws, size_t ws_bytes, bool caller_ws)
 {
     if (!c || !d || !e || !u || !g_acc || !absmax_slot) return EOQ_ERR_ARG;
     if (d->N <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0 || d->stride <= 0 ||
@@ -541,7 +592,28 @@ extern "C" int eoq_conv_bwd_weight(eoq_ctx *c, const eoq_conv_desc *d, const int
     const int P = conv_out_dim(d->H, d->pad, d->R, d->stride), Q = conv_out_dim(d->W, d->pad, d->S, d->stride);
     if (P <= 0 || Q <= 0 || d->K % 16) return EOQ_ERR_SHAPE;
     if (((uintptr_t)e | (uintptr_t)u | (uintptr_t)g_acc) & 15) return EOQ_ERR_ARG;
-    if (!ws || ws_bytes < eoq_workspace_bytes(d, EOQ_OP_CONV_BWD_WEIGHT) || ((uintptr_t)ws & 15)) return EOQ_ERR_WORKSPACE;
+    if (!ws) return EOQ_OK;
+    // bytes in front of the partial sums: the staged copy of a few-channel or odd-channel input
+    // and the elements of one partial-sum buffer (rows padded like the staged input)
+    size_t prefix = 0, part_elems = (size_t)d->K * d->R * d->S * d->C;
+    if (d->C % 16 && d->C <= 4) {
+        const Pad4Geom g = pad4_geom(d);
+        prefix = round_up(g.img_bytes, 256) + round_up(g.w_bytes, 256);
+        part_elems = (size_t)d->K * g.KP;
+    } else if (d->C % 16) {
+        const size_t KPx = round_up((size_t)d->R * d->S * d->C, 64);
+        prefix = round_up((size_t)d->N * P * Q * KPx, 256) + round_up((size_t)d->K * KPx, 256);
+        part_elems = (size_t)d->K * KPx;
+    }
+    if (prefix >= ws_bytes) return EOQ_ERR_WORKSPACE;
+    // as many partial-sum buffers as the scratch holds, at most the cap eoq_workspace_bytes was sized for; the
+    // shortest legal ranges (131072 terms) need at least min_splits of them -- all decided before the first launch
+    size_t fit = (ws_bytes - prefix) / ((part_elems + WGRAD_PART_PAD) * 4);
+    const size_t cap = (size_t)wgrad_max_splits(part_elems);
+    if (caller_ws || fit > cap) fit = cap;
+    const size_t min_splits = ((size_t)d->N * P * Q + 131071) / 131072;
+    if (fit < 1 || fit < min_splits) return EOQ_ERR_WORKSPACE;
+    const int max_splits = (int)fit;
 
     WgradParams p{};
     p.E = e;
@@ -590,13 +662,14 @@ extern "C" int eoq_conv_bwd_weight(eoq_ctx *c, const eoq_conv_desc *d, const int
     p.RS = p.R * p.S;
     p.part = part;
     p.part_stride = (size_t)p.K * p.RS * p.C + WGRAD_PART_PAD;
+    if (p.part_stride != part_elems + WGRAD_PART_PAD) return EOQ_ERR_SHAPE;      // (cannot happen: same geometry)
     int splits = 0, rc;
     if (p.RS == 1) {
-        if (p.K >= 128) rc = launch_wgrad<2, 2, 2, 2, 1, 2>(c, p, p.RS, &splits);
-        else rc = launch_wgrad<2, 2, 1, 2, 1, 2>(c, p, p.RS, &splits);
+        if (p.K >= 128) rc = launch_wgrad<2, 2, 2, 2, 1, 2>(c, p, p.RS, max_splits, &splits);
+        else rc = launch_wgrad<2, 2, 1, 2, 1, 2>(c, p, p.RS, max_splits, &splits);
     } else {
-        if (p.R == 3 && p.S == 3 && p.stride == 1) rc = launch_wgrad<2, 2, 1, 1, 9, 2>(c, p, p.RS, &splits);
-        else rc = launch_wgrad<2, 2, 1, 1, 9, 5>(c, p, p.RS, &splits);
+        if (p.R == 3 && p.S == 3 && p.stride == 1) rc = launch_wgrad<2, 2, 1, 1, 9, 2>(c, p, p.RS, max_splits, &splits);
+        else rc = launch_wgrad<2, 2, 1, 1, 9, 5>(c, p, p.RS, max_splits, &splits);
     }
     if (rc != EOQ_OK) return rc;
     const size_t total = (size_t)d->K * rsc;
@@ -620,3 +693,5 @@ extern "C" int eoq_conv_bwd_weight(eoq_ctx *c, const eoq_conv_desc *d, const int
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }
+
+} // namespace

@@ -17,6 +17,7 @@ extern "C" int eoq_create(eoq_ctx **out, void *hip_stream)
     if (!c) return EOQ_ERR_ARG;
     c->stream = (hipStream_t)hip_stream;
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return EOQ_ERR_HIP; }
+    if (wgrad_static_scratch_init(c->device, &c->static_scratch) != EOQ_OK) { delete c; return EOQ_ERR_HIP; }
     if (hipMalloc((void **)&c->d_status, 256) != hipSuccess) { delete c; return EOQ_ERR_HIP; }
     if (hipMalloc((void **)&c->d_scratch, sizeof(int32_t) * EOQ_SCRATCH_SLOTS) != hipSuccess) {
         (void)hipFree(c->d_status);

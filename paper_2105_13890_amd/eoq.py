@@ -21,7 +21,7 @@ RQ_FWD, RQ_SQ_ACC, RQ_SQ_GAMMA, RQ_SQ_MERGE = 0, 1, 2, 3
 EXPORTS = [
     "eoq_create", "eoq_destroy", "eoq_strerror", "eoq_status", "eoq_spec_counters", "eoq_workspace_bytes", "eoq_fill_zero",
     "eoq_reduce_sum_i64",
-    "eoq_quantize", "eoq_pre_bias", "eoq_conv_fwd", "eoq_conv_bwd_data", "eoq_conv_bwd_data_sq", "eoq_transpose_filters", "eoq_conv_bwd_weight",
+    "eoq_quantize", "eoq_pre_bias", "eoq_conv_fwd", "eoq_conv_bwd_data", "eoq_conv_bwd_data_sq", "eoq_transpose_filters", "eoq_conv_bwd_weight", "eoq_conv_bwd_weight_static",
     "eoq_relu_bwd", "eoq_relu_bwd_recompute", "eoq_merge_absmax", "eoq_requant_epilogue", "eoq_update_int8", "eoq_grad_update", "eoq_update_scalars",
     "eoq_maxpool_fwd", "eoq_maxpool_bwd", "eoq_maxpool_bwd_sq", "eoq_gap_sum", "eoq_broadcast_hw", "eoq_head_workspace_bytes",
     "eoq_head_fwd_bwd",
@@ -88,6 +88,7 @@ def _load():
     lib.eoq_transpose_filters.argtypes = [vp, C.POINTER(ConvDesc), vp, vp]
     lib.eoq_conv_bwd_data_sq.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, i32, vp, vp, C.POINTER(BwdFuse), vp, sz]
     lib.eoq_conv_bwd_weight.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, sz]
+    lib.eoq_conv_bwd_weight_static.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp]
     lib.eoq_relu_bwd.argtypes = [vp, vp, vp, vp, sz, vp, vp, vp, vp]
     lib.eoq_relu_bwd_recompute.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, vp, vp, vp, vp, vp]
     lib.eoq_merge_absmax.argtypes = [vp, vp, vp, vp, vp, sz, vp]
@@ -213,6 +214,10 @@ class Context:
     def conv_bwd_weight(self, desc, e, u, g_acc, absmax_slot, ws):
         _check(_lib.eoq_conv_bwd_weight(self._h, C.byref(desc), _ptr(e), _ptr(u), _ptr(g_acc), _ptr(absmax_slot),
                                         _ptr(ws), _nbytes(ws)), "eoq_conv_bwd_weight")
+
+    def conv_bwd_weight_static(self, desc, e, u, g_acc, absmax_slot):
+        _check(_lib.eoq_conv_bwd_weight_static(self._h, C.byref(desc), _ptr(e), _ptr(u), _ptr(g_acc),
+                                               _ptr(absmax_slot)), "eoq_conv_bwd_weight_static")
 
     def relu_bwd(self, e0, mask, t_wide, e1, sum_e1=None, sum_e1t=None, absmax_e1=None):
         _check(_lib.eoq_relu_bwd(self._h, _ptr(e0), _ptr(mask), _ptr(t_wide), e0.numel(), _ptr(e1), _ptr(sum_e1),
