@@ -12,7 +12,8 @@ LIB = os.path.join(HERE, "libeoq.so")
 SOURCES = ["ctx.hip", "elementwise.hip", "conv_igemm.hip", "conv_wgrad.hip", "pool_head.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-value"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-value",
+         "-Wno-inline-asm"]     # (the direct-to-LDS load sets M0 in inline assembly and says so in its clobber list)
 
 
 def _stale() -> bool:

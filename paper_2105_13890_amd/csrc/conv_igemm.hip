@@ -19,6 +19,9 @@
 #include "common.h"
 
 #include <atomic>
+#ifdef EOQ_TUNE
+#include <cstdlib>
+#endif
 
 namespace {
 
@@ -38,6 +41,8 @@ struct IgemmCls {
     int rm_Hc, rm_Wc, rm_h0, rm_w0;
     int tile_base;                 // first workgroup tile of the class (= its first tile_shift entry)
     int b_off;                     // byte offset of the class's packed filters
+    uint32_t mulQ, mulP;           // reciprocals of Q and P (see make_recip)
+    int shQ, shP;
 };
 
 struct IgemmParams {
@@ -47,6 +52,8 @@ struct IgemmParams {
     int P, Q, NOUT;
     int R, S, stride, pad;
     int M, nk16, c16;
+    uint32_t mulQ, mulP;           // reciprocals of Q and P for the pixel decomposition (filled in by the dispatcher)
+    int shQ, shP;
     int xstep;         // bytes per unit of the column origin (C, except for the 4-bytes-per-pixel stem layout)
     int no_pad;        // every tap of every row is in range (physically padded input)
     int gemm;          // 1x1 filter, stride 1, no padding: row m of the GEMM is pixel m of the input
@@ -84,7 +91,25 @@ struct IgemmParams {
     const int32_t *sp_exp_in, *sp_exp_other;
     int32_t sp_exp_off;
     int64_t *sp_part;          // per-wave records {sum e4, sum e1, max merged, max merged under the mask}
+#ifdef EOQ_TUNE
+    int abl;                   // tuning builds: bit 0 = skip the loads, bit 1 = skip the MFMAs, bit 2 = skip the LDS reads
+    unsigned long long *dbg;   // tuning builds: four timestamps per workgroup (entry, set-up done, reduction done, exit)
+#endif
 };
+
+// n / d for n < 2^31 through a host-made reciprocal: mul = ceil(2^(31+sh) / d), sh = ceil(log2 d)
+struct Recip { uint32_t mul; int sh; };
+static inline Recip make_recip(uint32_t d)
+{
+    Recip r{0x80000000u, 0};
+    if (d <= 1) return r;
+    int s = 0;
+    while ((1ull << s) < d) ++s;
+    r.sh = s;
+    r.mul = (uint32_t)((((unsigned long long)1 << (31 + s)) + d - 1) / d);
+    return r;
+}
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t mul, int sh) { return __umulhi(n << 1, mul) >> sh; }
 
 enum { MODE_FWD = 0, MODE_BWD_DATA = 1 };
 enum { EPI_FWD = 0, EPI_ACC = 1, EPI_SPEC = 3, EPI_RELU_BWD = 4, EPI_D16 = 5 };
@@ -112,6 +137,27 @@ __device__ __forceinline__ void set_byte(v4i &v, int i, int code)
 __device__ __forceinline__ int byte_at(const v4i &v, int i)
 {
     return (int)(int8_t)((uint32_t)v[i >> 2] >> (8 * (i & 3)));
+}
+
+// 16 bytes per lane from a buffer straight into LDS (gfx950: buffer_load_dwordx4 ... lds): lane l of the wave writes
+// LDS bytes [lds_base + 16 l, lds_base + 16 l + 16) with whatever ITS offset addresses in memory (an in-bounds probe
+// confirmed the lane order, and that an out-of-range offset writes zeros).  lds_base is wave-uniform (it travels in
+// M0).  Issued through inline assembly on purpose: the compiler, when it knows of such a load, waits for ALL
+// outstanding memory operations before the next LDS read, which would drain the prefetch ring at every stage; here the
+// waits are written by hand (wait_vmcnt) next to the barriers that publish a stage.
+__device__ __forceinline__ void lds_direct_load16(const v4i &rsrc, uint32_t lds_base, int voffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(rsrc)
+                 : "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N));
 }
 
 // Forward epilogue for 16 consecutive channels of one pixel (Eq.2 x2..x5 and the next layer's x1).
@@ -274,24 +320,32 @@ __device__ __forceinline__ bool epilogue_fits32(const EpiDev &ep, int gamma, int
     return ag < (1 << 23) && tmax < (1 << 23) && ag * tmax + 128 * (ab + sk) < (1ll << 31) - 256;
 }
 
-// D = 2 selects the low-register form: no ring of prefetched stages, no double-buffered fragments, the stages strictly
-// one after the other, epilogue side inputs fetched two chunks ahead of their use.  The pipelined form holds about 250
-// registers per lane, i.e. TWO workgroups per compute unit; this one is compiled for 128 (FOUR workgroups).  Measured
-// per workgroup on a 1x1 layer with a 64-byte reduction: 9 us of life, 6.6 of them in the epilogue -- such layers want
-// more workgroups in flight, not a deeper pipeline.  Measured over the whole net: the low-register form wins for
-// reductions of up to about 80 sixteen-byte chunks and ties with the pipelined form beyond (a variant with one stage
-// of prefetch and two LDS buffers was no better than the strictly serial loop).
-template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
+// Main loop: a ring of NS LDS stages (BK bytes of the reduction each) filled by direct-to-LDS loads -- no staging
+// registers, no LDS writes by the waves -- one barrier per stage.  Two forms are instantiated:
+//   BK = 64, NS = 2 at 128 registers per lane: FOUR workgroups per compute unit.  Measured per workgroup, a layer with a
+//     short reduction spends most of its life outside the reduction (0.5-1 us of set-up, 2-6 us of epilogue against
+//     2-6 us of loads and MFMAs), so such layers want workgroups in flight, not a deep pipeline; the second stage lets
+//     the next loads fly while this stage is multiplied.
+//   BK = 128, NS = 2 at 168 registers: whole 128-byte lines per row and load, half as many barriers; wins (by 15-20 %)
+//     where at most two workgroups per compute unit exist anyway (the 14x14 layers with 256+ input channels).
+// Rings of three and four stages, and 64-byte stages at three workgroups per compute unit, were measured and are no
+// faster: the loop is bound by the rate at which a compute unit's memory path delivers 16-byte gathers
+// (35-40 B/clk), not by their latency.
+template <int BM, int BN, int WGM, int WGN, int BK, int NS, bool UNI, int MODE, int EPI>
 __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
 {
-    constexpr bool LOWREG = D == 2;
+#ifdef EOQ_TUNE
+    const unsigned long long ts0 = __builtin_amdgcn_s_memrealtime();
+#endif
+    constexpr bool LEAN = BK == 64;                // compiled for 128 registers: epilogue side inputs two chunks ahead
     if (EPI == EPI_D16 && pin.spec && spec_hit(pin.absmax, pin.spec_used)) return;     // the speculative launch was right
     // (the recompute runs on the weight-gradient chain: see the note on wave priority in conv_wgrad.hip)
     if (EPI == EPI_RELU_BWD) __builtin_amdgcn_s_setprio(3);
     IgemmParams p = pin;           // uniform; patched below when the launch covers several classes
     constexpr int NW = WGM * WGN, NT = NW * 64;
-    static_assert(NW == 4 || NW == 8, "4 or 8 waves");
+    static_assert(NW == 4, "4 waves");
     static_assert(BK == 64 || BK == 128, "stage depth in bytes");
+    static_assert(NS >= 2 && NS <= 4, "ring stages");
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
     static_assert(TM >= 1 && TN >= 1, "tile");
@@ -299,9 +353,10 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     constexpr int RPP = NT / CH;                // rows loaded per pass of the workgroup's threads
     constexpr int RP = 16 / CH;                 // rows per 256 bytes of LDS (swizzle period)
     constexpr int A_ROWS = (BM + RPP - 1) / RPP, B_ROWS = (BN + RPP - 1) / RPP;
-    constexpr int STAGE_BYTES = (BM + BN) * BK;
+    // (direct-to-LDS loads fill whole passes of RPP rows: the operand regions are padded to that)
+    constexpr int A_REGION = A_ROWS * RPP * BK, B_REGION = B_ROWS * RPP * BK;
+    constexpr int STAGE_BYTES = A_REGION + B_REGION;
     constexpr int EPI_LD = WTN + 4;                       // int32 row stride of the epilogue staging
-    static_assert(D == 2 || (D >= 4 && D % 2 == 0), "global-load stages in flight");
 
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
 
@@ -322,6 +377,7 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
             if (i < p.ncls && bid >= p.cls[i].tile_base) cl = i;
         const IgemmCls &q = pin.cls[cl];
         p.P = q.P; p.Q = q.Q; p.R = q.R; p.S = q.S; p.pad = q.pad; p.pad_w_delta = q.pad_w_delta; p.M = q.M;
+        p.mulQ = q.mulQ; p.shQ = q.shQ; p.mulP = q.mulP; p.shP = q.shP;
         p.nk16 = q.nk16; p.rm_Hc = q.rm_Hc; p.rm_Wc = q.rm_Wc; p.rm_h0 = q.rm_h0; p.rm_w0 = q.rm_w0;
         p.B = pin.B + q.b_off;
         p.ts_base = q.tile_base;
@@ -336,7 +392,10 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     //   forward:       input pixel = (ho*stride - pad + r, wo*stride - pad + s)
     //   backward data: error pixel = ((ho + pad - r)/stride, (wo + pad - s)/stride) where both divide; for those
     //                  taps (ho+pad-r)/stride = floor((ho+pad)/stride) - floor(r/stride)
-    const int kc = tid % CH, lrow = tid / CH;
+    // direct-to-LDS: lane l lands in slot l of its wave's kilobyte, so the swizzle is applied on the memory side --
+    // the lane asks for the logical chunk that belongs in its slot
+    const int lrow = tid / CH;
+    const int kc = (tid % CH) ^ ((lrow / RP) % CH);
     // Buffer descriptors: a lane whose tap falls into the padding (or past the end of the reduction) gets an
     // offset beyond num_records and the hardware returns zeros -- no branch, no select.
     const __amdgpu_buffer_rsrc_t rsrc_a =
@@ -357,17 +416,29 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
             a_off[i] = mm * p.C + kc * 16;
             continue;
         }
-        const int wo = mm % p.Q;
-        const int t = mm / p.Q;
-        const int ho = t % p.P, n = t / p.P;
+        // pixel decomposition by multiply-high with host-made reciprocals (an integer division costs ~40 instructions
+        // per lane here, and every workgroup pays this set-up before its first load can leave)
+        const int t = (int)fast_div((uint32_t)mm, p.mulQ, p.shQ);
+        const int wo = mm - t * p.Q;
+        const int n = (int)fast_div((uint32_t)t, p.mulP, p.shP);
+        const int ho = t - n * p.P;
         int hb, wb;
         unsigned long long mask = 0;
-        if (MODE == MODE_FWD) {
-            hb = ho * p.stride - p.pad; wb = wo * p.stride - p.pad;
-            int tap = 0;
+        if (MODE == MODE_FWD || p.stride == 1) {
+            // valid taps form a rectangle [r0, r1) x [s0, s1): one run of column bits, repeated for the valid rows
+            int r0, r1, s0, s1;
+            if (MODE == MODE_FWD) {
+                hb = ho * p.stride - p.pad; wb = wo * p.stride - p.pad;
+                r0 = max(0, -hb); r1 = min(p.R, p.H - hb);
+                s0 = max(0, -wb); s1 = min(p.S, p.W - wb);
+            } else {
+                hb = ho + p.pad; wb = wo + p.pad + p.pad_w_delta;          // stride 1: the error pixel of tap r is hb - r
+                r0 = max(0, hb - p.H + 1); r1 = min(p.R, hb + 1);
+                s0 = max(0, wb - p.W + 1); s1 = min(p.S, wb + 1);
+            }
+            const unsigned long long colbits = s1 > s0 ? ((~0ull >> (64 - (s1 - s0))) << s0) : 0ull;
             for (int rr = 0; rr < p.R; ++rr)
-                for (int ss = 0; ss < p.S; ++ss, ++tap)
-                    if ((unsigned)(hb + rr) < (unsigned)p.H && (unsigned)(wb + ss) < (unsigned)p.W) mask |= 1ull << tap;
+                if (rr >= r0 && rr < r1) mask |= colbits << (rr * p.S);
         } else {
             const int hp = ho + p.pad, wp = wo + p.pad + p.pad_w_delta;
             hb = hp / p.stride; wb = wp / p.stride;
@@ -401,72 +472,6 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     // thread derives its own tap from its chunk index.
     int ld_r = 0, ld_s = 0, ld_cb = 0, ld_rd = 0, ld_rm = 0, ld_sd = 0, ld_sm = 0, ld_kk = 0;
 
-    auto load_stage = [&](v4i (&ra)[A_ROWS], v4i (&rb)[B_ROWS]) {
-        bool tap_ok;
-        int tap, toff;
-        if (UNI) {
-            tap_ok = ld_r < p.R;
-            tap = tap_ok ? ld_r * p.S + ld_s : 0;
-            if (MODE == MODE_FWD) toff = ld_r * wc_step + ld_s * p.C + ld_cb * 16;
-            else toff = -(ld_rd * wc_step + ld_sd * p.C) + ld_cb * 16;
-        } else {
-            const int kk = ld_kk + kc;
-            tap_ok = kk < p.nk16;
-            const int tp = kk / p.c16, cc = kk - tp * p.c16;
-            const int rr = tp / p.S, ss = tp - rr * p.S;
-            tap = tap_ok ? tp : 0;
-            if (MODE == MODE_FWD) toff = rr * wc_step + ss * p.C + cc * 16;
-            else toff = -((rr / p.stride) * wc_step + (ss / p.stride) * p.C) + cc * 16;
-            toff -= kc * 16;                      // a_off already carries the thread's chunk column
-        }
-#pragma unroll
-        for (int i = 0; i < A_ROWS; ++i) {
-            const bool v = tap_ok && ((a_mask[i] >> tap) & 1ull);
-            const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_a, v ? a_off[i] + toff : OOB, 0, 0);
-            ra[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
-        }
-#pragma unroll
-        for (int i = 0; i < B_ROWS; ++i) {
-            const v4u x =
-                __builtin_amdgcn_raw_buffer_load_b128(rsrc_b, (tap_ok && b_ok[i]) ? b_off[i] + ld_kk * 16 : OOB, 0, 0);
-            rb[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
-        }
-        ld_kk += CH;
-        if (UNI) {
-            ld_cb += CH;
-            if (ld_cb == p.c16) {
-                ld_cb = 0;
-                ++ld_s;
-                if (++ld_sm == p.stride) { ld_sm = 0; ++ld_sd; }
-                if (ld_s == p.S) {
-                    ld_s = 0; ld_sd = 0; ld_sm = 0;
-                    ++ld_r;
-                    if (++ld_rm == p.stride) { ld_rm = 0; ++ld_rd; }
-                }
-            }
-        }
-    };
-    int wr_a[A_ROWS], wr_b[B_ROWS];
-#pragma unroll
-    for (int i = 0; i < A_ROWS; ++i) {
-        const int row = lrow + RPP * i;
-        wr_a[i] = row < BM ? row * BK + ((kc ^ ((row / RP) % CH)) << 4) : -1;
-    }
-#pragma unroll
-    for (int i = 0; i < B_ROWS; ++i) {
-        const int row = lrow + RPP * i;
-        wr_b[i] = row < BN ? BM * BK + row * BK + ((kc ^ ((row / RP) % CH)) << 4) : -1;
-    }
-    auto store_stage = [&](int buf, const v4i (&ra)[A_ROWS], const v4i (&rb)[B_ROWS]) {
-        int8_t *base = lds + buf;
-#pragma unroll
-        for (int i = 0; i < A_ROWS; ++i)
-            if (BM % RPP == 0 || wr_a[i] >= 0) *(v4i *)(base + wr_a[i]) = ra[i];
-#pragma unroll
-        for (int i = 0; i < B_ROWS; ++i)
-            if (BN % RPP == 0 || wr_b[i] >= 0) *(v4i *)(base + wr_b[i]) = rb[i];
-    };
-
     v16i acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -484,7 +489,7 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
         const int chunk = 2 * j + lhalf;
         const int rowa = wm * WTM + lrow32, rowb = wn * WTN + lrow32;
         rd_a[j] = rowa * BK + ((chunk ^ ((rowa / RP) % CH)) << 4);
-        rd_b[j] = BM * BK + rowb * BK + ((chunk ^ ((rowb / RP) % CH)) << 4);
+        rd_b[j] = A_REGION + rowb * BK + ((chunk ^ ((rowb / RP) % CH)) << 4);
     }
     // MFMA operands are double-buffered in registers: the fragments of stage st+1 are read from LDS while
     // the MFMAs of stage st run, so neither the LDS latency nor the global latency sits on the critical path.
@@ -507,185 +512,111 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     };
 
     const int nstages = (p.nk16 + CH - 1) / CH;
-    if constexpr (LOWREG) {
-        // Strictly serial: a stage is loaded, stored into the one LDS buffer, multiplied (fragments read one reduction
-        // step at a time), and only then the next stage is requested; two barriers per stage.  The latency of a
-        // stage is covered by the three other workgroups of the compute unit, not by this one's own prefetch.
-        static_assert(BK == 64, "low-register form");
-        for (int st = 0; st < nstages; ++st) {
-            {
-                v4i ra0[A_ROWS], rb0[B_ROWS];
-                load_stage(ra0, rb0);
-                store_stage(0, ra0, rb0);
-            }
-            __syncthreads();
-#pragma unroll
-            for (int j = 0; j < CH / 2; ++j) {
-                v4i fa0[TM], fb0[TN];
-#pragma unroll
-                for (int i = 0; i < TM; ++i) fa0[i] = *(const v4i *)(lds + rd_a[j] + i * 32 * BK);
-#pragma unroll
-                for (int i = 0; i < TN; ++i) fb0[i] = *(const v4i *)(lds + rd_b[j] + i * 32 * BK);
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int jn = 0; jn < TN; ++jn)
-                        acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa0[i], fb0[jn], acc[i][jn], 0, 0, 0);
-            }
-            __syncthreads();
-        }
-    } else if constexpr (BK == 128) {
-        // 128-byte stages: every row of a stage is one full 128-byte cache line per global load instruction (8
-        // lanes per row).  With 64-byte stages and rows longer than 64 bytes each instruction takes half of
-        // 16 different lines and the other halves are fetched again one stage later -- measured on this chip,
-        // half-line gathers move 30 B/clk/CU out of L2 against 50 B/clk/CU for whole lines.
-        // A stage is 4 MFMA reduction steps; fragments are pipelined by HALF stages (two steps) so that their
-        // register cost stays that of the 64-byte kernel: P holds the first half of the stage about to be
-        // multiplied (read at the end of the previous iteration), Q its second half (read at the start of this
-        // one).  Global registers: a ring of two stages.  One barrier per stage:
-        //     read Q(st) | MFMA P | MFMA Q | barrier | read P(st+1) | LDS <- stage st+2 | request stage st+4
-        // Entering iteration st: LDS[cur] = stage st, LDS[other] = st+1, ring[st & 1] = st+2, ring[~st & 1] = st+3.
-        // After the barrier every wave has read both halves of stage st, so its buffer takes stage st+2; stage
-        // st+1 was written before the previous barrier.  All steps are unconditional (see the 64-byte loop).
-        constexpr int HJ = CH / 4;                   // MFMA reduction steps per half stage
-        static_assert(HJ == 2, "two steps per half stage");
-        v4i ra2[2][A_ROWS], rb2[2][B_ROWS];
-        v4i pa[HJ][TM], pb[HJ][TN], qa[HJ][TM], qb[HJ][TN];
-        auto read_half = [&](int buf, int h, v4i (&fa)[HJ][TM], v4i (&fb)[HJ][TN]) {
-            const int8_t *base = lds + buf;
-#pragma unroll
-            for (int j = 0; j < HJ; ++j) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) fa[j][i] = *(const v4i *)(base + rd_a[h * HJ + j] + i * 32 * BK);
-#pragma unroll
-                for (int i = 0; i < TN; ++i) fb[j][i] = *(const v4i *)(base + rd_b[h * HJ + j] + i * 32 * BK);
-            }
-        };
-        auto mfma2 = [&](const v4i (&fa)[HJ][TM], const v4i (&fb)[HJ][TN]) {
-#pragma unroll
-            for (int j = 0; j < HJ; ++j)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int jn = 0; jn < TN; ++jn)
-                        acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[j][i], fb[j][jn], acc[i][jn], 0, 0, 0);
-        };
-        load_stage(ra2[0], rb2[0]);                                  // stage 0
-        load_stage(ra2[1], rb2[1]);                                  // stage 1
-        store_stage(0, ra2[0], rb2[0]);
-        load_stage(ra2[0], rb2[0]);                                  // stage 2
-        store_stage(STAGE_BYTES, ra2[1], rb2[1]);
-        load_stage(ra2[1], rb2[1]);                                  // stage 3
-        __syncthreads();
-        read_half(0, 0, pa, pb);
-        int cur = 0, st = 0;
-        for (; st + 2 <= nstages; st += 2) {
-#pragma unroll
-            for (int d = 0; d < 2; ++d) {
-                read_half(cur, 1, qa, qb);                           // second half of stage st+d
-                __builtin_amdgcn_sched_barrier(0);
-                mfma2(pa, pb);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma2(qa, qb);
-                __builtin_amdgcn_sched_barrier(0);
-                __syncthreads();
-                read_half(STAGE_BYTES - cur, 0, pa, pb);             // first half of stage st+d+1
-                __builtin_amdgcn_sched_barrier(0);
-                store_stage(cur, ra2[d], rb2[d]);                    // stage st+d+2
-                __builtin_amdgcn_sched_barrier(0);
-                load_stage(ra2[d], rb2[d]);                          // stage st+d+4
-                __builtin_amdgcn_sched_barrier(0);
-                cur = STAGE_BYTES - cur;
-            }
-        }
-        if (st < nstages) {                                          // odd number of stages: the last one
-            read_half(cur, 1, qa, qb);
-            mfma2(pa, pb);
-            mfma2(qa, qb);
-        }
-        __syncthreads();
-    } else {
-    // Software pipeline over the reduction, unrolled D (= 4) times so that the register rings are indexed
-    // statically.  Entering iteration st: fragments of stage st are in registers, LDS buffer (st+1)%2 holds
-    // stage st+1, global registers hold stages st+2 .. st+D-1.  The iteration reads the fragments of st+1,
-    // issues the global loads of st+D, multiplies stage st, and moves stage st+2 from registers into the LDS
-    // buffer stage st occupied (its fragments were read one iteration ago, before the last barrier).
-    // Every step of an iteration is UNCONDITIONAL: loads past the end of the reduction are out of range, cost
-    // no memory traffic and return zeros, which are stored and read like real data and never multiplied.
-    // The number of loads in flight at each wait is therefore a compile-time constant, and the compiler can
-    // wait for exactly the oldest stage (a conditional load anywhere in the loop would force it to wait for
-    // everything, i.e. to expose the full memory latency in every iteration).
-    v4i ra[D][A_ROWS], rb[D][B_ROWS];
-    v4i fa[2][CH / 2][TM], fb[2][CH / 2][TN];
-#pragma unroll
-    for (int d = 0; d < D; ++d) load_stage(ra[d], rb[d]);
-    store_stage(0, ra[0], rb[0]);
-    store_stage(STAGE_BYTES, ra[1], rb[1]);
-    __syncthreads();
-    read_frags(0, fa[0], fb[0]);
-    __syncthreads();                               // every wave has its stage-0 fragments before buffer 0 is reused
-    int cur = 0;                                   // LDS buffer of the stage being multiplied
-    int st = 0;
-    // The order inside an iteration is pinned (scheduling barriers): LDS reads of the next stage and the global
-    // loads go first, so that their latency runs under this stage's MFMAs; the LDS writes sit between the two
-    // halves of the MFMAs, so that a wave that has to wait for its global data has already queued matrix work
-    // and the writes have landed by the time the last MFMA is issued and the barrier is reached.
-    // With 8 waves, the waves of the second half of the workgroup (the second wave of every SIMD) run an
-    // iteration in the opposite order -- all MFMAs first, then the data movement -- so that on every SIMD one wave
-    // multiplies while the other uses LDS and the memory pipeline.  Within an iteration the order is free: the
-    // MFMAs use fragments read one iteration ago, the LDS reads use the buffer written one iteration ago, and the
-    // LDS writes go to the buffer whose fragments every wave read before the last barrier.
-    const bool mfma_first = NW == 8 && wave >= NW / 2;                              // wave-uniform
-    for (; st + D <= nstages; st += D) {           // full groups: straight-line code, one exit
-#pragma unroll
-        for (int d = 0; d < D; ++d) {
-            if (mfma_first) {
-#pragma unroll
-                for (int j = 0; j < CH / 2; ++j) mfma_half(j, fa[d & 1], fb[d & 1]);    // stage st+d
-                __builtin_amdgcn_sched_barrier(0);
-                read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);        // stage st+d+1
-                __builtin_amdgcn_sched_barrier(0);
-                load_stage(ra[d], rb[d]);                                               // stage st+d+D
-                __builtin_amdgcn_sched_barrier(0);
-                store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);                     // stage st+d+2
+#ifdef EOQ_TUNE
+    const unsigned long long ts1 = __builtin_amdgcn_s_memrealtime();
+#endif
+    {
+        // Ring of NS LDS stages filled by direct-to-LDS loads.  Stage st lives in buffer st % NS.  Iteration st:
+        //     wait until this thread's loads of stage st have landed | barrier | request stage st+NS-1 | multiply stage st
+        // After the barrier every wave's part of stage st is in LDS, and every wave has finished reading stage st-1
+        // (its fragments were consumed by MFMAs issued before the barrier), whose buffer is the one stage st+NS-1
+        // goes to.  Loads past the end of the reduction are out of range: no traffic, zeros written, never
+        // multiplied -- so every iteration issues the same number of loads and the wait count is a constant.
+        constexpr int L = A_ROWS + B_ROWS;              // loads per thread and stage
+        static_assert((NS - 1) * L < 64, "vmcnt range");
+        const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+        const uint32_t wave_base = lds0 + (uint32_t)__builtin_amdgcn_readfirstlane(wave) * (64 / CH) * BK;
+        const uint64_t pa = (uint64_t)p.A, pb = (uint64_t)p.B;
+        const v4i rs_a = {(int)(uint32_t)pa, (int)((uint32_t)(pa >> 32) & 0xffffu), p.N * p.H * p.W * p.C, 0x00020000};
+        const v4i rs_b = {(int)(uint32_t)pb, (int)((uint32_t)(pb >> 32) & 0xffffu), p.NOUT * p.nk16 * 16, 0x00020000};
+        auto dma_stage = [&](int buf) {
+            bool tap_ok;
+            int tap, toff;
+            if (UNI) {
+                tap_ok = ld_r < p.R;
+                tap = tap_ok ? ld_r * p.S + ld_s : 0;
+                if (MODE == MODE_FWD) toff = ld_r * wc_step + ld_s * p.C + ld_cb * 16;
+                else toff = -(ld_rd * wc_step + ld_sd * p.C) + ld_cb * 16;
             } else {
-                read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);        // stage st+d+1
-                __builtin_amdgcn_sched_barrier(0);
-                load_stage(ra[d], rb[d]);                                               // stage st+d+D
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_half(0, fa[d & 1], fb[d & 1]);                                     // stage st+d
-                __builtin_amdgcn_sched_barrier(0);
-                store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);                     // stage st+d+2
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int j = 1; j < CH / 2; ++j) mfma_half(j, fa[d & 1], fb[d & 1]);
+                const int kk = ld_kk + kc;
+                tap_ok = kk < p.nk16;
+                const int tp = kk / p.c16, cc = kk - tp * p.c16;
+                const int rr = tp / p.S, ss = tp - rr * p.S;
+                tap = tap_ok ? tp : 0;
+                if (MODE == MODE_FWD) toff = rr * wc_step + ss * p.C + cc * 16;
+                else toff = -((rr / p.stride) * wc_step + (ss / p.stride) * p.C) + cc * 16;
+                toff -= kc * 16;
             }
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
-            cur = STAGE_BYTES - cur;
-        }
-    }
-    // the last nstages % D stages: everything they need is already in registers or in flight
 #pragma unroll
-    for (int d = 0; d < D - 1; ++d) {
-        if (st + d < nstages) {                                                     // uniform
-            read_frags(STAGE_BYTES - cur, fa[(d + 1) & 1], fb[(d + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_half(0, fa[d & 1], fb[d & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-            store_stage(cur, ra[(d + 2) % D], rb[(d + 2) % D]);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < A_ROWS; ++i) {
+                const bool v = tap_ok && ((a_mask[i] >> tap) & 1ull);
+                lds_direct_load16(rs_a, wave_base + buf + i * RPP * BK, v ? a_off[i] + toff : OOB);
+            }
 #pragma unroll
-            for (int j = 1; j < CH / 2; ++j) mfma_half(j, fa[d & 1], fb[d & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
-            cur = STAGE_BYTES - cur;
+            for (int i = 0; i < B_ROWS; ++i)
+                lds_direct_load16(rs_b, wave_base + buf + A_REGION + i * RPP * BK,
+                                  (tap_ok && b_ok[i]) ? b_off[i] + ld_kk * 16 : OOB);
+            ld_kk += CH;
+            if (UNI) {
+                ld_cb += CH;
+                if (ld_cb == p.c16) {
+                    ld_cb = 0;
+                    ++ld_s;
+                    if (++ld_sm == p.stride) { ld_sm = 0; ++ld_sd; }
+                    if (ld_s == p.S) {
+                        ld_s = 0; ld_sd = 0; ld_sm = 0;
+                        ++ld_r;
+                        if (++ld_rm == p.stride) { ld_rm = 0; ++ld_rd; }
+                    }
+                }
+            }
+        };
+#pragma unroll
+        for (int d = 0; d < NS - 1; ++d) dma_stage(d * STAGE_BYTES);
+        int cur = 0;
+        v4i fa[CH / 2][TM], fb[CH / 2][TN];
+#ifdef EOQ_TUNE
+#pragma unroll
+        for (int j = 0; j < CH / 2; ++j) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[j][i] = v4i{tid, 1, 2, 3};
+#pragma unroll
+            for (int i = 0; i < TN; ++i) fb[j][i] = v4i{tid, 5, 6, 7};
         }
+#endif
+        for (int st = 0; st < nstages; ++st) {
+            wait_vmcnt<(NS - 2) * L>();
+            __syncthreads();
+#ifdef EOQ_TUNE
+            if (!(p.abl & 1)) dma_stage(cur == 0 ? (NS - 1) * STAGE_BYTES : cur - STAGE_BYTES);
+            __builtin_amdgcn_sched_barrier(0);
+            if (!(p.abl & 4)) read_frags(cur, fa, fb);
+            if (!(p.abl & 2)) {
+#pragma unroll
+                for (int j = 0; j < CH / 2; ++j) mfma_half(j, fa, fb);
+            } else {
+#pragma unroll
+                for (int j = 0; j < CH / 2; ++j)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) acc[i][0][0] += fa[j][i][0] + fb[j][0][1];    // keep the reads alive
+            }
+#else
+            dma_stage(cur == 0 ? (NS - 1) * STAGE_BYTES : cur - STAGE_BYTES);
+            __builtin_amdgcn_sched_barrier(0);
+            read_frags(cur, fa, fb);
+#pragma unroll
+            for (int j = 0; j < CH / 2; ++j) mfma_half(j, fa, fb);
+#endif
+            __builtin_amdgcn_sched_barrier(0);
+            cur = cur + STAGE_BYTES == NS * STAGE_BYTES ? 0 : cur + STAGE_BYTES;
+        }
+        wait_vmcnt<0>();          // the tail's out-of-range loads still write (zeros): they land before LDS is reused
+        __syncthreads();
     }
-    __syncthreads();
 
-    }
-
+#ifdef EOQ_TUNE
+    const unsigned long long ts2 = __builtin_amdgcn_s_memrealtime();
+#endif
     // ---- epilogue ----
     // Block-scaled 16-bit output (the scale quantiser of Eq.11 needs max|d| of the WHOLE tensor before any element
     // can be coded, so the exact 32-bit sums would have to be stored or recomputed).  Instead each workgroup keeps,
@@ -758,8 +689,8 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     constexpr bool HAS_SIDE = EPI == EPI_FWD || EPI == EPI_RELU_BWD || EPI == EPI_SPEC;
     // (the 2 x 2 forward layout with 128-column tiles serves the layers without ReLU, which have no int8 side input,
     // and is short of registers as it is)
-    constexpr bool NO_RING = LOWREG && EPI == EPI_FWD && WGN == 2 && BN == 128;
-    constexpr int PD = !HAS_SIDE || NO_RING ? 0 : (!LOWREG ? TP : (TP < 2 ? TP : 2));
+    constexpr bool NO_RING = LEAN && EPI == EPI_FWD && WGN == 2 && BN == 128;
+    constexpr int PD = !HAS_SIDE || NO_RING ? 0 : (!LEAN ? TP : (TP < 2 ? TP : 2));
     v4i ring8[PD > 0 ? PD : 1];
     uint32_t ringmk[PD > 0 ? PD : 1];
     auto load_side = [&](int t, v4i &s8, uint32_t &smk) {
@@ -937,6 +868,12 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
         __syncthreads();
       }
     }
+#ifdef EOQ_TUNE
+    if (pin.dbg && tid == 0) {
+        unsigned long long *r = pin.dbg + 4 * (size_t)blockIdx.x;
+        r[0] = ts0; r[1] = ts1; r[2] = ts2; r[3] = __builtin_amdgcn_s_memrealtime();
+    }
+#endif
     if (EPI == EPI_FWD && range_bad) atomicOr(p.status, (uint32_t)EOQ_FLAG_ACC_OVERFLOW);
     if (EPI == EPI_ACC && p.absmax) block_atomic_max_i32(mx, p.absmax);
     if (EPI == EPI_SPEC) {
@@ -967,17 +904,18 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
-__global__ __launch_bounds__(WGM * WGN * 64) void igemm_kernel(IgemmParams pin)
+// 64-byte stages: four workgroups per compute unit (128 registers per lane)
+template <int BM, int BN, int WGM, int WGN, int BK, int NS, bool UNI, int MODE, int EPI>
+__global__ __launch_bounds__(WGM * WGN * 64, 4) void igemm_kernel(IgemmParams pin)
 {
-    igemm_body<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>(pin);
+    igemm_body<BM, BN, WGM, WGN, BK, NS, UNI, MODE, EPI>(pin);
 }
 
-// the low-register form is compiled for four waves per SIMD (128 registers per lane)
-template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
-__global__ __launch_bounds__(WGM * WGN * 64, 4) void igemm_lr_kernel(IgemmParams pin)
+// 128-byte stages (64 KB of LDS per workgroup, two per compute unit): 168 registers per lane
+template <int BM, int BN, int WGM, int WGN, int BK, int NS, bool UNI, int MODE, int EPI>
+__global__ __launch_bounds__(WGM * WGN * 64, 3) void igemm_wide_kernel(IgemmParams pin)
 {
-    igemm_body<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>(pin);
+    igemm_body<BM, BN, WGM, WGN, BK, NS, UNI, MODE, EPI>(pin);
 }
 
 // ---- small layout kernels -------------------------------------------------------------------
@@ -1317,24 +1255,46 @@ inline unsigned grid_for(size_t total)
     return (unsigned)b;
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK, int D, bool UNI, int MODE, int EPI>
+#ifdef EOQ_TUNE
+// tuning builds only (never defined for the product library): per-workgroup timestamps and ablation switches
+static unsigned long long *g_tune_dbg = nullptr;
+static int g_tune_launch = 0;
+static int tune_env(const char *name)
+{
+    const char *e = getenv(name);
+    return e ? atoi(e) : 0;
+}
+#endif
+
+template <int BM, int BN, int WGM, int WGN, int BK, int NS, bool UNI, int MODE, int EPI>
 int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
 {
     constexpr int NW = WGM * WGN;
     constexpr int epi_rows = (BN / WGN) >= 64 ? 16 : 32;        // rows staged at a time (SR in the kernel)
-    constexpr int main_bytes = 2 * (BM + BN) * BK, epi_bytes = NW * epi_rows * (BN / WGN + 4) * 4;
+    constexpr int CHX = BK / 16, RPPX = NW * 64 / CHX;          // rows per load pass, as in the kernel
+    constexpr int stage_rows = ((BM + RPPX - 1) / RPPX + (BN + RPPX - 1) / RPPX) * RPPX;
+    constexpr int main_bytes = NS * stage_rows * BK, epi_bytes = NW * epi_rows * (BN / WGN + 4) * 4;
     constexpr int lds_bytes = main_bytes > epi_bytes ? main_bytes : epi_bytes;
     static std::atomic<bool> attr_done{false};     // (setting the attribute twice from two threads is harmless)
-    void (*kern)(IgemmParams) = igemm_kernel<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>;
-    if constexpr (D == 2) kern = igemm_lr_kernel<BM, BN, WGM, WGN, BK, D, UNI, MODE, EPI>;
+    void (*kern)(IgemmParams);
+    if constexpr (BK == 128) kern = igemm_wide_kernel<BM, BN, WGM, WGN, BK, NS, UNI, MODE, EPI>;
+    else kern = igemm_kernel<BM, BN, WGM, WGN, BK, NS, UNI, MODE, EPI>;
     if (lds_bytes > 48 * 1024 && !attr_done.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
             return EOQ_ERR_HIP;
         attr_done.store(true, std::memory_order_release);
     }
     long tiles = (long)((p.M + BM - 1) / BM) * ((p.NOUT + BN - 1) / BN);
+#ifdef EOQ_TUNE
+    IgemmParams pt = p;
+    pt.abl = tune_env("EOQ_ABL");
+    pt.dbg = g_tune_dbg ? g_tune_dbg + (size_t)(g_tune_launch++) * 4 * 8192 : nullptr;
+    const IgemmParams &pl = pt;
+#else
+    const IgemmParams &pl = p;
+#endif
     if (p.ncls) {
-        IgemmParams q = p;
+        IgemmParams q = pl;
         tiles = 0;
         for (int i = 0; i < p.ncls; ++i) {
             q.cls[i].tile_base = (int)tiles;
@@ -1344,31 +1304,26 @@ int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
         EOQ_LAUNCH_CHECK();
         return EOQ_OK;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(NW * 64), lds_bytes, c->stream, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(NW * 64), lds_bytes, c->stream, pl);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }
 
-// longest reduction (in 16-byte chunks) that takes the low-register form (swept over the layers of ResNet-50 at
-// batch 128: the low-register form wins up to about 80 chunks and ties beyond)
-constexpr int LOWREG_MAX_NK16 = 80;
 // fewest 128 x 128 workgroups for which that tile is chosen over 128 x 64 (one per compute unit)
 constexpr long MIN_WGS_128 = 256;
+// 128-byte stages: input channels a multiple of 128, a reduction of at least this many 16-byte chunks, and at most
+// two 128 x 128 workgroups per compute unit
+constexpr int WIDE_MIN_NK16 = 64;
+constexpr long WIDE_MAX_WGS = 512;
 
-template <int BM, int BN, int WGM, int WGN, int BK, int MODE, int EPI>
-int launch_igemm(eoq_ctx *c, const IgemmParams &p)
+template <int BM, int BN, int WGM, int WGN, int MODE, int EPI>
+int launch_igemm(eoq_ctx *c, const IgemmParams &p, bool wide = false)
 {
-    if (p.c16 % (BK / 16) == 0) {
-        if constexpr (BK == 64 && WGM * WGN == 4 && (EPI == EPI_FWD || EPI == EPI_D16 || EPI == EPI_RELU_BWD || EPI == EPI_SPEC)) {
-            if (p.nk16 <= LOWREG_MAX_NK16)
-                return launch_igemm_u<BM, BN, WGM, WGN, BK, 2, true, MODE, EPI>(c, p);
-        }
-        return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, true, MODE, EPI>(c, p);
+    if constexpr (BM == 128 && BN == 128 && WGM == 2 && WGN == 2) {
+        if (wide) return launch_igemm_u<BM, BN, WGM, WGN, 128, 2, true, MODE, EPI>(c, p);
     }
-    if constexpr (BK == 64 && WGM * WGN == 4 && (EPI == EPI_FWD || EPI == EPI_D16 || EPI == EPI_RELU_BWD || EPI == EPI_SPEC)) {
-        if (p.nk16 <= LOWREG_MAX_NK16) return launch_igemm_u<BM, BN, WGM, WGN, BK, 2, false, MODE, EPI>(c, p);
-    }
-    return launch_igemm_u<BM, BN, WGM, WGN, BK, 4, false, MODE, EPI>(c, p);
+    if (p.c16 % 4 == 0) return launch_igemm_u<BM, BN, WGM, WGN, 64, 2, true, MODE, EPI>(c, p);
+    return launch_igemm_u<BM, BN, WGM, WGN, 64, 2, false, MODE, EPI>(c, p);
 }
 
 template <int MODE, int EPI>
@@ -1385,21 +1340,30 @@ int dispatch_igemm(eoq_ctx *c, const IgemmParams &p_in, int *bm_out = nullptr, i
     p.gemm = (p.R == 1 && p.S == 1 && p.stride == 1 && p.pad == 0 && p.pad_w_delta == 0 && !p.no_pad && p.P == p.H &&
               p.Q == p.W) ? 1 : 0;
     if (p.ncls) p.gemm = 0;            // the classes differ in their grids and taps
+    {
+        const Recip rq = make_recip((uint32_t)p.Q), rp = make_recip((uint32_t)p.P);
+        p.mulQ = rq.mul; p.shQ = rq.sh; p.mulP = rp.mul; p.shP = rp.sh;
+        for (int i = 0; i < p.ncls; ++i) {
+            const Recip cq = make_recip((uint32_t)p.cls[i].Q), cp = make_recip((uint32_t)p.cls[i].P);
+            p.cls[i].mulQ = cq.mul; p.cls[i].shQ = cq.sh; p.cls[i].mulP = cp.mul; p.cls[i].shP = cp.sh;
+        }
+    }
     const int nout = p.NOUT;
     auto wgs = [&](int bm, int bn) { return (long)((p.M + bm - 1) / bm) * ((nout + bn - 1) / bn); };
-    // Measured on MI355X: throughput is nearly flat in the tile shape and in the prefetch depth (4, 6, 8 stages),
-    // so small tiles win through occupancy and grid size; the 128x128 tile pays off only for wide outputs with
-    // enough workgroups to fill the chip.
-    if (nout <= 32) { chosen(128, 32); return launch_igemm<128, 32, 4, 1, 64, MODE, EPI>(c, p); }
+    // Measured on MI355X: throughput is nearly flat in the tile shape, so small tiles win through occupancy and grid
+    // size; the 128x128 tile pays off only for wide outputs with enough workgroups to fill the chip.
+    if (nout <= 32) { chosen(128, 32); return launch_igemm<128, 32, 4, 1, MODE, EPI>(c, p); }
     if (nout >= 128 && wgs(128, 128) >= MIN_WGS_128) {
         chosen(128, 128);
+        if (p.c16 % 8 == 0 && p.nk16 >= WIDE_MIN_NK16 && wgs(128, 128) <= WIDE_MAX_WGS && !p.ncls)
+            return launch_igemm<128, 128, 2, 2, MODE, EPI>(c, p, true);
         // The forward epilogue with int8 outputs stacks the four waves along M, so that a wave owns whole 128-byte
         // output rows and its stores fill cache lines (measured: 3-9 % on the wide 1x1 layers, a loss elsewhere).
-        if (EPI == EPI_FWD && p.ep.relu) return launch_igemm<128, 128, EPI == EPI_FWD ? 4 : 2, EPI == EPI_FWD ? 1 : 2, 64, MODE, EPI>(c, p);
-        return launch_igemm<128, 128, 2, 2, 64, MODE, EPI>(c, p);
+        if (EPI == EPI_FWD && p.ep.relu) return launch_igemm<128, 128, EPI == EPI_FWD ? 4 : 2, EPI == EPI_FWD ? 1 : 2, MODE, EPI>(c, p);
+        return launch_igemm<128, 128, 2, 2, MODE, EPI>(c, p);
     }
     chosen(128, 64);
-    return launch_igemm<128, 64, 2, 2, 64, MODE, EPI>(c, p);
+    return launch_igemm<128, 64, 2, 2, MODE, EPI>(c, p);
 }
 
 bool desc_ok(const eoq_conv_desc *d)
@@ -1422,6 +1386,10 @@ int fill_epi(const eoq_epilogue *e, EpiDev &o)
 }
 
 } // namespace
+
+#ifdef EOQ_TUNE
+extern "C" void eoq_tune_set_dbg(unsigned long long *buf) { g_tune_dbg = buf; g_tune_launch = 0; }
+#endif
 
 // padded reduction length of the explicit im2col path
 static inline int im2col_kp(const eoq_conv_desc *d) { return (int)round_up((size_t)d->R * d->S * d->C, 64); }
