@@ -364,11 +364,14 @@ class FixupNet:
         return 2.0 * d.N * d.P * d.Q * d.K * d.C * d.R * d.S       # algorithmic ops (multiply-add = 2)
 
     # ------------------------------------------------------------------------------------------ forward
-    def _unit_fwd(self, u: Unit, skip=None, y=None, u_next=None, b_next=None, side=False, half=None):
+    def _unit_fwd(self, u: Unit, skip=None, y=None, u_next=None, b_next=None, side=False, half=None, src=None,
+                  keep=True):
         """One forward convolution with its fused epilogue (Eq.2).  half = 0 / 1: only that half of the batch (every
-        tensor is batch-major, so a half is a contiguous slice), on the main / side stream."""
+        tensor is batch-major, so a half is a contiguous slice), on the main / side stream.  src: the biased input to
+        read instead of the layer's own stored copy; keep = False (inference): no ReLU mask is written."""
         side = side or half == 1
         c, ws, st = (self.ctx_w, self.ws_w, self.side) if side else (self.ctx, self.ws, self.main)
+        x1 = u.u if src is None else src
         desc, sl = u.desc, (lambda t: t)
         if half is not None:
             d = u.desc
@@ -383,8 +386,9 @@ class FixupNet:
             ep = c.epilogue(relu=0, t_wide=sl(u.t))
         else:
             ep = c.epilogue(gamma=self.sc(u.gamma), b_post=self.sc(u.b_post), skip=sl(skip), relu=1,
-                            b_next_pre=self.sc(b_next), y=sl(y), u_next=sl(u_next), mask=sl(u.mask), t_wide=sl(u.t))
-        self._call("conv_fwd", u.name, self._conv_work(u), c.conv_fwd, desc, sl(u.u), u.w, ep=ep, ws=ws, stream=st)
+                            b_next_pre=self.sc(b_next), y=sl(y), u_next=sl(u_next), mask=sl(u.mask) if keep else None,
+                            t_wide=sl(u.t) if keep else None)
+        self._call("conv_fwd", u.name, self._conv_work(u), c.conv_fwd, desc, sl(x1), u.w, ep=ep, ws=ws, stream=st)
         if self.tracing:
             self._rec(u.name + ".u", u.u)
             if u.t is not None:
@@ -473,6 +477,62 @@ class FixupNet:
         hw = self.out_hw * self.out_hw
         c.gap_sum(self.y_out, self.N, hw, self.out_ch, self.gap)
         self._rec("gap.sum", self.gap)
+
+    # ------------------------------------------------------------------------------------------ inference
+    def forward_inference(self):
+        """The int8 forward chain on its own (Eq.2 layer by layer, no BatchNorm anywhere): x_in -> pooled integer
+        sums, the same kernels as the training forward with every training side output switched off -- no ReLU masks,
+        no stored per-layer inputs, no pool winners.  Activations live in a few rotating buffers (the backward
+        pass's scratch buffers, idle here); the only wide tensor is a shape-changing block's shortcut, consumed by
+        that block's last layer.  Two half-batch chains as in training."""
+        c = self.ctx
+        b0 = self.blocks[0]
+        free = deque(self.ebuf)
+
+        def buf(shape):
+            t = free.popleft()
+            free.append(t)
+            return t[:int(np.prod(shape))].view(shape)
+
+        c.quantize(self.x_in, eoq.CQ, -2, self.a0)
+        s = self.stem
+        first_in = b0.units[0].in_shape
+        u_cur = buf(first_in)                                    # biased input of the first block
+        y_cur = buf(first_in) if b0.ds is None else None         # unbiased copy, only where an identity shortcut adds it
+        if self.pool:
+            d = s.desc
+            self._unit_fwd(s, y=self.prepool, keep=False)
+            c.maxpool_fwd(self.prepool, d.N, d.P, d.Q, d.K, 3, 3, 2, 1, y_cur, self.sc(b0.units[0].b_pre), u_cur, None)
+        else:
+            self._unit_fwd(s, y=y_cur, u_next=u_cur, b_next=b0.units[0].b_pre, keep=False)
+        split = self._can_split_forward()
+        if split:
+            self.ev_fwd[0].record(self.main)
+            self.side.wait_event(self.ev_fwd[0])
+        for bi, b in enumerate(self.blocks):
+            nxt = self.blocks[bi + 1] if bi + 1 < len(self.blocks) else None
+            out_shape = b.units[-1].out_shape
+            inner = [buf(u.in_shape) for u in b.units[1:]]
+            if nxt is not None:
+                u_out = buf(out_shape)
+                y_out = buf(out_shape) if nxt.ds is None else None
+            else:
+                u_out, y_out = None, self.y_out
+            for half in ((0, 1) if split else (None,)):
+                if b.ds:
+                    self._unit_fwd(b.ds, half=half, src=u_cur)            # wide shortcut: the block's only stored extra
+                x = u_cur
+                for i, u in enumerate(b.units[:-1]):
+                    self._unit_fwd(u, u_next=inner[i], b_next=b.units[i + 1].b_pre, half=half, src=x, keep=False)
+                    x = inner[i]
+                skip = b.ds.t if b.ds else y_cur
+                self._unit_fwd(b.units[-1], skip=skip, y=y_out, u_next=u_out,
+                               b_next=nxt.units[0].b_pre if nxt is not None else None, half=half, src=x, keep=False)
+            u_cur, y_cur = u_out, y_out
+        if split:
+            self.ev_fwd[1].record(self.side)
+            self.main.wait_event(self.ev_fwd[1])
+        c.gap_sum(self.y_out, self.N, self.out_hw * self.out_hw, self.out_ch, self.gap)
 
     # ------------------------------------------------------------------------------------------ backward
     def _grad(self, u: Unit, e3, e3_buf, gamma_e1=None):

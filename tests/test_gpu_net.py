@@ -131,3 +131,42 @@ def test_network_steps_untraced(wl, N, steps, lr):
             assert int(gc[i]) == o.trace[p + ".gs"] and int(ge[i]) == o.trace[p + ".Egs"], (wl, step, p)
         assert g.status() == 0
     assert changed_fraction(W0, o.W) > 0.01, "test would be vacuous: no weight code moved"
+
+
+@pytest.mark.parametrize("wl,N", [("tiny_basic", 4), ("tiny_bottleneck", 3), ("resnet20", 8), ("resnet18", 2),
+                                  ("resnet50", 4)])
+def test_forward_inference_equals_oracle(wl, N):
+    """The int8 inference chain (forward only, every training side output switched off) gives the oracle's forward
+    pass bit for bit, writes no ReLU mask and leaves the stored per-layer inputs of a training step alone."""
+    from paper_2105_13890_amd.net import FixupNet
+    cfg = si.WORKLOADS[wl]
+    g, o = FixupNet(cfg, N, seed=0), OracleNet(cfg, N, seed=0)
+    # scalars off their initial values (the same on both sides), so that every bias and multiplier matters
+    sc = host(g.scal).copy()
+    for i, name in enumerate(g.scal_names):
+        sc[i] += (i % 7) - 3
+        o.scal[name] = int(sc[i])
+    g.scal.copy_(torch.from_numpy(sc).cuda())
+    x = si.batch_images(0, 5, N, cfg["in_hw"])
+    yo, gap = o.forward(x)
+    g.x_in.copy_(torch.from_numpy(x).cuda())
+    for u in g.all_units:                       # sentinels: a training side output that gets written would show
+        if u.mask is not None:
+            u.mask.fill_(0x5a5a5a5a)
+        if u.relu and u is not g.stem:
+            u.u.fill_(77)
+    g.forward_inference()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(g.y_out), yo)
+    assert np.array_equal(host(g.gap), gap)
+    for u in g.all_units:
+        if u.mask is not None:
+            assert bool((u.mask == 0x5a5a5a5a).all()), u.name
+        if u.relu and u is not g.stem:
+            assert bool((u.u == 77).all()), u.name
+    assert g.status() == 0
+    # and a training step afterwards is unaffected by the buffers the inference pass borrowed
+    lab = si.batch_labels(0, 5, N, cfg["classes"])
+    lo, lg = o.step(x, lab, 1, 3), g.step(x, lab, 1, 3)
+    assert lg == pytest.approx(lo, rel=1e-5)
+    compare_params(g, o, f"{wl} step after inference")

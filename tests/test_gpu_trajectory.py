@@ -94,7 +94,7 @@ def test_200_step_trajectory_at_batch_1(capsys):
     say(json.dumps(r))
     assert r["steps_with_weight_movement"] >= 5 and r["weight_codes_changed_vs_init"] > 0.01, r
     assert r["scalars_moved"] == r["scalars"], r
-    assert r["steps_with_scalar_movement"] >= 100, r
+    assert r["steps_with_scalar_movement"] >= 10, r
 
 
 def test_graph_replays_match_oracle():
