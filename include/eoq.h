@@ -325,6 +325,29 @@ int eoq_update_scalars(eoq_ctx *ctx, int32_t *scalars, const eoq_scalar_grad *de
                        const int64_t *sums, const int32_t *exps, const int32_t *lr_slot,
                        int32_t *g_code_out, int32_t *g_exp_out);
 
+/* ---- optional stochastic rounding of the update: BEYOND the paper, never the default ---------------------------
+ * Eq.13 with round-to-nearest loses every update below half a code (the paper has no stochastic rounding; its
+ * deterministic rule is what eoq_update_int8 / eoq_grad_update / eoq_update_scalars implement).  The _sr forms replace
+ * the last rounding, d = R(u_code * 2^(Eu + 7)), by d = floor((u_code + r) / 2^s) for s = -(Eu + 7) > 0 with r uniform in
+ * [0, 2^s) -- unbiased, E[d] = u_code / 2^s; an exact left shift when s <= 0 -- and are otherwise identical.  r is the
+ * low s bits (s capped at 62) of a counter-based 64-bit hash, so that both the library and any checker can regenerate
+ * every element's draw:  z = seed * 0x9E3779B97F4A7C15 + tensor_id * 0xC2B2AE3D27D4EB4F + step * 0xA0761D6478BD642F
+ * + index * 0xD6E8FEB86659FD93 (mod 2^64), word = the splitmix64 finaliser of z (z ^= z >> 30; z *= 0xBF58476D1CE4E5B9;
+ * z ^= z >> 27; z *= 0x94D049BB133111EB; z ^= z >> 31); index = the element's linear index in K x R x S x C order (0 for a
+ * scalar).  sr_slot: device uint32[2] = {seed, step}, read at kernel time; eoq_sr_next_step adds one to the step (a
+ * kernel, so a captured training step advances its own counter on every replay).  tensor_id: any caller-chosen
+ * constant per tensor (tensor_ids: a device array with one id per eoq_scalar_grad descriptor). */
+int eoq_update_int8_sr(eoq_ctx *ctx, int8_t *w, size_t n, const int8_t *g, const int32_t *g_exp_slot,
+                       const int32_t *g_max_code, const int32_t *lr_slot, const uint32_t *sr_slot, uint32_t tensor_id);
+int eoq_grad_update_sr(eoq_ctx *ctx, const eoq_conv_desc *desc, const int32_t *acc, const int32_t *absmax_slot,
+                       const int32_t *exp_in, int32_t exp_in_off, const int32_t *lr_slot, int8_t *w, int8_t *wt,
+                       int8_t *g_out, int32_t *exp_out, int32_t *max_code_out, const uint32_t *sr_slot,
+                       uint32_t tensor_id);
+int eoq_update_scalars_sr(eoq_ctx *ctx, int32_t *scalars, const eoq_scalar_grad *descs, int32_t count,
+                          const int64_t *sums, const int32_t *exps, const int32_t *lr_slot, int32_t *g_code_out,
+                          int32_t *g_exp_out, const uint32_t *sr_slot, const uint32_t *tensor_ids);
+int eoq_sr_next_step(eoq_ctx *ctx, uint32_t *sr_slot);
+
 /* ---- pooling, head (outside the quantised arithmetic of Eq.2-13 but on the step's path) ----------
  * Max pool R x S / stride / pad on int8 codes; padding never wins; the winner of a window is its first
  * maximum in (r,s) scan order and arg[n,p,q,c] = r*S+s of the winner (arg may be NULL when no backward

@@ -10,6 +10,7 @@ name so that tests can compare them one by one.
 """
 from __future__ import annotations
 
+import zlib
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -41,8 +42,9 @@ class Block:
 
 
 class Net:
-    def __init__(self, cfg: dict, batch: int, seed: int = 0):
+    def __init__(self, cfg: dict, batch: int, seed: int = 0, sr_seed: int | None = None):
         self.cfg, self.N, self.seed = dict(cfg), batch, seed
+        self.sr_seed, self.sr_step = sr_seed, 0      # optional stochastic rounding of the update (beyond the paper)
         self.W: dict[str, np.ndarray] = {}       # int8 KRSC codes
         self.scal: dict[str, int] = {}           # bias / multiplier codes (grid 2^-7)
         self.trace: dict[str, object] = {}
@@ -225,14 +227,19 @@ class Net:
 
     # ------------------------------------------------------------------ update
     def apply_updates(self, grads, sums, lr_m, lr_j):
-        """Eq.13 on every parameter; all gradients were taken with the old parameters."""
+        """Eq.13 on every parameter; all gradients were taken with the old parameters.  With self.sr_seed set (not
+        the paper's method: see ops.sr_shift) the update is rounded stochastically; a tensor's id in the hash is the
+        CRC-32 of its name, the step counter advances once per call."""
         T = self.trace
+        sr = (lambda name: None) if self.sr_seed is None else \
+             (lambda name: (self.sr_seed, zlib.crc32(name.encode("utf-8")) & 0xFFFFFFFF, self.sr_step))
         for name, (g, Eg) in grads.items():
-            self.W[name] = ops.update_weights(self.W[name], g, Eg, lr_m, lr_j)
+            self.W[name] = ops.update_weights(self.W[name], g, Eg, lr_m, lr_j, sr(name))
         for name, terms in sums.items():
             gc, Eg = ops.scalar_gradient(terms)
             T[name + ".gs"], T[name + ".Egs"] = gc, Eg
-            self.scal[name] = ops.update_scalar(self.scal[name], gc, Eg, lr_m, lr_j)
+            self.scal[name] = ops.update_scalar(self.scal[name], gc, Eg, lr_m, lr_j, sr(name))
+        self.sr_step += 1
 
     # ------------------------------------------------------------------ whole steps
     def block_step(self, a, e0, E0, lr_m, lr_j):

@@ -207,22 +207,60 @@ def scalar_gradient(terms, max_gap: int = 24):
 # --------------------------------------------------------------------------
 # update (Eq.13) with lr = m * 2^-j
 # --------------------------------------------------------------------------
-def update_delta(g_codes, Eg: int, lr_m: int, lr_j: int) -> np.ndarray:
+# ---- optional stochastic rounding of the update (NOT in the paper; off unless asked for) --------------------
+# With round-to-nearest an update below half a code vanishes, so at small learning rates the 8-bit weights never
+# move.  The optional mode rounds u_code * 2^(Eu+7) to one of its two neighbours with probabilities proportional to
+# the distance from the other (unbiased): d = floor((u_code + r) / 2^s), r uniform in [0, 2^s), s = -(Eu + 7) > 0
+# (an exact left shift otherwise).  r is the low s bits (s capped at 62) of a counter-based 64-bit hash of
+# (seed, tensor id, step, element index), so that every element's draw can be regenerated on its own:
+#     z = seed*A + tensor*B + step*C + index*D  (mod 2^64),  word = finalise(z)   (the splitmix64 finaliser)
+SR_A, SR_B, SR_C, SR_D = 0x9E3779B97F4A7C15, 0xC2B2AE3D27D4EB4F, 0xA0761D6478BD642F, 0xD6E8FEB86659FD93
+_M64 = (1 << 64) - 1
+
+
+def sr_words(seed: int, tensor: int, step: int, n: int) -> np.ndarray:
+    """64-bit hash words for elements 0 .. n-1 of one tensor in one step (uint64)."""
+    base = (int(seed) * SR_A + int(tensor) * SR_B + int(step) * SR_C) & _M64
+    with np.errstate(over="ignore"):
+        z = np.arange(n, dtype=np.uint64) * np.uint64(SR_D) + np.uint64(base)
+        z ^= z >> np.uint64(30)
+        z *= np.uint64(0xBF58476D1CE4E5B9)
+        z ^= z >> np.uint64(27)
+        z *= np.uint64(0x94D049BB133111EB)
+        z ^= z >> np.uint64(31)
+    return z
+
+
+def sr_shift(v, s: int, words) -> np.ndarray:
+    """v * 2^-s rounded stochastically with the given hash words (one per element); exact left shift for s <= 0."""
+    v = np.asarray(v, dtype=np.int64)
+    if s <= 0:
+        return v * (np.int64(1) << np.int64(-s))
+    s = min(int(s), 62)
+    r = (np.asarray(words, dtype=np.uint64) & np.uint64((1 << s) - 1)).astype(np.int64)
+    return (v + r) >> np.int64(s)               # arithmetic shift = floor, also for negative sums
+
+
+def update_delta(g_codes, Eg: int, lr_m: int, lr_j: int, sr=None) -> np.ndarray:
     """Q_u(lr*g) re-expressed on the parameter grid 2^-7:
-    u = SQ(m*g * 2^(Eg-j)) -> (u_code, Eu); delta = R(u_code * 2^(Eu+7))."""
+    u = SQ(m*g * 2^(Eg-j)) -> (u_code, Eu); delta = R(u_code * 2^(Eu+7)).
+    sr = (seed, tensor id, step): the optional stochastic rounding above instead of R."""
     u, Eu = sq_int(np.asarray(g_codes, dtype=np.int64) * int(lr_m), Eg - int(lr_j))
-    return rne_shift(u, -(Eu + 7))
+    if sr is None:
+        return rne_shift(u, -(Eu + 7))
+    seed, tensor, step = sr
+    return sr_shift(u, -(Eu + 7), sr_words(seed, tensor, step, u.size).reshape(u.shape))
 
 
-def update_weights(W, g_codes, Eg, lr_m, lr_j) -> np.ndarray:
+def update_weights(W, g_codes, Eg, lr_m, lr_j, sr=None) -> np.ndarray:
     """W <- Q_w(W - Q_u(lr*g)) = clamp(W - delta, -127, 127) on int8 codes."""
-    d = update_delta(g_codes, Eg, lr_m, lr_j)
+    d = update_delta(g_codes, Eg, lr_m, lr_j, sr)
     return np.clip(W.astype(np.int64) - d, -CODE_MAX, CODE_MAX).astype(np.int8)
 
 
-def update_scalar(code: int, g_code: int, Eg: int, lr_m: int, lr_j: int) -> int:
+def update_scalar(code: int, g_code: int, Eg: int, lr_m: int, lr_j: int, sr=None) -> int:
     """Bias / multiplier codes use the unclamped basic quantiser (Eq.10)."""
-    d = update_delta(np.array([g_code]), Eg, lr_m, lr_j)
+    d = update_delta(np.array([g_code]), Eg, lr_m, lr_j, sr)
     new = int(code) - int(d[0])
     assert -2 ** 31 < new < 2 ** 31, "scalar code left the int32 range it is stored in"
     return new

@@ -452,6 +452,38 @@ struct UpdateRule {
     }
 };
 
+// ---- optional stochastic rounding of the update (not the paper's rule; selected by a non-NULL sr_slot) ----
+// d = floor((u_code + r) / 2^s) for s = -(Eu + 7) > 0, r = the low s bits (s capped at 62) of a 64-bit hash of
+// (seed, tensor id, step, element index); an exact left shift otherwise.  The hash is counter based, so any
+// element's draw can be regenerated on its own: z = seed*A + tensor*B + step*C + index*D (mod 2^64), then the
+// splitmix64 finaliser.
+constexpr uint64_t SR_A = 0x9E3779B97F4A7C15ull, SR_B = 0xC2B2AE3D27D4EB4Full, SR_C = 0xA0761D6478BD642Full,
+                   SR_D = 0xD6E8FEB86659FD93ull;
+
+__device__ __forceinline__ uint64_t sr_base(const uint32_t *sr_slot, uint32_t tensor)
+{
+    return (uint64_t)sr_slot[0] * SR_A + (uint64_t)tensor * SR_B + (uint64_t)sr_slot[1] * SR_C;
+}
+
+__device__ __forceinline__ uint64_t sr_word(uint64_t base, uint64_t index)
+{
+    uint64_t z = base + index * SR_D;
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+__device__ __forceinline__ int sr_delta(const UpdateRule &u, int g, uint64_t word)
+{
+    const int64_t c = sq_code((int64_t)u.m * g, u.r);
+    if (u.sh <= 0) return (int)(c << (-u.sh));
+    const int s = u.sh > 62 ? 62 : u.sh;
+    return (int)((c + (int64_t)(word & ((uint64_t(1) << s) - 1))) >> s);
+}
+
+__global__ void sr_next_step_kernel(uint32_t *sr_slot) { sr_slot[1] += 1u; }
+
 __device__ __forceinline__ bool make_update_rule(int max_code, int Eg, const int32_t *lr_slot, UpdateRule &u,
                                                  uint32_t *status)
 {
@@ -469,23 +501,31 @@ __device__ __forceinline__ bool make_update_rule(int max_code, int Eg, const int
 }
 
 __global__ void update_int8_kernel(int8_t *w, size_t n, const int8_t *g, const int32_t *g_exp, const int32_t *g_max,
-                                   const int32_t *lr_slot, uint32_t *status)
+                                   const int32_t *lr_slot, uint32_t *status, const uint32_t *sr_slot, uint32_t tensor)
 {
     UpdateRule u;
     if (!make_update_rule(*g_max, *g_exp, lr_slot, u, status)) return;
+    const uint64_t base = sr_slot ? sr_base(sr_slot, tensor) : 0;
     const size_t nv = n / 16;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (; i < nv; i += stride) {
         v4i wv = ((const v4i *)w)[i], gv = ((const v4i *)g)[i], o = {0, 0, 0, 0};
+        if (sr_slot) {
 #pragma unroll
-        for (int k = 0; k < 16; ++k)
-            set_byte(o, k, clamp_i(byte_at(wv, k) - u.delta(byte_at(gv, k)), -CODE_MAX, CODE_MAX));
+            for (int k = 0; k < 16; ++k)
+                set_byte(o, k, clamp_i(byte_at(wv, k) - sr_delta(u, byte_at(gv, k), sr_word(base, i * 16 + k)), -CODE_MAX, CODE_MAX));
+        } else {
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+                set_byte(o, k, clamp_i(byte_at(wv, k) - u.delta(byte_at(gv, k)), -CODE_MAX, CODE_MAX));
+        }
         ((v4i *)w)[i] = o;
     }
     if (blockIdx.x == 0 && threadIdx.x < (n & 15)) {
         size_t t = nv * 16 + threadIdx.x;
-        w[t] = (int8_t)clamp_i((int)w[t] - u.delta(g[t]), -CODE_MAX, CODE_MAX);
+        const int d = sr_slot ? sr_delta(u, g[t], sr_word(base, t)) : u.delta(g[t]);
+        w[t] = (int8_t)clamp_i((int)w[t] - d, -CODE_MAX, CODE_MAX);
     }
 }
 
@@ -500,12 +540,16 @@ struct GradUpdate {
     uint32_t *status;
     int K, RS, C;
     size_t n;
+    const uint32_t *sr_slot;   // non-NULL: stochastic rounding of the update
+    uint32_t tensor;
 };
 
 struct GradRule {
     int r;            // Q_g shift exponent
     bool live;        // a non-zero gradient exists
     UpdateRule u;
+    bool sr;
+    uint64_t sr_base;
 };
 
 __device__ __forceinline__ GradRule make_grad_rule(const GradUpdate &p, bool writer)
@@ -521,15 +565,26 @@ __device__ __forceinline__ GradRule make_grad_rule(const GradUpdate &p, bool wri
         if (p.max_code_out) *p.max_code_out = gmax;
     }
     gr.live = make_update_rule(gmax, Eg, p.lr, gr.u, p.status);
+    gr.sr = p.sr_slot != nullptr;
+    gr.sr_base = gr.sr ? sr_base(p.sr_slot, p.tensor) : 0;
     return gr;
 }
 
-// 16 consecutive elements: codes of the gradient, new weights
-__device__ __forceinline__ void grad_update16(const GradRule &gr, const v4i a[4], v4i wv, v4i &gv, v4i &ov)
+// 16 consecutive elements (the first has linear index i0 in K x R x S x C order): codes of the gradient, new weights
+__device__ __forceinline__ void grad_update16(const GradRule &gr, const v4i a[4], v4i wv, v4i &gv, v4i &ov, size_t i0)
 {
     gv = v4i{0, 0, 0, 0};
     ov = wv;
     if (!gr.live) return;
+    if (gr.sr) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const int g = sq_code((int64_t)a[k >> 2][k & 3], gr.r);
+            set_byte(gv, k, g);
+            set_byte(ov, k, clamp_i(byte_at(wv, k) - sr_delta(gr.u, g, sr_word(gr.sr_base, i0 + k)), -CODE_MAX, CODE_MAX));
+        }
+        return;
+    }
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
         const int g = sq_code((int64_t)a[k >> 2][k & 3], gr.r);
@@ -547,14 +602,15 @@ __global__ void grad_update_flat_kernel(GradUpdate p)
         v4i a[4], gv, ov;
 #pragma unroll
         for (int k = 0; k < 4; ++k) a[k] = ((const v4i *)p.acc)[i * 4 + k];
-        grad_update16(gr, a, ((const v4i *)p.w)[i], gv, ov);
+        grad_update16(gr, a, ((const v4i *)p.w)[i], gv, ov, i * 16);
         ((v4i *)p.w)[i] = ov;
         if (p.g_out) ((v4i *)p.g_out)[i] = gv;
     }
     if (blockIdx.x == 0 && threadIdx.x < (p.n & 15)) {
         const size_t t = nv * 16 + threadIdx.x;
         const int g = gr.live ? sq_code((int64_t)p.acc[t], gr.r) : 0;
-        if (gr.live) p.w[t] = (int8_t)clamp_i((int)p.w[t] - gr.u.delta(g), -CODE_MAX, CODE_MAX);
+        const int d = !gr.live ? 0 : (gr.sr ? sr_delta(gr.u, g, sr_word(gr.sr_base, t)) : gr.u.delta(g));
+        if (gr.live) p.w[t] = (int8_t)clamp_i((int)p.w[t] - d, -CODE_MAX, CODE_MAX);
         if (p.g_out) p.g_out[t] = (int8_t)g;
     }
 }
@@ -580,7 +636,7 @@ __global__ void __launch_bounds__(256) grad_update_tiled_kernel(GradUpdate p)
         v4i a[4], gv, ov;
 #pragma unroll
         for (int q = 0; q < 4; ++q) a[q] = ((const v4i *)p.acc)[i * 4 + q];
-        grad_update16(gr, a, ((const v4i *)p.w)[i], gv, ov);
+        grad_update16(gr, a, ((const v4i *)p.w)[i], gv, ov, i * 16);
         ((v4i *)p.w)[i] = ov;
         if (p.g_out) ((v4i *)p.g_out)[i] = gv;
 #pragma unroll
@@ -595,7 +651,8 @@ __global__ void __launch_bounds__(256) grad_update_tiled_kernel(GradUpdate p)
 
 __global__ void update_scalars_kernel(int32_t *scalars, const eoq_scalar_grad *descs, int count, const int64_t *sums,
                                       const int32_t *exps, const int32_t *lr_slot, int32_t *g_code_out,
-                                      int32_t *g_exp_out, uint32_t *status)
+                                      int32_t *g_exp_out, uint32_t *status, const uint32_t *sr_slot,
+                                      const uint32_t *tensor_ids)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= count) return;
@@ -629,7 +686,8 @@ __global__ void update_scalars_kernel(int32_t *scalars, const eoq_scalar_grad *d
     // Q_u and the unclamped update (Eq.13, Eq.10)
     UpdateRule u;
     int a = gc < 0 ? -gc : gc;
-    if (make_update_rule(a, Eg, lr_slot, u, status)) scalars[d.param] -= u.delta(gc);
+    if (make_update_rule(a, Eg, lr_slot, u, status))
+        scalars[d.param] -= sr_slot ? sr_delta(u, gc, sr_word(sr_base(sr_slot, tensor_ids[i]), 0)) : u.delta(gc);
 }
 
 } // namespace
@@ -748,8 +806,8 @@ extern "C" int eoq_requant_epilogue(eoq_ctx *c, const eoq_requant_args *a)
     return EOQ_OK;
 }
 
-extern "C" int eoq_update_int8(eoq_ctx *c, int8_t *w, size_t n, const int8_t *g, const int32_t *g_exp_slot,
-                               const int32_t *g_max_code, const int32_t *lr_slot)
+static int update_int8_impl(eoq_ctx *c, int8_t *w, size_t n, const int8_t *g, const int32_t *g_exp_slot,
+                            const int32_t *g_max_code, const int32_t *lr_slot, const uint32_t *sr_slot, uint32_t tensor)
 {
     if (!c || !g_exp_slot || !lr_slot || (n && (!w || !g)) || !aligned16(w) || !aligned16(g)) return EOQ_ERR_ARG;
     if (!n) return EOQ_OK;
@@ -761,14 +819,37 @@ extern "C" int eoq_update_int8(eoq_ctx *c, int8_t *w, size_t n, const int8_t *g,
         g_max_code = slot;
     }
     hipLaunchKernelGGL(update_int8_kernel, grid, block, 0, c->stream, w, n, g, g_exp_slot, g_max_code, lr_slot,
-                       c->d_status);
+                       c->d_status, sr_slot, tensor);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }
 
-extern "C" int eoq_grad_update(eoq_ctx *c, const eoq_conv_desc *d, const int32_t *acc, const int32_t *absmax_slot,
-                               const int32_t *exp_in, int32_t exp_in_off, const int32_t *lr_slot, int8_t *w, int8_t *wt,
-                               int8_t *g_out, int32_t *exp_out, int32_t *max_code_out)
+extern "C" int eoq_update_int8(eoq_ctx *c, int8_t *w, size_t n, const int8_t *g, const int32_t *g_exp_slot,
+                               const int32_t *g_max_code, const int32_t *lr_slot)
+{
+    return update_int8_impl(c, w, n, g, g_exp_slot, g_max_code, lr_slot, nullptr, 0);
+}
+
+extern "C" int eoq_update_int8_sr(eoq_ctx *c, int8_t *w, size_t n, const int8_t *g, const int32_t *g_exp_slot,
+                                  const int32_t *g_max_code, const int32_t *lr_slot, const uint32_t *sr_slot,
+                                  uint32_t tensor_id)
+{
+    if (!sr_slot) return EOQ_ERR_ARG;
+    return update_int8_impl(c, w, n, g, g_exp_slot, g_max_code, lr_slot, sr_slot, tensor_id);
+}
+
+extern "C" int eoq_sr_next_step(eoq_ctx *c, uint32_t *sr_slot)
+{
+    if (!c || !sr_slot) return EOQ_ERR_ARG;
+    hipLaunchKernelGGL(sr_next_step_kernel, dim3(1), dim3(1), 0, c->stream, sr_slot);
+    EOQ_LAUNCH_CHECK();
+    return EOQ_OK;
+}
+
+static int grad_update_impl(eoq_ctx *c, const eoq_conv_desc *d, const int32_t *acc, const int32_t *absmax_slot,
+                            const int32_t *exp_in, int32_t exp_in_off, const int32_t *lr_slot, int8_t *w, int8_t *wt,
+                            int8_t *g_out, int32_t *exp_out, int32_t *max_code_out, const uint32_t *sr_slot,
+                            uint32_t tensor)
 {
     if (!c || !d || !acc || !absmax_slot || !exp_in || !lr_slot || !w) return EOQ_ERR_ARG;
     if (d->K <= 0 || d->R <= 0 || d->S <= 0 || d->C <= 0) return EOQ_ERR_SHAPE;
@@ -778,6 +859,7 @@ extern "C" int eoq_grad_update(eoq_ctx *c, const eoq_conv_desc *d, const int32_t
     p.w = w; p.wt = wt; p.g_out = g_out; p.exp_out = exp_out; p.max_code_out = max_code_out; p.status = c->d_status;
     p.K = d->K; p.RS = d->R * d->S; p.C = d->C;
     p.n = (size_t)d->K * p.RS * d->C;
+    p.sr_slot = sr_slot; p.tensor = tensor;
     if (wt) {
         if (d->K % 16 || d->C % 16) return EOQ_ERR_SHAPE;
         const size_t tiles = (size_t)((d->K + 63) / 64) * p.RS * ((d->C + 63) / 64);
@@ -790,14 +872,48 @@ extern "C" int eoq_grad_update(eoq_ctx *c, const eoq_conv_desc *d, const int32_t
     return EOQ_OK;
 }
 
-extern "C" int eoq_update_scalars(eoq_ctx *c, int32_t *scalars, const eoq_scalar_grad *descs, int32_t count,
-                                  const int64_t *sums, const int32_t *exps, const int32_t *lr_slot,
-                                  int32_t *g_code_out, int32_t *g_exp_out)
+extern "C" int eoq_grad_update(eoq_ctx *c, const eoq_conv_desc *d, const int32_t *acc, const int32_t *absmax_slot,
+                               const int32_t *exp_in, int32_t exp_in_off, const int32_t *lr_slot, int8_t *w, int8_t *wt,
+                               int8_t *g_out, int32_t *exp_out, int32_t *max_code_out)
+{
+    return grad_update_impl(c, d, acc, absmax_slot, exp_in, exp_in_off, lr_slot, w, wt, g_out, exp_out, max_code_out,
+                            nullptr, 0);
+}
+
+extern "C" int eoq_grad_update_sr(eoq_ctx *c, const eoq_conv_desc *d, const int32_t *acc, const int32_t *absmax_slot,
+                                  const int32_t *exp_in, int32_t exp_in_off, const int32_t *lr_slot, int8_t *w,
+                                  int8_t *wt, int8_t *g_out, int32_t *exp_out, int32_t *max_code_out,
+                                  const uint32_t *sr_slot, uint32_t tensor_id)
+{
+    if (!sr_slot) return EOQ_ERR_ARG;
+    return grad_update_impl(c, d, acc, absmax_slot, exp_in, exp_in_off, lr_slot, w, wt, g_out, exp_out, max_code_out,
+                            sr_slot, tensor_id);
+}
+
+static int update_scalars_impl(eoq_ctx *c, int32_t *scalars, const eoq_scalar_grad *descs, int32_t count,
+                               const int64_t *sums, const int32_t *exps, const int32_t *lr_slot, int32_t *g_code_out,
+                               int32_t *g_exp_out, const uint32_t *sr_slot, const uint32_t *tensor_ids)
 {
     if (!c || count < 0 || (count && (!scalars || !descs || !sums || !exps)) || !lr_slot) return EOQ_ERR_ARG;
     if (!count) return EOQ_OK;
     hipLaunchKernelGGL(update_scalars_kernel, dim3((count + 63) / 64), dim3(64), 0, c->stream, scalars, descs, count,
-                       sums, exps, lr_slot, g_code_out, g_exp_out, c->d_status);
+                       sums, exps, lr_slot, g_code_out, g_exp_out, c->d_status, sr_slot, tensor_ids);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
+}
+
+extern "C" int eoq_update_scalars(eoq_ctx *c, int32_t *scalars, const eoq_scalar_grad *descs, int32_t count,
+                                  const int64_t *sums, const int32_t *exps, const int32_t *lr_slot,
+                                  int32_t *g_code_out, int32_t *g_exp_out)
+{
+    return update_scalars_impl(c, scalars, descs, count, sums, exps, lr_slot, g_code_out, g_exp_out, nullptr, nullptr);
+}
+
+extern "C" int eoq_update_scalars_sr(eoq_ctx *c, int32_t *scalars, const eoq_scalar_grad *descs, int32_t count,
+                                     const int64_t *sums, const int32_t *exps, const int32_t *lr_slot,
+                                     int32_t *g_code_out, int32_t *g_exp_out, const uint32_t *sr_slot,
+                                     const uint32_t *tensor_ids)
+{
+    if (!sr_slot || (count && !tensor_ids)) return EOQ_ERR_ARG;
+    return update_scalars_impl(c, scalars, descs, count, sums, exps, lr_slot, g_code_out, g_exp_out, sr_slot, tensor_ids);
 }

@@ -23,6 +23,7 @@ EXPORTS = [
     "eoq_reduce_sum_i64",
     "eoq_quantize", "eoq_pre_bias", "eoq_conv_fwd", "eoq_conv_bwd_data", "eoq_conv_bwd_data_sq", "eoq_transpose_filters", "eoq_conv_bwd_weight", "eoq_conv_bwd_weight_static",
     "eoq_relu_bwd", "eoq_relu_bwd_recompute", "eoq_merge_absmax", "eoq_requant_epilogue", "eoq_update_int8", "eoq_grad_update", "eoq_update_scalars",
+    "eoq_update_int8_sr", "eoq_grad_update_sr", "eoq_update_scalars_sr", "eoq_sr_next_step",
     "eoq_maxpool_fwd", "eoq_maxpool_bwd", "eoq_maxpool_bwd_sq", "eoq_gap_sum", "eoq_broadcast_hw", "eoq_head_workspace_bytes",
     "eoq_head_fwd_bwd",
 ]
@@ -96,6 +97,11 @@ def _load():
     lib.eoq_update_int8.argtypes = [vp, vp, sz, vp, vp, vp, vp]
     lib.eoq_grad_update.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.eoq_update_scalars.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp]
+    u32 = C.c_uint32
+    lib.eoq_update_int8_sr.argtypes = [vp, vp, sz, vp, vp, vp, vp, vp, u32]
+    lib.eoq_grad_update_sr.argtypes = [vp, C.POINTER(ConvDesc), vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, u32]
+    lib.eoq_update_scalars_sr.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.eoq_sr_next_step.argtypes = [vp, vp]
     lib.eoq_maxpool_fwd.argtypes = [vp, vp] + [i32] * 8 + [vp, vp, vp, vp]
     lib.eoq_maxpool_bwd.argtypes = [vp, vp, vp] + [i32] * 8 + [vp, vp]
     lib.eoq_maxpool_bwd_sq.argtypes = [vp, vp, vp] + [i32] * 8 + [vp, vp, vp, vp, vp, vp, vp]
@@ -241,17 +247,35 @@ class Context:
                         _ptr(absmax_masked))
         _check(_lib.eoq_requant_epilogue(self._h, C.byref(a)), "eoq_requant_epilogue")
 
-    def update_int8(self, w, g, g_exp_slot, g_max_code, lr_slot):
+    def update_int8(self, w, g, g_exp_slot, g_max_code, lr_slot, sr_slot=None, tensor_id=0):
+        if sr_slot is not None:
+            _check(_lib.eoq_update_int8_sr(self._h, _ptr(w), w.numel(), _ptr(g), _ptr(g_exp_slot), _ptr(g_max_code),
+                                           _ptr(lr_slot), _ptr(sr_slot), tensor_id), "eoq_update_int8_sr")
+            return
         _check(_lib.eoq_update_int8(self._h, _ptr(w), w.numel(), _ptr(g), _ptr(g_exp_slot), _ptr(g_max_code),
                                     _ptr(lr_slot)), "eoq_update_int8")
 
+    def sr_next_step(self, sr_slot):
+        _check(_lib.eoq_sr_next_step(self._h, _ptr(sr_slot)), "eoq_sr_next_step")
+
     def grad_update(self, desc, acc, absmax_slot, exp_in, exp_in_off, lr_slot, w, wt=None, g_out=None, exp_out=None,
-                    max_code_out=None):
+                    max_code_out=None, sr_slot=None, tensor_id=0):
+        if sr_slot is not None:
+            _check(_lib.eoq_grad_update_sr(self._h, C.byref(desc), _ptr(acc), _ptr(absmax_slot), _ptr(exp_in), exp_in_off,
+                                           _ptr(lr_slot), _ptr(w), _ptr(wt), _ptr(g_out), _ptr(exp_out),
+                                           _ptr(max_code_out), _ptr(sr_slot), tensor_id), "eoq_grad_update_sr")
+            return
         _check(_lib.eoq_grad_update(self._h, C.byref(desc), _ptr(acc), _ptr(absmax_slot), _ptr(exp_in), exp_in_off,
                                     _ptr(lr_slot), _ptr(w), _ptr(wt), _ptr(g_out), _ptr(exp_out), _ptr(max_code_out)),
                "eoq_grad_update")
 
-    def update_scalars(self, scalars, descs, count, sums, exps, lr_slot, g_code_out=None, g_exp_out=None):
+    def update_scalars(self, scalars, descs, count, sums, exps, lr_slot, g_code_out=None, g_exp_out=None,
+                       sr_slot=None, tensor_ids=None):
+        if sr_slot is not None:
+            _check(_lib.eoq_update_scalars_sr(self._h, _ptr(scalars), _ptr(descs), count, _ptr(sums), _ptr(exps),
+                                              _ptr(lr_slot), _ptr(g_code_out), _ptr(g_exp_out), _ptr(sr_slot),
+                                              _ptr(tensor_ids)), "eoq_update_scalars_sr")
+            return
         _check(_lib.eoq_update_scalars(self._h, _ptr(scalars), _ptr(descs), count, _ptr(sums), _ptr(exps),
                                        _ptr(lr_slot), _ptr(g_code_out), _ptr(g_exp_out)), "eoq_update_scalars")
 

@@ -18,6 +18,7 @@ before that read has finished.  The two chains share no scratch memory.
 """
 from __future__ import annotations
 
+import zlib
 from collections import deque
 from dataclasses import dataclass, field
 
@@ -81,10 +82,11 @@ class FixupNet:
     N_EBUF = 6     # rotating error buffers (at least 5: e1, e3, e4 of a layer, the shortcut error, the other merge input)
 
     def __init__(self, cfg: dict, batch: int, seed: int = 0, trace: bool = False, overlap: bool = True,
-                 weights: dict | None = None, classifier=None):
+                 weights: dict | None = None, classifier=None, sr_seed: int | None = None):
         """weights: {layer name: int8 K x R x S x C codes} and classifier = (W fp64 [classes x features], b fp64):
         the initial parameters as input data.  Left out, they are drawn by fixup_init from `seed` and coded with
-        Q_w by the library."""
+        Q_w by the library.  sr_seed: switch the update to the library's optional stochastic rounding (not the
+        paper's rule; off by default), with this seed."""
         assert torch.cuda.is_available(), "libeoq needs the GPU; there is no CPU path"
         self.cfg, self.N, self.seed, self.tracing = dict(cfg), batch, seed, trace
         self.dev = torch.device("cuda")
@@ -234,6 +236,12 @@ class FixupNet:
         self.sums64 = torch.zeros((len(self.sl.names64) + 4,), dtype=torch.int64, device=self.dev)
         self.lr = torch.zeros((2,), dtype=torch.int32, device=self.dev)
         self.sgrad_tab = eoq.scalar_grad_table(self.sgrad_entries, self.dev)
+        # optional stochastic rounding: {seed, step} on the device; a tensor's id in the hash is the CRC-32 of its name
+        self.sr = None
+        if sr_seed is not None:
+            self.sr = torch.tensor([sr_seed & 0xFFFFFFFF, 0], dtype=torch.int64).to(torch.int32).to(self.dev)
+            ids = np.array([zlib.crc32(p.encode("utf-8")) & 0xFFFFFFFF for p in self.sgrad_params], dtype=np.uint32)
+            self.sr_scal_ids = torch.from_numpy(ids.view(np.int32).copy()).to(self.dev)
         self.g_code = i32((len(self.sgrad_entries) + 1,))
         self.g_exp = i32((len(self.sgrad_entries) + 1,))
         if self.classes:
@@ -587,7 +595,7 @@ class FixupNet:
             n = u.w.numel()
             self._call("hbm_grad_update", u.name, (4 + 1 + (2 if u.wt is not None else 1)) * float(n), c.grad_update, u.desc,
                        G, M_G, self.s32(u.E3), -7, self.lr, u.w, wt=u.wt, exp_out=Eg, max_code_out=gmax,
-                       stream=self.side if self.overlap else self.main)
+                       sr_slot=self.sr, tensor_id=self._tid(u.name), stream=self.side if self.overlap else self.main)
             return
         n = u.w.numel()
         g = self.gq[:n]
@@ -595,9 +603,13 @@ class FixupNet:
                            exp_out=Eg, max_code_out=gmax)
         self._rec(u.name + ".G", G.view(u.w.shape))
         self._rec(u.name + ".gw", g.view(u.w.shape))
-        c.update_int8(u.w, g, Eg, gmax, self.lr)
+        c.update_int8(u.w, g, Eg, gmax, self.lr, sr_slot=self.sr, tensor_id=self._tid(u.name))
         if u.wt is not None:
             c.transpose_filters(u.desc, u.w, u.wt)
+
+    @staticmethod
+    def _tid(name: str) -> int:
+        return zlib.crc32(name.encode("utf-8")) & 0xFFFFFFFF
 
     def _gamma_sum(self, u: Unit, e1, c, st):
         """Sum of e1 * x2 for the multiplier's gradient (Eq.4), with x2 recomputed from (u, w) instead of having
@@ -753,7 +765,8 @@ class FixupNet:
             self.main.wait_event(self._side_ev[self._last_gdone])       # the multiplier-gradient sums come from the side stream
             self._synced = self._last_gdone
         self.ctx.update_scalars(self.scal, self.sgrad_tab, len(self.sgrad_entries), self.sums64, self.slots32, self.lr,
-                                self.g_code, self.g_exp)
+                                self.g_code, self.g_exp, sr_slot=self.sr,
+                                tensor_ids=self.sr_scal_ids if self.sr is not None else None)
 
     def _join(self):
         """End of a step: everything the side stream did is ordered before what the main stream does next."""
@@ -793,6 +806,8 @@ class FixupNet:
         self._backward_stem(e, bufs)
         self._update_scalars()
         self._join()
+        if self.sr is not None:
+            self.ctx.sr_next_step(self.sr)          # behind every update of this step, on both streams
         if self.tracing:
             self._rec("slots32", self.slots32)
             self._rec("g_code", self.g_code)
@@ -842,6 +857,8 @@ class FixupNet:
         e = self._backward_blocks(e, bufs)
         self._update_scalars()
         self._join()
+        if self.sr is not None:
+            self.ctx.sr_next_step(self.sr)
         if self.tracing:
             self._rec("slots32", self.slots32)
             self._rec("g_code", self.g_code)

@@ -160,3 +160,41 @@ def test_head_against_float_reference():
     lib = ops.lib()
     for x in [0.0, -1e-9, -0.3, -1.0, -17.25, -300.0, -699.0]:
         assert lib.eo_head_exp(x) == pytest.approx(math.exp(x), rel=4e-16)
+
+
+def test_stochastic_rounding_of_the_update():
+    """The optional stochastic rounding (beyond the paper, off by default): hand cases with given hash words, the
+    two-neighbour bracket, exactness for left shifts, zero bias, and the generator against a scalar re-evaluation of its
+    definition."""
+    from oracle import ops as oo
+    # d = floor((v + r) / 2^s), r = word mod 2^s
+    assert oo.sr_shift(np.array([5, 5, -5, -5, 16, 0]), 3, np.array([2, 3, 2, 5, 7, 7])).tolist() == [0, 1, -1, 0, 2, 0]
+    assert oo.sr_shift(np.array([3, -3]), 0, np.array([99, 99])).tolist() == [3, -3]
+    assert oo.sr_shift(np.array([3, -3]), -4, np.array([99, 99])).tolist() == [48, -48]
+    # only the low s bits of the word count; a shift beyond 62 is capped
+    assert oo.sr_shift(np.array([5]), 3, np.array([2 + 8 * 12345], dtype=np.uint64)).tolist() == [0]
+    assert oo.sr_shift(np.array([127, -127]), 70, np.array([2 ** 62 - 1, 0], dtype=np.uint64)).tolist() == [1, -1]
+    # generator: one element re-evaluated with Python integers
+    seed, tensor, step, idx = 7, 0xDEADBEEF, 41, 1234567
+    M = (1 << 64) - 1
+    z = (seed * oo.SR_A + tensor * oo.SR_B + step * oo.SR_C + idx * oo.SR_D) & M
+    z ^= z >> 30; z = (z * 0xBF58476D1CE4E5B9) & M
+    z ^= z >> 27; z = (z * 0x94D049BB133111EB) & M
+    z ^= z >> 31
+    w = oo.sr_words(seed, tensor, step, idx + 1)
+    assert int(w[idx]) == z and len(set(w[:1000].tolist())) == 1000
+    # bracket and zero bias: v / 2^s lies between the two candidates, the mean over many draws approaches it
+    v = np.full(200000, 37, dtype=np.int64)
+    d = oo.sr_shift(v, 6, oo.sr_words(1, 2, 3, v.size))
+    assert set(d.tolist()) == {0, 1} and abs(d.mean() - 37 / 64) < 0.005
+    d = oo.sr_shift(-v, 6, oo.sr_words(1, 2, 4, v.size))
+    assert set(d.tolist()) == {-1, 0} and abs(d.mean() + 37 / 64) < 0.005
+    # whole update: deterministic rounding loses a sub-code update, the stochastic one keeps its mean
+    W = np.zeros(100000, dtype=np.int8)
+    g = np.full(100000, 100, dtype=np.int8)                 # the gradient 100 * 2^-17 is a tenth of a code
+    assert not oo.update_weights(W, g, -17, 1, 0).any()
+    Ws = oo.update_weights(W, g, -17, 1, 0, sr=(5, 6, 7))
+    from oracle.quant import sq_int
+    uc, Eu = sq_int(np.array([100]), -17)                  # Q_u: (100, -17) -> the update in codes is uc * 2^(Eu+7)
+    assert set(Ws.tolist()) == {-1, 0}
+    assert abs(-Ws.astype(np.float64).mean() - float(uc[0]) * 2.0 ** (Eu + 7)) < 0.01
