@@ -42,6 +42,28 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
+// ---- direct-to-LDS loads ----
+// 16 bytes per lane from a buffer straight into LDS (gfx950: buffer_load_dwordx4 ... lds): lane l of the wave writes
+// LDS bytes [lds_base + 16 l, lds_base + 16 l + 16) with whatever ITS offset addresses in memory (an in-bounds probe
+// confirmed the lane order, and that an out-of-range offset writes zeros).  lds_base is wave-uniform (it travels in
+// M0).  Issued through inline assembly on purpose: the compiler, when it knows of such a load, waits for ALL
+// outstanding memory operations before the next LDS read, which would drain the prefetch ring at every stage; here the
+// waits are written by hand (wait_vmcnt) next to the barriers that publish a stage.
+__device__ __forceinline__ void lds_direct_load16(const v4i &rsrc, uint32_t lds_base, int voffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(rsrc)
+                 : "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N));
+}
+
 // ---- rounding: v * 2^-s to nearest, ties to even (s >= 1); exact left shift for s <= 0 ----
 __device__ __forceinline__ int64_t rne_shift64(int64_t v, int s)
 {
@@ -221,6 +243,23 @@ __device__ __forceinline__ void merge_shifts(int Ea, int Eb, int &sa, int &sb, i
         sb = sb > 24 ? 24 : sb;
     }
 }
+
+// n / d for n < 2^31 through a host-made reciprocal: mul = ceil(2^(31+sh) / d), sh = ceil(log2 d).  (An integer
+// division costs about 40 instructions per lane on this chip; kernels whose set-up decomposes pixel indices take
+// the reciprocals of their divisors from the host instead.)
+struct Recip { uint32_t mul; int sh; };
+static inline Recip make_recip(uint32_t d)
+{
+    Recip r{0x80000000u, 0};
+    if (d <= 1) return r;
+    int s = 0;
+    while ((1ull << s) < d) ++s;
+    r.sh = s;
+    r.mul = (uint32_t)((((unsigned long long)1 << (31 + s)) + d - 1) / d);
+    return r;
+}
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t mul, int sh) { return __umulhi(n << 1, mul) >> sh; }
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const Recip &r) { return __umulhi(n << 1, r.mul) >> r.sh; }
 
 static inline int conv_out_dim(int in, int pad, int k, int st) { return (in + 2 * pad - k) / st + 1; }
 static inline int conv_out_dim_fwd(int in, int pad, int k, int st) { return (in + 2 * pad - k) / st + 1; }

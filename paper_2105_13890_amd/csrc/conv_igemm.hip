@@ -97,20 +97,6 @@ struct IgemmParams {
 #endif
 };
 
-// n / d for n < 2^31 through a host-made reciprocal: mul = ceil(2^(31+sh) / d), sh = ceil(log2 d)
-struct Recip { uint32_t mul; int sh; };
-static inline Recip make_recip(uint32_t d)
-{
-    Recip r{0x80000000u, 0};
-    if (d <= 1) return r;
-    int s = 0;
-    while ((1ull << s) < d) ++s;
-    r.sh = s;
-    r.mul = (uint32_t)((((unsigned long long)1 << (31 + s)) + d - 1) / d);
-    return r;
-}
-__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t mul, int sh) { return __umulhi(n << 1, mul) >> sh; }
-
 enum { MODE_FWD = 0, MODE_BWD_DATA = 1 };
 enum { EPI_FWD = 0, EPI_ACC = 1, EPI_SPEC = 3, EPI_RELU_BWD = 4, EPI_D16 = 5 };
 
@@ -137,27 +123,6 @@ __device__ __forceinline__ void set_byte(v4i &v, int i, int code)
 __device__ __forceinline__ int byte_at(const v4i &v, int i)
 {
     return (int)(int8_t)((uint32_t)v[i >> 2] >> (8 * (i & 3)));
-}
-
-// 16 bytes per lane from a buffer straight into LDS (gfx950: buffer_load_dwordx4 ... lds): lane l of the wave writes
-// LDS bytes [lds_base + 16 l, lds_base + 16 l + 16) with whatever ITS offset addresses in memory (an in-bounds probe
-// confirmed the lane order, and that an out-of-range offset writes zeros).  lds_base is wave-uniform (it travels in
-// M0).  Issued through inline assembly on purpose: the compiler, when it knows of such a load, waits for ALL
-// outstanding memory operations before the next LDS read, which would drain the prefetch ring at every stage; here the
-// waits are written by hand (wait_vmcnt) next to the barriers that publish a stage.
-__device__ __forceinline__ void lds_direct_load16(const v4i &rsrc, uint32_t lds_base, int voffset)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :
-                 : "s"(lds_base), "v"(voffset), "s"(rsrc)
-                 : "m0");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N));
 }
 
 // Forward epilogue for 16 consecutive channels of one pixel (Eq.2 x2..x5 and the next layer's x1).

@@ -33,12 +33,18 @@ struct WgradParams {
     int PH, PW;        // patch shape in staged input pixels
     int pstep;         // input pixels between staged patch pixels (stride for 1x1 filters, else 1)
     int tiles_p, tiles_q, nchunks, chunks_per_split;
+    Recip rPQ, rPW, rTQ, rTP;   // reciprocals of PQ, PW, tiles_q, tiles_p
+    int sdiv;                   // stride / pstep (patch pixels per output pixel step)
     int tap_groups;
     int32_t *part;     // [splits][K][RS][C]
     size_t part_stride;
     // few-channel input staged as zero-bordered 4-bytes-per-pixel image: the "channels" of the 1x1 problem are
     // the R*S4 sixteen-byte column groups of the filter window (pad4_S4 > 0 switches this addressing on)
     int pad4_S4, pad4_R, pad4_Wp, pad4_stride;
+#ifdef EOQ_TUNE
+    unsigned long long *dbg;   // tuning builds: four timestamps per workgroup (entry, set-up done, reduction done, exit)
+    int remap;
+#endif
 };
 
 __device__ __forceinline__ v2i lds_read_tr8(const int8_t *p)
@@ -46,7 +52,11 @@ __device__ __forceinline__ v2i lds_read_tr8(const int8_t *p)
     return __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3))) *)p);
 }
 
-template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL>
+// The chunks travel through a ring of NS LDS stages filled by direct-to-LDS loads (no staging registers, NS - 1 chunks
+// in flight).  Rows are stored unpadded, with the 16-byte chunk index XOR-swizzled by the row so that the eight rows a
+// transposing read touches spread over all banks; the swizzle is applied on the memory side (a lane asks for the
+// logical chunk that belongs in the slot it fills).
+template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL, int NS>
 __device__ __forceinline__ void wgrad_body(const WgradParams &p)
 {
     // Wave priority 3 for the kernels of the weight-gradient chain (this one, the reduction of its partial sums, the
@@ -54,16 +64,23 @@ __device__ __forceinline__ void wgrad_body(const WgradParams &p)
     // which spend their time waiting for memory; letting the matrix-bound waves issue first whenever both are ready
     // shortens the step by about 1 % (measured run against run on one machine; the opposite choice, priority for the
     // error chain's convolutions, costs 3 %).  It changes no result and means nothing when a kernel runs alone.
+#ifdef EOQ_TUNE
+    const unsigned long long ts0 = __builtin_amdgcn_s_memrealtime();
+#endif
     __builtin_amdgcn_s_setprio(3);
     static_assert(WK * WC == 4, "4 waves");
-    constexpr int KT = WK * TK * 32, CT = WC * TC * 32;
-    constexpr int E_LD = KT + 16, U_LD = CT + 16;            // padded LDS row strides (bytes)
+    static_assert(NS >= 2, "ring");
+    constexpr int KT = WK * TK * 32, CT = WC * TC * 32;      // tile = LDS row lengths (bytes)
+    static_assert((KT == 64 || KT == 128) && (CT == 64 || CT == 128), "swizzle periods");
+    // chunk-index swizzle of a row of RB bytes: eight consecutive rows cover a 128-byte bank line in eight distinct slots
+    auto swz_e = [](int row) { return KT == 128 ? (row & 7) : ((row >> 1) & 3); };
+    auto swz_u = [](int row) { return CT == 128 ? (row & 7) : ((row >> 1) & 3); };
     constexpr int E_CH = KT / 16, U_CH = CT / 16;            // 16-byte chunks per row
     constexpr int E_LOADS = (PIX * E_CH + 255) / 256;
     static_assert(PIX * E_CH % 256 == 0, "error tile loads divide evenly");
-    constexpr int E_BYTES = PIX * E_LD;
+    constexpr int E_BYTES = PIX * KT;
     constexpr int U_ROWS = U_LOADS * 256 / U_CH;             // patch pixels that fit
-    constexpr int U_BYTES = U_ROWS * U_LD;
+    constexpr int U_BYTES = U_ROWS * CT;
     constexpr int STAGE_BYTES = E_BYTES + U_BYTES;
     constexpr int OOB = 0x7fffff00;
 
@@ -72,7 +89,17 @@ __device__ __forceinline__ void wgrad_body(const WgradParams &p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wk = wave / WC, wc = wave % WC;
     const int tiles_k = (p.K + KT - 1) / KT, tiles_c = (p.C + CT - 1) / CT;
+    // Consecutive workgroup ids go round-robin over the 8 XCDs (each with its own L2).  Remapped so that an XCD works on
+    // a contiguous range of (pixel range, tile) pairs with the pixel range slowest: an XCD then pulls only its own one or
+    // two pixel ranges of both operands through its L2, instead of every XCD pulling nearly all of both.
     int bid = blockIdx.x;
+#ifdef EOQ_TUNE
+    if (p.remap)
+#endif
+    {
+        const int nb = gridDim.x, per = nb >> 3, rem = nb & 7, x = bid & 7;
+        bid = x * per + (x < rem ? x : rem) + (bid >> 3);
+    }
     const int tile_c = bid % tiles_c; bid /= tiles_c;
     const int tile_k = bid % tiles_k; bid /= tiles_k;
     const int tapg = bid % p.tap_groups;
@@ -81,33 +108,28 @@ __device__ __forceinline__ void wgrad_body(const WgradParams &p)
 
     // Out-of-range offsets make the buffer loads return zeros: padding pixels, pixel slots beyond the
     // chunk and channels beyond the tensor cost neither a branch nor a select.
-    const __amdgpu_buffer_rsrc_t rsrc_e =
-        __builtin_amdgcn_make_buffer_rsrc((void *)p.E, 0, p.N * p.P * p.Q * p.K, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rsrc_u =
-        __builtin_amdgcn_make_buffer_rsrc((void *)p.U, 0, p.pad4_S4 ? p.N * p.H * p.pad4_Wp * 4 : p.N * p.H * p.W * p.C,
-                                          0x00020000);
-
     // ---- loader state (fixed per thread): offsets relative to the chunk origin ----
-    int e_dp[E_LOADS], e_dq[E_LOADS], e_off[E_LOADS], e_dst[E_LOADS];
+    int e_dp[E_LOADS], e_dq[E_LOADS], e_off[E_LOADS];
 #pragma unroll
     for (int i = 0; i < E_LOADS; ++i) {
         const int idx = tid + 256 * i;
-        const int slot = idx / E_CH, col = idx % E_CH;
+        const int slot = idx / E_CH, col = (idx % E_CH) ^ swz_e(slot);
         const bool ok = slot < p.PR * p.PQ && (k0 + col * 16) < p.K;
-        e_dp[i] = ok ? slot / p.PQ : 1 << 20;               // an invalid slot never passes the row test
-        e_dq[i] = ok ? slot % p.PQ : 0;
+        const int sp = (int)fast_div((uint32_t)slot, p.rPQ);
+        e_dp[i] = ok ? sp : 1 << 20;                        // an invalid slot never passes the row test
+        e_dq[i] = ok ? slot - sp * p.PQ : 0;
         e_off[i] = ok ? (e_dp[i] * p.Q + e_dq[i]) * p.K + k0 + col * 16 : 0;
-        e_dst[i] = slot * E_LD + col * 16;
     }
-    int u_py[U_LOADS], u_px[U_LOADS], u_off[U_LOADS], u_dst[U_LOADS];
+    int u_py[U_LOADS], u_px[U_LOADS], u_off[U_LOADS];
     const int npatch = p.PH * p.PW;
 #pragma unroll
     for (int i = 0; i < U_LOADS; ++i) {
         const int idx = tid + 256 * i;
-        const int pix = idx / U_CH, col = idx % U_CH;
+        const int pix = idx / U_CH, col = (idx % U_CH) ^ swz_u(pix);
         const bool ok = pix < npatch && (c0 + col * 16) < p.C;
-        u_py[i] = ok ? (pix / p.PW) * p.pstep : 1 << 20;
-        u_px[i] = ok ? (pix % p.PW) * p.pstep : 0;
+        const int py = (int)fast_div((uint32_t)pix, p.rPW);
+        u_py[i] = ok ? py * p.pstep : 1 << 20;
+        u_px[i] = ok ? (pix - py * p.PW) * p.pstep : 0;
         if (p.pad4_S4) {
             // slot (py,px) of the chunk, column group cg = (filter row r, 4-column group j)
             const int cg = c0 / 16 + col, r = cg / p.pad4_S4, j = cg % p.pad4_S4;
@@ -115,28 +137,31 @@ __device__ __forceinline__ void wgrad_body(const WgradParams &p)
         } else {
             u_off[i] = ok ? (u_py[i] * p.W + u_px[i]) * p.C + c0 + col * 16 : 0;
         }
-        u_dst[i] = pix < U_ROWS ? E_BYTES + pix * U_LD + col * 16 : -1;
     }
 
     // ---- MFMA operand addressing (fixed per lane) ----
     const int g = lane >> 5, grp16 = (lane & 31) >> 4, L = lane & 15;
-    int a_off[4], b_off[4];                       // index jh = 2*j + h : reduction step j, 8-slot half h
+    // rows this lane reads: error slot and patch pixel, index jh = 2*j + h : reduction step j, 8-slot half h
+    int a_row[4], b_row[4];
 #pragma unroll
     for (int jh = 0; jh < 4; ++jh) {
         const int slot = (jh >> 1) * 32 + 16 * g + 8 * (jh & 1) + (L >> 1);
-        a_off[jh] = slot * E_LD + grp16 * 16 + 8 * (L & 1) + wk * TK * 32;
         int dp = 0, dq = 0;
-        if (slot < p.PR * p.PQ) { dp = slot / p.PQ; dq = slot % p.PQ; }
-        const int pix = ((dp * p.stride) / p.pstep) * p.PW + (dq * p.stride) / p.pstep;
-        b_off[jh] = E_BYTES + pix * U_LD + grp16 * 16 + 8 * (L & 1) + wc * TC * 32;
+        if (slot < p.PR * p.PQ) { dp = (int)fast_div((uint32_t)slot, p.rPQ); dq = slot - dp * p.PQ; }
+        a_row[jh] = slot;
+        b_row[jh] = dp * p.sdiv * p.PW + dq * p.sdiv;
     }
-    // LDS byte offset of each tap inside the patch (uniform)
+    // row offset of each tap inside the patch (uniform)
     int tap_off[TAPS];
 #pragma unroll
     for (int t = 0; t < TAPS; ++t) {
         const int tap = tap0 + t;
-        tap_off[t] = (p.RS == 1 || tap >= p.RS) ? 0 : ((tap / p.S) * p.PW + (tap % p.S)) * U_LD;
+        const int rows = (p.RS == 1 || tap >= p.RS) ? 0 : (tap / p.S) * p.PW + (tap % p.S);
+        tap_off[t] = rows;
     }
+    // byte address of this lane's half of (row, 16-byte chunk), swizzle applied
+    auto addr_e = [&](int row, int chunk) { return row * KT + ((chunk ^ swz_e(row)) << 4) + 8 * (L & 1); };
+    auto addr_u = [&](int row, int chunk) { return E_BYTES + row * CT + ((chunk ^ swz_u(row)) << 4) + 8 * (L & 1); };
 
     v16i acc[TK][TC][TAPS];
 #pragma unroll
@@ -154,48 +179,23 @@ __device__ __forceinline__ void wgrad_body(const WgradParams &p)
     const int nch = ch_end - ch_begin;
 
     // chunk being loaded: (image, chunk row, chunk column), advanced without divisions (all uniform)
-    int ld_q = ch_begin % p.tiles_q;
-    int ld_p = (ch_begin / p.tiles_q) % p.tiles_p, ld_n = ch_begin / (p.tiles_q * p.tiles_p);
+    const int cq = (int)fast_div((uint32_t)ch_begin, p.rTQ);
+    int ld_q = ch_begin - cq * p.tiles_q;
+    int ld_n = (int)fast_div((uint32_t)cq, p.rTP), ld_p = cq - ld_n * p.tiles_p;
 
     int ld_i = 0;                                  // chunks requested so far; past the range every load is out of range
-    auto load_chunk = [&](v4i (&re)[E_LOADS], v4i (&ru)[U_LOADS]) {
-        const bool live = ld_i < nch;
-        ++ld_i;
-        const int p0 = ld_p * p.PR, q0 = ld_q * p.PQ;
-        const int base_e = ((ld_n * p.P + p0) * p.Q + q0) * p.K;
-#pragma unroll
-        for (int i = 0; i < E_LOADS; ++i) {
-            const bool ok = live && p0 + e_dp[i] < p.P && q0 + e_dq[i] < p.Q;
-            const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_e, ok ? base_e + e_off[i] : OOB, 0, 0);
-            re[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
-        }
-        const int h0 = p0 * p.stride - p.pad, w0 = q0 * p.stride - p.pad;
-        const int base_u = p.pad4_S4 ? ((ld_n * p.H + p0 * p.pad4_stride) * p.pad4_Wp + q0 * p.pad4_stride) * 4
-                                     : ((ld_n * p.H + h0) * p.W + w0) * p.C;
-#pragma unroll
-        for (int i = 0; i < U_LOADS; ++i) {
-            const bool ok = live && (p.pad4_S4 ? (p0 + u_py[i] < p.P && q0 + u_px[i] < p.Q)
-                                               : ((unsigned)(h0 + u_py[i]) < (unsigned)p.H && (unsigned)(w0 + u_px[i]) < (unsigned)p.W));
-            const v4u x = __builtin_amdgcn_raw_buffer_load_b128(rsrc_u, ok ? base_u + u_off[i] : OOB, 0, 0);
-            ru[i] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
-        }
-        if (++ld_q == p.tiles_q) { ld_q = 0; if (++ld_p == p.tiles_p) { ld_p = 0; ++ld_n; } }
-    };
-    auto store_chunk = [&](int buf, const v4i (&re)[E_LOADS], const v4i (&ru)[U_LOADS]) {
-        int8_t *base = lds + buf;
-#pragma unroll
-        for (int i = 0; i < E_LOADS; ++i) *(v4i *)(base + e_dst[i]) = re[i];
-#pragma unroll
-        for (int i = 0; i < U_LOADS; ++i)
-            if (u_dst[i] >= 0) *(v4i *)(base + u_dst[i]) = ru[i];
-    };
+#ifdef EOQ_WABL
+    auto rd = [&](const int8_t *q) { return (EOQ_WABL & 2) ? v2i{lane + (int)(uintptr_t)q, tid} : lds_read_tr8(q); };
+#define lds_read_tr8 rd
+#endif
     auto compute_half = [&](int buf, int j) {      // one of the two 32-pixel reduction steps of a chunk
         const int8_t *base = lds + buf;
         v4i a[TK];
 #pragma unroll
         for (int tk = 0; tk < TK; ++tk) {
-            const v2i lo = lds_read_tr8(base + a_off[2 * j] + tk * 32);
-            const v2i hi = lds_read_tr8(base + a_off[2 * j + 1] + tk * 32);
+            const int ch = 2 * (wk * TK + tk) + grp16;
+            const v2i lo = lds_read_tr8(base + addr_e(a_row[2 * j], ch));
+            const v2i hi = lds_read_tr8(base + addr_e(a_row[2 * j + 1], ch));
             a[tk] = v4i{lo[0], lo[1], hi[0], hi[1]};
         }
 #pragma unroll
@@ -203,57 +203,82 @@ __device__ __forceinline__ void wgrad_body(const WgradParams &p)
             if (FULL || tap0 + t < p.RS) {
 #pragma unroll
                 for (int tc = 0; tc < TC; ++tc) {
-                    const v2i lo = lds_read_tr8(base + b_off[2 * j] + tap_off[t] + tc * 32);
-                    const v2i hi = lds_read_tr8(base + b_off[2 * j + 1] + tap_off[t] + tc * 32);
+                    const int ch = 2 * (wc * TC + tc) + grp16;
+                    const v2i lo = lds_read_tr8(base + addr_u(b_row[2 * j] + tap_off[t], ch));
+                    const v2i hi = lds_read_tr8(base + addr_u(b_row[2 * j + 1] + tap_off[t], ch));
                     const v4i b = v4i{lo[0], lo[1], hi[0], hi[1]};
 #pragma unroll
-                    for (int tk = 0; tk < TK; ++tk)
+                    for (int tk = 0; tk < TK; ++tk) {
+#ifdef EOQ_WABL
+                        if (EOQ_WABL & 4) { acc[tk][tc][t][0] += a[tk][0] ^ b[0]; acc[tk][tc][t][1] += a[tk][2] ^ b[3]; continue; }
+#endif
                         acc[tk][tc][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[tk], b, acc[tk][tc][t], 0, 0, 0);
+                    }
                 }
             }
         }
     };
+#ifdef EOQ_WABL
+#undef lds_read_tr8
+#endif
 
-    // Software pipeline over the pixel chunks with a ring of D register sets, unrolled D times so that the ring is
-    // indexed statically.  Entering step i: LDS buffer i%2 holds chunk i, the register sets hold chunks i+1 .. i+D-1
-    // (loaded or in flight).  The step requests chunk i+D, multiplies chunk i and moves chunk i+1 into the other LDS
-    // buffer.  Every load of a step is unconditional (past the range it is out of range: no traffic, zeros), so the
-    // number of loads in flight at the wait before the LDS stores is a compile-time constant and only the oldest
-    // set is waited for; the order of the phases is pinned with scheduling barriers.
-    constexpr int D = 2;
-    static_assert(D % 2 == 0, "buffer parity follows the chunk index");
-    v4i re[D][E_LOADS], ru[D][U_LOADS];
+#ifdef EOQ_TUNE
+    const unsigned long long ts1 = __builtin_amdgcn_s_memrealtime();
+#endif
+    {
+        // Iteration i: wait until this thread's loads of chunk i have landed | barrier | request chunk i+NS-1 into the
+        // buffer chunk i-1 was multiplied from | multiply chunk i.  Requests past the range are out of range (zeros, no
+        // traffic), so the number of loads in flight at the wait is a compile-time constant.
+        constexpr int L = E_LOADS + U_LOADS;
+        static_assert((NS - 1) * L < 64, "vmcnt range");
+        const uint32_t wave_base = (uint32_t)(uintptr_t)lds + (uint32_t)__builtin_amdgcn_readfirstlane(wave) * 1024u;
+        const uint64_t pe = (uint64_t)p.E, pu = (uint64_t)p.U;
+        const v4i rs_e = {(int)(uint32_t)pe, (int)((uint32_t)(pe >> 32) & 0xffffu), p.N * p.P * p.Q * p.K, 0x00020000};
+        const v4i rs_u = {(int)(uint32_t)pu, (int)((uint32_t)(pu >> 32) & 0xffffu),
+                          p.pad4_S4 ? p.N * p.H * p.pad4_Wp * 4 : p.N * p.H * p.W * p.C, 0x00020000};
+        auto dma_chunk = [&](int buf) {
+#ifdef EOQ_WABL       // timing experiments only (results are then wrong): 1 no loads, 2 no LDS reads, 4 no MFMA
+            if (EOQ_WABL & 1) return;
+#endif
+            const bool live = ld_i < nch;
+            ++ld_i;
+            const int p0 = ld_p * p.PR, q0 = ld_q * p.PQ;
+            const int base_e = ((ld_n * p.P + p0) * p.Q + q0) * p.K;
 #pragma unroll
-    for (int d = 0; d < D; ++d) load_chunk(re[d], ru[d]);
-    store_chunk(0, re[0], ru[0]);
-    __syncthreads();
-    int i = 0;
-    for (; i + D <= nch; i += D) {
+            for (int i = 0; i < E_LOADS; ++i) {
+                const bool ok = live && p0 + e_dp[i] < p.P && q0 + e_dq[i] < p.Q;
+                lds_direct_load16(rs_e, wave_base + buf + i * 4096, ok ? base_e + e_off[i] : OOB);
+            }
+            const int h0 = p0 * p.stride - p.pad, w0 = q0 * p.stride - p.pad;
+            const int base_u = p.pad4_S4 ? ((ld_n * p.H + p0 * p.pad4_stride) * p.pad4_Wp + q0 * p.pad4_stride) * 4
+                                         : ((ld_n * p.H + h0) * p.W + w0) * p.C;
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            const int buf = (d & 1) ? STAGE_BYTES : 0;
-            load_chunk(re[d], ru[d]);                                     // chunk i+d+D
-            __builtin_amdgcn_sched_barrier(0);
-            compute_half(buf, 0);                                         // chunk i+d
-            __builtin_amdgcn_sched_barrier(0);
-            store_chunk(STAGE_BYTES - buf, re[(d + 1) % D], ru[(d + 1) % D]);   // chunk i+d+1
-            __builtin_amdgcn_sched_barrier(0);
-            compute_half(buf, 1);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < U_LOADS; ++i) {
+                const bool ok = live && (p.pad4_S4 ? (p0 + u_py[i] < p.P && q0 + u_px[i] < p.Q)
+                                                   : ((unsigned)(h0 + u_py[i]) < (unsigned)p.H && (unsigned)(w0 + u_px[i]) < (unsigned)p.W));
+                lds_direct_load16(rs_u, wave_base + buf + E_BYTES + i * 4096, ok ? base_u + u_off[i] : OOB);
+            }
+            if (++ld_q == p.tiles_q) { ld_q = 0; if (++ld_p == p.tiles_p) { ld_p = 0; ++ld_n; } }
+        };
+#pragma unroll
+        for (int d = 0; d < NS - 1; ++d) dma_chunk(d * STAGE_BYTES);
+        int cur = 0;
+        for (int i = 0; i < nch; ++i) {
+            wait_vmcnt<(NS - 2) * L>();
             __syncthreads();
+            dma_chunk(cur == 0 ? (NS - 1) * STAGE_BYTES : cur - STAGE_BYTES);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_half(cur, 0);
+            compute_half(cur, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            cur = cur + STAGE_BYTES == NS * STAGE_BYTES ? 0 : cur + STAGE_BYTES;
         }
-    }
-#pragma unroll
-    for (int d = 0; d < D - 1; ++d) {
-        if (i + d < nch) {                                                // uniform
-            const int buf = (d & 1) ? STAGE_BYTES : 0;
-            compute_half(buf, 0);
-            store_chunk(STAGE_BYTES - buf, re[(d + 1) % D], ru[(d + 1) % D]);
-            compute_half(buf, 1);
-            __syncthreads();
-        }
+        wait_vmcnt<0>();          // the out-of-range requests behind the last chunk still write (zeros) to LDS
     }
 
+#ifdef EOQ_TUNE
+    const unsigned long long ts2 = __builtin_amdgcn_s_memrealtime();
+#endif
     // ---- write this range's partial sums: part[split][k][tap][c] ----
     int32_t *out = p.part + (size_t)split * p.part_stride;
     const int col = lane & 31;
@@ -274,27 +299,33 @@ __device__ __forceinline__ void wgrad_body(const WgradParams &p)
                 }
             }
         }
+#ifdef EOQ_TUNE
+    if (p.dbg && tid == 0) {
+        unsigned long long *r = p.dbg + 4 * (size_t)blockIdx.x;
+        r[0] = ts0; r[1] = ts1; r[2] = ts2; r[3] = __builtin_amdgcn_s_memrealtime();
+    }
+#endif
 }
 
-template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL>
+template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL, int NS>
 __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
 {
-    wgrad_body<WK, WC, TK, TC, TAPS, U_LOADS, FULL>(p);
+    wgrad_body<WK, WC, TK, TC, TAPS, U_LOADS, FULL, NS>(p);
 }
 
 // Occupancy decides more here than prefetch depth: with two stages of loads in flight instead of four, the single-tap
 // (1x1) kernels fit 152 registers (three workgroups per compute unit instead of two) and the nine-tap stride-1 kernel,
 // whose 9 x 16 accumulators alone take 144, fits 256 (two instead of one).
-template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL>
+template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL, int NS>
 __global__ __launch_bounds__(256, 2) void wgrad_occ2_kernel(WgradParams p)
 {
-    wgrad_body<WK, WC, TK, TC, TAPS, U_LOADS, FULL>(p);
+    wgrad_body<WK, WC, TK, TC, TAPS, U_LOADS, FULL, NS>(p);
 }
 
-template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL>
+template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL, int NS>
 __global__ __launch_bounds__(256, 3) void wgrad_occ3_kernel(WgradParams p)
 {
-    wgrad_body<WK, WC, TK, TC, TAPS, U_LOADS, FULL>(p);
+    wgrad_body<WK, WC, TK, TC, TAPS, U_LOADS, FULL, NS>(p);
 }
 
 // exact combination of the partial sums; int32 range check; abs-max for Q_g.
@@ -479,22 +510,36 @@ void pick_chunk(int P, int Q, int stride, int R, int S, int max_patch, int &PR, 
     PW = ((PQ - 1) * stride + S + pstep - 1) / pstep;
 }
 
-template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS>
+#ifdef EOQ_TUNE
+static unsigned long long *g_wtune_dbg = nullptr;
+static int g_wtune_launch = 0;
+#endif
+
+template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, int NS>
 int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int max_splits, int *splits_out)
 {
     constexpr int KT = WK * TK * 32, CT = WC * TC * 32;
     constexpr int U_ROWS = U_LOADS * 256 / (CT / 16);
-    constexpr int lds_bytes = 2 * (PIX * (KT + 16) + U_ROWS * (CT + 16));
+    constexpr int lds_bytes = NS * (PIX * KT + U_ROWS * CT);
     pick_chunk(p.P, p.Q, p.stride, p.R, p.S, U_ROWS, p.PR, p.PQ, p.PH, p.PW, p.pstep);
     if (p.PH * p.PW > U_ROWS) return EOQ_ERR_SHAPE;
     p.tiles_p = (p.P + p.PR - 1) / p.PR;
     p.tiles_q = (p.Q + p.PQ - 1) / p.PQ;
     p.nchunks = p.N * p.tiles_p * p.tiles_q;
+    p.rPQ = make_recip((uint32_t)p.PQ); p.rPW = make_recip((uint32_t)p.PW);
+    p.rTQ = make_recip((uint32_t)p.tiles_q); p.rTP = make_recip((uint32_t)p.tiles_p);
+    p.sdiv = p.stride / p.pstep;
     p.tap_groups = (RS + TAPS - 1) / TAPS;
     const int tiles = ((p.K + KT - 1) / KT) * ((p.C + CT - 1) / CT) * p.tap_groups;
     // workgroups aimed for when splitting the reduction: with three resident per compute unit and the error chain
     // sharing the chip, 448 measured better than 256 (by 2 % of a ResNet-50 step) and than 768
+#ifdef EOQ_TUNE
+    static const int target_wgs = getenv("EOQ_WTARGET") ? atoi(getenv("EOQ_WTARGET")) : 448;
+    static const int tune_remap = getenv("EOQ_WXCD") ? atoi(getenv("EOQ_WXCD")) : 1;
+    p.remap = tune_remap;
+#else
     constexpr int target_wgs = 448;
+#endif
     int splits = target_wgs / tiles;
     if (splits < 1) splits = 1;
     if (splits > max_splits) splits = max_splits;
@@ -506,14 +551,14 @@ int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int max_splits, int *splits_
     splits = (p.nchunks + p.chunks_per_split - 1) / p.chunks_per_split;
     if (splits > max_splits) return EOQ_ERR_WORKSPACE;     // the partial sums of the shortest legal ranges do not fit
     static std::atomic<bool> attr_done{false};
-    void (*kern_full)(WgradParams) = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true>;
-    void (*kern_part)(WgradParams) = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false>;
+    void (*kern_full)(WgradParams) = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true, NS>;
+    void (*kern_part)(WgradParams) = wgrad_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false, NS>;
     if constexpr (TAPS == 1) {
-        kern_full = wgrad_occ3_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true>;
-        kern_part = wgrad_occ3_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false>;
+        kern_full = wgrad_occ3_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true, NS>;
+        kern_part = wgrad_occ3_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false, NS>;
     } else if constexpr (U_LOADS == 2) {
-        kern_full = wgrad_occ2_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true>;
-        kern_part = wgrad_occ2_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false>;
+        kern_full = wgrad_occ2_kernel<WK, WC, TK, TC, TAPS, U_LOADS, true, NS>;
+        kern_part = wgrad_occ2_kernel<WK, WC, TK, TC, TAPS, U_LOADS, false, NS>;
     }
     if (lds_bytes > 48 * 1024 && !attr_done.load(std::memory_order_acquire)) {
         if (hipFuncSetAttribute((const void *)kern_full, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess ||
@@ -522,6 +567,9 @@ int launch_wgrad(eoq_ctx *c, WgradParams p, int RS, int max_splits, int *splits_
         attr_done.store(true, std::memory_order_release);
     }
     if ((size_t)p.N * p.P * p.Q * p.K > 0x7fffff00u || (size_t)p.N * p.H * p.W * p.C > 0x7fffff00u) return EOQ_ERR_SHAPE;
+#ifdef EOQ_TUNE
+    p.dbg = g_wtune_dbg ? g_wtune_dbg + (size_t)(g_wtune_launch++) * 4 * 8192 : nullptr;
+#endif
     hipLaunchKernelGGL(RS % TAPS == 0 ? kern_full : kern_part, dim3((unsigned)(tiles * splits)), dim3(256), lds_bytes,
                        c->stream, p);
     EOQ_LAUNCH_CHECK();
@@ -544,6 +592,10 @@ int wgrad_run(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *e, const int8_t 
               int32_t *absmax_slot, void *ws, size_t ws_bytes, bool caller_ws);
 
 } // namespace
+
+#ifdef EOQ_TUNE
+extern "C" void eoq_tune_set_wdbg(unsigned long long *buf) { g_wtune_dbg = buf; g_wtune_launch = 0; }
+#endif
 
 int wgrad_static_scratch_init(int device, void **ptr_out)
 {
@@ -665,11 +717,11 @@ int wgrad_run(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *e, const int8_t 
     if (p.part_stride != part_elems + WGRAD_PART_PAD) return EOQ_ERR_SHAPE;      // (cannot happen: same geometry)
     int splits = 0, rc;
     if (p.RS == 1) {
-        if (p.K >= 128) rc = launch_wgrad<2, 2, 2, 2, 1, 2>(c, p, p.RS, max_splits, &splits);
-        else rc = launch_wgrad<2, 2, 1, 2, 1, 2>(c, p, p.RS, max_splits, &splits);
+        if (p.K >= 128) rc = launch_wgrad<2, 2, 2, 2, 1, 2, 3>(c, p, p.RS, max_splits, &splits);
+        else rc = launch_wgrad<2, 2, 1, 2, 1, 2, 3>(c, p, p.RS, max_splits, &splits);
     } else {
-        if (p.R == 3 && p.S == 3 && p.stride == 1) rc = launch_wgrad<2, 2, 1, 1, 9, 2>(c, p, p.RS, max_splits, &splits);
-        else rc = launch_wgrad<2, 2, 1, 1, 9, 5>(c, p, p.RS, max_splits, &splits);
+        if (p.R == 3 && p.S == 3 && p.stride == 1) rc = launch_wgrad<2, 2, 1, 1, 9, 2, 4>(c, p, p.RS, max_splits, &splits);
+        else rc = launch_wgrad<2, 2, 1, 1, 9, 5, 3>(c, p, p.RS, max_splits, &splits);
     }
     if (rc != EOQ_OK) return rc;
     const size_t total = (size_t)d->K * rsc;
