@@ -1274,8 +1274,10 @@ int launch_igemm_u(eoq_ctx *c, const IgemmParams &p)
     return EOQ_OK;
 }
 
-// fewest 128 x 128 workgroups for which that tile is chosen over 128 x 64 (one per compute unit)
-constexpr long MIN_WGS_128 = 256;
+// fewest 128 x 128 workgroups for which that tile is chosen over 128 x 64: three quarters of the compute units (the
+// 7 x 7 layers with 512 outputs give 196; their reduction is long and bound by operand delivery, which the larger
+// tile halves per multiply-add -- measured 8 % faster on the 3x3, 4 % on the 1x1, than 392 workgroups of 128 x 64)
+constexpr long MIN_WGS_128 = 192;
 // 128-byte stages: input channels a multiple of 128, a reduction of at least this many 16-byte chunks, and at most
 // two 128 x 128 workgroups per compute unit
 constexpr int WIDE_MIN_NK16 = 64;
