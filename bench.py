@@ -30,7 +30,8 @@ TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "resnet50_b128_step_hbm_traffic
 # than live ones.  The timed loop therefore uses the largest rate that keeps the network alive over its steps; the
 # line reports what moved (weight codes, scalars), the pooled-feature mass at the end relative to the first step, and
 # the speculative backward-data calls that hit / had to be redone per step, so that the reader sees what was timed.
-LR = {"resnet20": (1, 4), "resnet18": (1, 8), "resnet34": (1, 8), "resnet50": (1, 6), "resnet110": (1, 4)}
+# (scanned with --lr-j: 30 steps, scalars move, pooled-feature mass stays above 0.3, device flags 0)
+LR = {"resnet20": (1, 4), "resnet18": (1, 6), "resnet34": (1, 6), "resnet50": (1, 6), "resnet110": (1, 5)}
 DEFAULT_BATCH = {"resnet20": 128, "resnet18": 64, "resnet34": 64, "resnet50": 128, "resnet110": 128}
 CPU_SAMPLE_BATCH = {"resnet20": 128, "resnet18": 32, "resnet34": 16, "resnet50": 16, "resnet110": 64}
 
