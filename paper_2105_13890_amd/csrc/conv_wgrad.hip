@@ -313,9 +313,10 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradParams p)
     wgrad_body<WK, WC, TK, TC, TAPS, U_LOADS, FULL, NS>(p);
 }
 
-// Occupancy decides more here than prefetch depth: with two stages of loads in flight instead of four, the single-tap
-// (1x1) kernels fit 152 registers (three workgroups per compute unit instead of two) and the nine-tap stride-1 kernel,
-// whose 9 x 16 accumulators alone take 144, fits 256 (two instead of one).
+// Launch bounds by family.  The single-tap (1x1) kernels need 118 registers and 48 KB of LDS (three stages of 16 KB):
+// three workgroups per compute unit.  The nine-tap stride-1 kernel, whose 9 x 16 accumulators alone take 144 registers,
+// fits 256 (two per compute unit, four stages of 12 KB each); the general nine-tap kernel (strided, 24 KB stages) runs
+// one workgroup per SIMD set with the full register file.
 template <int WK, int WC, int TK, int TC, int TAPS, int U_LOADS, bool FULL, int NS>
 __global__ __launch_bounds__(256, 2) void wgrad_occ2_kernel(WgradParams p)
 {
