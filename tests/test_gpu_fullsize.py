@@ -162,3 +162,33 @@ def test_full_batch_forward_equals_oracle_on_first_images(wl, batch):
         mc = g.slot_value(u.name + ".gmax")
         assert mc == 0 or 91 <= mc <= 127, (u.name, mc)
         assert int(u.w.abs().max().item()) <= 127
+
+
+@pytest.mark.parametrize("wl,batch", [("resnet18", 64), ("resnet50", 128)])
+def test_full_batch_inference_equals_oracle_on_sampled_images(wl, batch):
+    """The int8 inference chain at the size and in the launch configuration the benchmark times (two half-batch
+    chains, HIP graph replay): images sampled from both halves of the batch must match an oracle forward pass of
+    those images alone (no BatchNorm: an image's forward pass does not depend on the rest of the batch)."""
+    from paper_2105_13890_amd.net import FixupNet
+    cfg = si.WORKLOADS[wl]
+    x = si.batch_images(0, 0, batch, cfg["in_hw"])
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        g = FixupNet(cfg, batch, seed=0)
+        g.x_in.copy_(torch.from_numpy(x).cuda())
+        g.forward_inference()                            # eager once: one-time kernel attributes
+        torch.cuda.synchronize()
+        eager = g.gap.clone()
+        g.gap.zero_(); g.y_out.zero_()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr, stream=stream):
+            g.forward_inference()
+        gr.replay()
+        torch.cuda.synchronize()
+    assert torch.equal(g.gap, eager)
+    pick = [0, batch // 2 - 1, batch // 2, batch - 1]     # first and last image of each half-batch chain
+    o = OracleNet(cfg, len(pick), seed=0)
+    yo, gap = o.forward(x[pick])
+    assert np.array_equal(g.y_out[pick].cpu().numpy(), yo)
+    assert np.array_equal(g.gap[pick].cpu().numpy(), gap)
+    assert g.status() == 0
