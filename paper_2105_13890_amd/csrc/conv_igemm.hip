@@ -303,7 +303,15 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
     const unsigned long long ts0 = __builtin_amdgcn_s_memrealtime();
 #endif
     constexpr bool LEAN = BK == 64;                // compiled for 128 registers: epilogue side inputs two chunks ahead
-    if (EPI == EPI_D16 && pin.spec && spec_hit(pin.absmax, pin.spec_used)) return;     // the speculative launch was right
+    if (EPI == EPI_D16 && pin.spec && spec_hit(pin.absmax, pin.spec_used)) {           // the speculative launch was right
+#ifdef EOQ_TUNE
+        if (pin.dbg && threadIdx.x == 0 && blockIdx.x < 8192) {
+            unsigned long long *r = pin.dbg + 4 * (size_t)blockIdx.x;
+            r[0] = ts0; r[1] = r[2] = ts0; r[3] = __builtin_amdgcn_s_memrealtime();
+        }
+#endif
+        return;
+    }
     // (the recompute runs on the weight-gradient chain: see the note on wave priority in conv_wgrad.hip)
     if (EPI == EPI_RELU_BWD) __builtin_amdgcn_s_setprio(3);
     IgemmParams p = pin;           // uniform; patched below when the launch covers several classes
@@ -834,7 +842,7 @@ __device__ __forceinline__ void igemm_body(const IgemmParams &pin)
       }
     }
 #ifdef EOQ_TUNE
-    if (pin.dbg && tid == 0) {
+    if (pin.dbg && tid == 0 && blockIdx.x < 8192) {
         unsigned long long *r = pin.dbg + 4 * (size_t)blockIdx.x;
         r[0] = ts0; r[1] = ts1; r[2] = ts2; r[3] = __builtin_amdgcn_s_memrealtime();
     }
@@ -1356,6 +1364,7 @@ int fill_epi(const eoq_epilogue *e, EpiDev &o)
 
 #ifdef EOQ_TUNE
 extern "C" void eoq_tune_set_dbg(unsigned long long *buf) { g_tune_dbg = buf; g_tune_launch = 0; }
+extern "C" int eoq_tune_launch_index() { return g_tune_launch; }
 #endif
 
 // padded reduction length of the explicit im2col path

@@ -300,7 +300,7 @@ __device__ __forceinline__ void wgrad_body(const WgradParams &p)
             }
         }
 #ifdef EOQ_TUNE
-    if (p.dbg && tid == 0) {
+    if (p.dbg && tid == 0 && blockIdx.x < 8192) {
         unsigned long long *r = p.dbg + 4 * (size_t)blockIdx.x;
         r[0] = ts0; r[1] = ts1; r[2] = ts2; r[3] = __builtin_amdgcn_s_memrealtime();
     }
@@ -596,6 +596,7 @@ int wgrad_run(eoq_ctx *c, const eoq_conv_desc *d, const int8_t *e, const int8_t 
 
 #ifdef EOQ_TUNE
 extern "C" void eoq_tune_set_wdbg(unsigned long long *buf) { g_wtune_dbg = buf; g_wtune_launch = 0; }
+extern "C" int eoq_tune_wlaunch_index() { return g_wtune_launch; }
 #endif
 
 int wgrad_static_scratch_init(int device, void **ptr_out)
