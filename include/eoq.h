@@ -381,11 +381,17 @@ int eoq_broadcast_hw(eoq_ctx *ctx, const int8_t *codes, int32_t N, int32_t HW, i
  * feat = sum/(128*HW); logits = b + W feat (sequential fma, ascending feature); softmax with max
  * subtraction; loss = mean cross-entropy; d = (float)((W^T dlogits) / HW) per real activation;
  * then W -= lr*dW, b -= lr*db with lr = m * 2^-j from lr_slot.  ws: at least
- * eoq_head_workspace_bytes(N, F, J) bytes. */
+ * eoq_head_workspace_bytes(N, F, J) bytes; it keeps feat and dlogits of the call.
+ * lr_slot == NULL leaves W and b as they are: the update (the same two kernels, the same result) is then applied by
+ * eoq_head_update from the workspace the forward/backward call filled, on whatever stream that context owns -- nothing
+ * else in a training step reads the classifier, so a caller may run it beside the backward pass.  The caller orders it
+ * behind the eoq_head_fwd_bwd call and before the next one. */
 size_t eoq_head_workspace_bytes(int32_t N, int32_t F, int32_t J);
 int eoq_head_fwd_bwd(eoq_ctx *ctx, int32_t N, int32_t F, int32_t J, int32_t HW, const int32_t *gap_sum,
                      double *Wfc, double *bfc, const int32_t *labels, const int32_t *lr_slot, double *loss,
                      float *d, double *logits, void *ws, size_t ws_bytes);
+int eoq_head_update(eoq_ctx *ctx, int32_t N, int32_t F, int32_t J, double *Wfc, double *bfc, const int32_t *lr_slot,
+                    const void *ws, size_t ws_bytes);
 
 #ifdef __cplusplus
 }

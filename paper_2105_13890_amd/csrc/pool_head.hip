@@ -615,8 +615,7 @@ extern "C" int eoq_head_fwd_bwd(eoq_ctx *c, int32_t N, int32_t F, int32_t J, int
                                 double *Wfc, double *bfc, const int32_t *labels, const int32_t *lr_slot, double *loss,
                                 float *d, double *logits, void *ws, size_t ws_bytes)
 {
-    if (!c || N <= 0 || F <= 0 || J <= 0 || HW <= 0 || !gap_sum || !Wfc || !bfc || !labels || !lr_slot || !loss ||
-        !d || !logits)
+    if (!c || N <= 0 || F <= 0 || J <= 0 || HW <= 0 || !gap_sum || !Wfc || !bfc || !labels || !loss || !d || !logits)
         return EOQ_ERR_ARG;
     if (!ws || ws_bytes < eoq_head_workspace_bytes(N, F, J) || ((uintptr_t)ws & 7)) return EOQ_ERR_WORKSPACE;
     double *feat = (double *)ws;
@@ -638,11 +637,24 @@ extern "C" int eoq_head_fwd_bwd(eoq_ctx *c, int32_t N, int32_t F, int32_t J, int
     df.I = N; df.J = F; df.K = J; df.A = dl; df.sAi = J; df.sAk = 1; df.B = Wfc; df.sBj = 1; df.sBk = F;
     df.a_kfast = 1; df.b_kfast = 0; df.outf = d; df.so = F; df.denom = (double)HW;
     hipLaunchKernelGGL(head_gemm_kernel<HEAD_DFEAT>, dim3(tiles(F), tiles(N)), blk, 0, s, df);
+    EOQ_LAUNCH_CHECK();
+    // lr_slot == NULL: the classifier's own update is left to a later eoq_head_update on the same workspace
+    return lr_slot ? eoq_head_update(c, N, F, J, Wfc, bfc, lr_slot, ws, ws_bytes) : EOQ_OK;
+}
+
+extern "C" int eoq_head_update(eoq_ctx *c, int32_t N, int32_t F, int32_t J, double *Wfc, double *bfc,
+                               const int32_t *lr_slot, const void *ws, size_t ws_bytes)
+{
+    if (!c || N <= 0 || F <= 0 || J <= 0 || !Wfc || !bfc || !lr_slot) return EOQ_ERR_ARG;
+    if (!ws || ws_bytes < eoq_head_workspace_bytes(N, F, J) || ((uintptr_t)ws & 7)) return EOQ_ERR_WORKSPACE;
+    const double *feat = (const double *)ws;
+    const double *dl = feat + (size_t)N * F;
+    auto tiles = [](int v) { return (unsigned)((v + HG_T - 1) / HG_T); };
     HeadGemm up{};
     up.I = J; up.J = F; up.K = N; up.A = dl; up.sAi = 1; up.sAk = J; up.B = feat; up.sBj = 1; up.sBk = F;
     up.a_kfast = 0; up.b_kfast = 0; up.out = Wfc; up.so = F; up.lr_slot = lr_slot;
-    hipLaunchKernelGGL(head_gemm_kernel<HEAD_UPDATE>, dim3(tiles(F), tiles(J)), blk, 0, s, up);
-    hipLaunchKernelGGL(head_bias_update_kernel, dim3((J + 255) / 256), dim3(256), 0, s, N, J, dl, bfc, lr_slot);
+    hipLaunchKernelGGL(head_gemm_kernel<HEAD_UPDATE>, dim3(tiles(F), tiles(J)), dim3(256), 0, c->stream, up);
+    hipLaunchKernelGGL(head_bias_update_kernel, dim3((J + 255) / 256), dim3(256), 0, c->stream, N, J, dl, bfc, lr_slot);
     EOQ_LAUNCH_CHECK();
     return EOQ_OK;
 }

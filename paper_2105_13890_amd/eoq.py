@@ -25,7 +25,7 @@ EXPORTS = [
     "eoq_relu_bwd", "eoq_relu_bwd_recompute", "eoq_merge_absmax", "eoq_requant_epilogue", "eoq_update_int8", "eoq_grad_update", "eoq_update_scalars",
     "eoq_update_int8_sr", "eoq_grad_update_sr", "eoq_update_scalars_sr", "eoq_sr_next_step",
     "eoq_maxpool_fwd", "eoq_maxpool_bwd", "eoq_maxpool_bwd_sq", "eoq_gap_sum", "eoq_broadcast_hw", "eoq_head_workspace_bytes",
-    "eoq_head_fwd_bwd",
+    "eoq_head_fwd_bwd", "eoq_head_update",
 ]
 
 
@@ -109,6 +109,7 @@ def _load():
     lib.eoq_broadcast_hw.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.eoq_head_workspace_bytes.argtypes = [i32, i32, i32]
     lib.eoq_head_fwd_bwd.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz]
+    lib.eoq_head_update.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, sz]
     return lib
 
 
@@ -307,6 +308,10 @@ class Context:
         _check(_lib.eoq_head_fwd_bwd(self._h, N, F, J, HW, _ptr(gap_sum), _ptr(Wfc), _ptr(bfc), _ptr(labels),
                                      _ptr(lr_slot), _ptr(loss), _ptr(d), _ptr(logits), _ptr(ws), _nbytes(ws)),
                "eoq_head_fwd_bwd")
+
+    def head_update(self, N, F, J, Wfc, bfc, lr_slot, ws):
+        _check(_lib.eoq_head_update(self._h, N, F, J, _ptr(Wfc), _ptr(bfc), _ptr(lr_slot), _ptr(ws), _nbytes(ws)),
+               "eoq_head_update")
 
 
 def scalar_grad_table(entries, device) -> torch.Tensor:

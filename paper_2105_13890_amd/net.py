@@ -744,6 +744,11 @@ class FixupNet:
         s = self.stem
         d = s.desc
         masked = False
+        if self.overlap:
+            # The side stream has nothing to do while the main stream runs the last merge and the pool's backward
+            # pass: the float classifier's update goes there.  It is ordered behind the head's kernels through the
+            # side stream's waits for the main stream since, and before the next step's head by the join.
+            self.ctx_w.head_update(self.N, self.out_ch, self.classes, self.Wfc, self.bfc, self.lr, self.head_ws)
         if self.pool:
             n = int(np.prod(s.out_shape))
             e2 = self._acquire(bufs)
@@ -791,8 +796,10 @@ class FixupNet:
         self.forward()
         N, F, J = self.N, self.out_ch, self.classes
         hw = self.out_hw * self.out_hw
-        c.head_fwd_bwd(N, F, J, hw, self.gap, self.Wfc, self.bfc, self.labels, self.lr, self.loss, self.d32,
-                       self.logits, self.head_ws)
+        # the classifier's own update feeds nothing in this step: with two streams it runs on the side stream at the
+        # tail of the backward pass (see _backward_stem), not between the forward and the backward pass
+        c.head_fwd_bwd(N, F, J, hw, self.gap, self.Wfc, self.bfc, self.labels, None if self.overlap else self.lr,
+                       self.loss, self.d32, self.logits, self.head_ws)
         c.quantize(self.d32, eoq.SQ, 0, self.head_codes, self.s32("head.E"))     # Q_e on the head's error
         bufs = deque(self.ebuf)
         e = self._acquire(bufs)

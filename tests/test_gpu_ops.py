@@ -665,3 +665,28 @@ def test_empty_inputs_and_rejected_arguments(ctx):
     # the context still works after the refusals
     ctx.conv_fwd(desc_of(d), u, w, acc=acc, ws=ws_for(d, eoq.OP_CONV_FWD))
     assert np.array_equal(host(acc), oo.conv_fwd(d, host(u), host(w)))
+
+
+def test_head_update_as_a_call_of_its_own(ctx):
+    """eoq_head_fwd_bwd without a learning-rate slot leaves the classifier alone; eoq_head_update then applies the
+    same update from the workspace -- together they equal the single call, bit for bit."""
+    N, F, J, HW = 19, 200, 37, 49
+    gap = (si.words(9, "gap", N * F) % np.uint64(127 * HW)).astype(np.int32).reshape(N, F)
+    Wfc = si.standard_normal(9, "Wfc", (J, F)) * 0.2
+    bfc = si.standard_normal(9, "bfc", (J,)) * 0.1
+    lab = si.labels(9, "lab", N, J)
+    lr = dev(np.array([3, 5], dtype=np.int32))
+    outs = []
+    for split in (False, True):
+        Wd, bd = dev(Wfc), dev(bfc)
+        loss, d, logits = zeros((1,), torch.float64), zeros((N, F), torch.float32), zeros((N, J), torch.float64)
+        ws = zeros((ctx.head_workspace_bytes(N, F, J) // 8 + 1,), torch.float64)
+        ctx.head_fwd_bwd(N, F, J, HW, dev(gap), Wd, bd, dev(lab), None if split else lr, loss, d, logits, ws)
+        if split:
+            assert np.array_equal(host(Wd), Wfc) and np.array_equal(host(bd), bfc)
+            ctx.head_update(N, F, J, Wd, bd, lr, ws)
+        outs.append([host(t).copy() for t in (Wd, bd, loss, d, logits)])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    loss_o, d_o, dW_o, db_o, logits_o = oo.head(gap, Wfc, bfc, lab, HW)
+    assert np.array_equal(outs[1][0], Wfc - 3 * 2.0 ** -5 * dW_o)
